@@ -1,0 +1,277 @@
+"""CPU oracle for the ParallelComp chunked-prefill / parallel-attention path.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain fp64 statement of what the path
+computes, written from the paper's method section (3.1).  Only the tests, the smoke check
+and the benchmark's CPU-baseline leg may import it; the product path never does, and this
+module imports nothing from the product package.  It shares no code with the HIP kernels.
+
+Every function works on float64 numpy arrays (bf16 inputs are widened exactly by the caller)
+and follows the paper's order of steps:
+
+  rope                  position reuse: positions restart in every chunk (sec. 3.1, "Parallel
+                        attention"; related work on reusing position encodings)
+  local_attention       Eq. 1-2: A = Softmax(Q K^T / sqrt(d)), F = A V, inside one chunk
+  query_scores          Eq. 5-6: cumulative query->key attention, summed over voting rows
+  select_chunks         Eq. 3-4 mechanics: fixed number of best chunks (see readings below)
+  select_tokens         Eq. 7: retained token set per head per chunk
+  gather_kv             Eq. 7: compressed KV cache K_r = K_x[.], V_r = V_x[.]
+  global_attention_*    Eq. 9-11: the query attends over [K^1 .. K^C, K^q]
+
+Readings of the paper taken here (the paper is silent or ambiguous on each):
+  * Eq. 1 carries a causal mask (decoder LLMs): key j is visible to row r iff j <= r.
+  * The scale is 1/sqrt(head_dim) unless the caller passes another.
+  * RoPE pairs dimension i with i + D/2 ("rotate-half"), theta_i = base^(-2i/D).
+  * Each chunk sequence is [w context rows ; w_q query rows] under one causal mask.
+  * A(i, j) in Eq. 5 is the post-softmax probability of row i of Eq. 1, normalised over the
+    row's whole causal key set (chunk keys and the query's own keys).
+  * Only the last obs_window query rows vote (the appendix's "last 8 tokens"; a parameter).
+  * Scores cover chunk keys j < w only; query keys are always kept (Eq. 9 keeps K^q whole).
+  * The kept set of Eq. 7 is the top-k by score; ties go to the lower index.
+  * GQA: a KV head's score is the sum over the query heads that read it.
+  * Chunk criterion: the query's attention mass on the chunk (sum of its token scores),
+    larger is better.  This replaces Eq. 3's self-information, which needs a language-model
+    head and trained weights: selection against the paper's own criterion is PARITY UNPINNED.
+  * In global attention keys keep their chunk-local rotation and query row t sits at w + t.
+
+Pins (tests/test_oracle_pins.py): brute-force softmax in pure Python loops; closed forms
+(K = 0, V = 1, position 0, norm preservation, shift invariance); a library attention routine
+for one chunk without eviction; one softmax over concatenated keys versus the logsumexp merge;
+planted relevance with selections known by construction; gather as a pure permutation.
+"""
+import numpy as np
+
+
+# --------------------------------------------------------------------------- RoPE
+def rope_angles(positions, head_dim, base):
+    """angle[p, i] = position_p * theta_i, theta_i = base^(-2 i / D), i in [0, D/2)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    theta = np.power(np.float64(base), -2.0 * i / np.float64(head_dim))
+    return np.asarray(positions, dtype=np.float64)[:, None] * theta[None, :]
+
+
+def rope(x, positions, base):
+    """Rotate x [rows, heads, D] at the given integer positions (one per row).
+
+    Pair (i, i + D/2) is rotated by angle position * theta_i.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    half = x.shape[-1] // 2
+    ang = rope_angles(positions, x.shape[-1], base)[:, None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+# --------------------------------------------------------------------------- Eq. 1-2
+def local_attention(q_rot, k_rot, v, scale=None, rows=None, return_probs=False):
+    """Causal softmax attention inside one chunk sequence (Eq. 1-2).
+
+    q_rot [L, H_q, D], k_rot [L, H_kv, D], v [L, H_kv, D] (q, k already rotated).
+    Query head h reads KV head h // (H_q / H_kv).  rows: which rows to compute (default all).
+    Returns o [n_rows, H_q, D], lse [n_rows, H_q] and, if asked, P [n_rows, H_q, L].
+    """
+    L, Hq, D = q_rot.shape
+    Hkv = k_rot.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    rows = np.arange(L) if rows is None else np.asarray(rows, dtype=np.int64)
+    n = rows.shape[0]
+    o = np.zeros((n, Hq, D), dtype=np.float64)
+    lse = np.zeros((n, Hq), dtype=np.float64)
+    P_all = np.zeros((n, Hq, L), dtype=np.float64) if return_probs else None
+    visible = np.arange(L)[None, :] <= rows[:, None]          # j <= r
+    for h in range(Hq):
+        g = h // G
+        s = (q_rot[rows, h, :] @ k_rot[:, g, :].T) * scale       # [n, L]
+        s = np.where(visible, s, -np.inf)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        z = e.sum(axis=1, keepdims=True)
+        P = e / z
+        o[:, h, :] = P @ v[:, g, :]
+        lse[:, h] = (m + np.log(z))[:, 0]
+        if return_probs:
+            P_all[:, h, :] = P
+    return (o, lse, P_all) if return_probs else (o, lse)
+
+
+# --------------------------------------------------------------------------- Eq. 5-6
+def query_scores(q_rot, k_rot, chunk_len, obs_window, n_kv_heads, scale=None):
+    """Cumulative attention of the voting query rows to every chunk key (Eq. 5-6).
+
+    Voting rows R = the last obs_window rows of the sequence.  Returns
+    tok_score [H_kv, w] = sum over the group's query heads and over R of P[r, j], j < w,
+    and chunk_score = sum of tok_score (the query's attention mass on the chunk).
+    """
+    L, Hq, D = q_rot.shape
+    G = Hq // n_kv_heads
+    R = np.arange(L - obs_window, L)
+    v_dummy = np.zeros((L, n_kv_heads, 1), dtype=np.float64)
+    _, _, P = local_attention(q_rot, k_rot, v_dummy, scale=scale, rows=R, return_probs=True)
+    col = P.sum(axis=0)                                          # [H_q, L]
+    tok = col.reshape(n_kv_heads, G, L).sum(axis=1)[:, :chunk_len]
+    return tok, tok.sum()
+
+
+# --------------------------------------------------------------------------- selection
+def _top_k_lower_index_wins(score, k):
+    """Indices of the k largest scores under the total order (score desc, index asc)."""
+    score = np.asarray(score, dtype=np.float64)
+    order = np.lexsort((np.arange(score.shape[0]), -score))      # primary: -score, then index
+    return order[:k]
+
+
+def select_chunks(chunk_score, k_c):
+    """Kept chunk ids in rank order (best first); ties go to the lower id (Eq. 3-4 mechanics)."""
+    return _top_k_lower_index_wins(chunk_score, k_c).astype(np.int32)
+
+
+def select_tokens(tok_score, k_t):
+    """Kept token ids per row of tok_score [..., w], ascending; ties go to the lower id (Eq. 7)."""
+    tok_score = np.asarray(tok_score, dtype=np.float64)
+    flat = tok_score.reshape(-1, tok_score.shape[-1])
+    out = np.empty((flat.shape[0], k_t), dtype=np.int32)
+    for i in range(flat.shape[0]):
+        out[i] = np.sort(_top_k_lower_index_wins(flat[i], k_t))
+    return out.reshape(tok_score.shape[:-1] + (k_t,))
+
+
+# --------------------------------------------------------------------------- Eq. 7
+def gather_kv(k_src, v_src, chunk_idx, tok_idx):
+    """Compressed cache: dst[s, g, t, :] = src[chunk_idx[s], tok_idx[s, g, t], g, :].
+
+    k_src, v_src [C, rows, H_kv, D] (any dtype: this is a pure copy);
+    chunk_idx [n_sel]; tok_idx [n_sel, H_kv, k_t].  Returns [n_sel, H_kv, k_t, D] each.
+    """
+    n_sel, Hkv, kt = tok_idx.shape
+    kd = np.empty((n_sel, Hkv, kt) + k_src.shape[3:], dtype=k_src.dtype)
+    vd = np.empty_like(kd)
+    for s in range(n_sel):
+        for g in range(Hkv):
+            kd[s, g] = k_src[chunk_idx[s], tok_idx[s, g], g]
+            vd[s, g] = v_src[chunk_idx[s], tok_idx[s, g], g]
+    return kd, vd
+
+
+# --------------------------------------------------------------------------- Eq. 9-11
+def _masked_softmax_rows(s, visible=None):
+    """Row softmax of a logit matrix; returns (P, lse).  visible: boolean mask or None."""
+    if visible is not None:
+        s = np.where(visible, s, -np.inf)
+    m = s.max(axis=1, keepdims=True)
+    e = np.exp(s - m)
+    z = e.sum(axis=1, keepdims=True)
+    return e / z, (m + np.log(z))[:, 0]
+
+
+def global_attention_concat(q_rot, kc, vc, k_self=None, v_self=None, seg_len=None, scale=None):
+    """Eq. 9-11 as printed: one softmax over the concatenation [K^1 .. K^S, K^q].
+
+    q_rot [n_q, H_q, D] rotated query rows; kc, vc [S, H_kv, k_t, D] compressed segments
+    (keys rotated); optional causal self segment k_self, v_self [n_q, H_kv, D]: query row t
+    sees self keys 0..t.  seg_len [S]: valid rows per segment (default all k_t).
+    Returns o [n_q, H_q, D], lse [n_q, H_q].
+    """
+    nq, Hq, D = q_rot.shape
+    S, Hkv, kt, _ = kc.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    seg_len = np.full(S, kt, dtype=np.int64) if seg_len is None else np.asarray(seg_len)
+    o = np.zeros((nq, Hq, D))
+    lse = np.zeros((nq, Hq))
+    n_ctx = int(seg_len.sum())
+    for h in range(Hq):
+        g = h // G
+        K = [kc[s, g, :seg_len[s]] for s in range(S)]
+        V = [vc[s, g, :seg_len[s]] for s in range(S)]
+        visible = np.ones((nq, n_ctx), dtype=bool)
+        if k_self is not None:
+            K.append(k_self[:, g])
+            V.append(v_self[:, g])
+            causal = np.arange(nq)[None, :] <= np.arange(nq)[:, None]
+            visible = np.concatenate([visible, causal], axis=1)
+        K = np.concatenate(K, axis=0)
+        V = np.concatenate(V, axis=0)
+        P, lse[:, h] = _masked_softmax_rows((q_rot[:, h] @ K.T) * scale, visible)
+        o[:, h] = P @ V
+    return o, lse
+
+
+def lse_merge(o_parts, lse_parts):
+    """Exact merge of per-segment softmax partials (leading axis = segment):
+    LSE = log sum_s exp(lse_s), o = sum_s exp(lse_s - LSE) o_s.  A segment with no visible key
+    carries lse = -inf and weight 0."""
+    lse_parts = np.asarray(lse_parts, dtype=np.float64)
+    m = lse_parts.max(axis=0)
+    wgt = np.exp(lse_parts - m)
+    z = wgt.sum(axis=0)
+    o = (wgt[..., None] * np.asarray(o_parts)).sum(axis=0) / z[..., None]
+    return o, m + np.log(z)
+
+
+def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=None, scale=None):
+    """Same quantity as global_attention_concat, computed the "parallel" way: an independent
+    softmax per segment (and a causal one over the self segment), merged by lse_merge."""
+    nq, Hq, D = q_rot.shape
+    S, Hkv, kt, _ = kc.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    seg_len = np.full(S, kt, dtype=np.int64) if seg_len is None else np.asarray(seg_len)
+    n_parts = S + (1 if k_self is not None else 0)
+    o_p = np.zeros((n_parts, nq, Hq, D))
+    l_p = np.full((n_parts, nq, Hq), -np.inf)
+    causal = np.arange(nq)[None, :] <= np.arange(nq)[:, None]
+    for h in range(Hq):
+        g = h // G
+        for s in range(S):
+            if seg_len[s] > 0:
+                Ks, Vs = kc[s, g, :seg_len[s]], vc[s, g, :seg_len[s]]
+                P, l_p[s, :, h] = _masked_softmax_rows((q_rot[:, h] @ Ks.T) * scale)
+                o_p[s, :, h] = P @ Vs
+        if k_self is not None:
+            P, l_p[S, :, h] = _masked_softmax_rows((q_rot[:, h] @ k_self[:, g].T) * scale, causal)
+            o_p[S, :, h] = P @ v_self[:, g]
+    return lse_merge(o_p, l_p)
+
+
+# --------------------------------------------------------------------------- the whole layer
+def parallelcomp_layer(q, k, v, chunk_len, obs_window, keep_chunks, keep_tokens, rope_base,
+                       scale=None, attn_rows=None):
+    """One layer of the method on C chunk sequences, in the paper's order of steps.
+
+    q [C, L, H_q, D], k, v [C, L, H_kv, D] in float64, before RoPE; every chunk's last
+    L - chunk_len rows are the query rows.  attn_rows: rows of every chunk for which the local
+    attention output is computed (default all).  Returns a dict with every intermediate result.
+    """
+    C, L, Hq, D = q.shape
+    Hkv = k.shape[2]
+    w = chunk_len
+    wq = L - w
+    pos = np.arange(L)
+    rows = np.arange(L) if attn_rows is None else np.asarray(attn_rows)
+    out = {"o": np.zeros((C, rows.shape[0], Hq, D)), "lse": np.zeros((C, rows.shape[0], Hq)),
+           "k_rope": np.zeros_like(k), "tok_score": np.zeros((C, Hkv, w)),
+           "chunk_score": np.zeros(C), "attn_rows": rows}
+    q_rot_query = None
+    for c in range(C):
+        q_rot = rope(q[c], pos, rope_base)
+        k_rot = rope(k[c], pos, rope_base)
+        out["k_rope"][c] = k_rot
+        out["o"][c], out["lse"][c] = local_attention(q_rot, k_rot, v[c], scale, rows)
+        out["tok_score"][c], out["chunk_score"][c] = query_scores(q_rot, k_rot, w, obs_window,
+                                                                  Hkv, scale)
+        if c == 0:
+            q_rot_query = q_rot[w:]
+    if keep_chunks <= 0:
+        return out
+    chunk_idx = select_chunks(out["chunk_score"], keep_chunks)
+    tok_idx = select_tokens(out["tok_score"][chunk_idx], keep_tokens)
+    kc, vc = gather_kv(out["k_rope"], v, chunk_idx, tok_idx)
+    k_self, v_self = out["k_rope"][0, w:], v[0, w:]
+    og, lg = global_attention_merged(q_rot_query, kc, vc, k_self, v_self, scale=scale)
+    out.update({"chunk_idx": chunk_idx, "tok_idx": tok_idx, "kc": kc, "vc": vc,
+                "global_o": og, "global_lse": lg, "q_rot_query": q_rot_query})
+    return out

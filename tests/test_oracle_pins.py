@@ -1,0 +1,415 @@
+"""Pins of the CPU oracle against things other than itself: brute force in pure Python loops,
+closed forms, a library attention routine, textbook identities and planted inputs whose
+selections are known by construction.  Each test names the passage of the paper it pins."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import (CFG0, CFG0U, CFG1_SMALL, CFG2_SMALL, prefill_inputs, bf16_bits_to_f64,
+                       relevant_chunks, f32_to_bf16_bits, bf16_bits_to_f32)
+
+
+def _rng(seed):
+    return np.random.default_rng([7, seed])
+
+
+# ------------------------------------------------------------------ RoPE (position reuse, sec. 3.1)
+def test_rope_position_zero_is_identity():
+    x = _rng(0).standard_normal((3, 2, 8))
+    np.testing.assert_array_equal(oracle.rope(x, np.zeros(3, dtype=np.int64), 1e4), x)
+
+
+def test_rope_pairing_and_sign_closed_form():
+    # D = 4: pairs are (0, 2) with theta_0 = 1 and (1, 3) with theta_1 = base^(-1/2).
+    base, p = 1.0e4, 3
+    th1 = 1.0 / math.sqrt(base)
+    e0 = np.zeros((1, 1, 4)); e0[0, 0, 0] = 1.0
+    e1 = np.zeros((1, 1, 4)); e1[0, 0, 1] = 1.0
+    e2 = np.zeros((1, 1, 4)); e2[0, 0, 2] = 1.0
+    r0 = oracle.rope(e0, [p], base)[0, 0]
+    r1 = oracle.rope(e1, [p], base)[0, 0]
+    r2 = oracle.rope(e2, [p], base)[0, 0]
+    np.testing.assert_allclose(r0, [math.cos(p), 0, math.sin(p), 0], atol=1e-15)
+    np.testing.assert_allclose(r1, [0, math.cos(p * th1), 0, math.sin(p * th1)], atol=1e-15)
+    np.testing.assert_allclose(r2, [-math.sin(p), 0, math.cos(p), 0], atol=1e-15)
+
+
+def test_rope_frequency_formula():
+    # theta_i = base^(-2i/D): D = 128, base 5e5 -> theta_32 = base^(-1/2).
+    ang = oracle.rope_angles([1, 10], 128, 5.0e5)
+    assert ang.shape == (2, 64)
+    np.testing.assert_allclose(ang[0, 0], 1.0, rtol=0, atol=0)
+    np.testing.assert_allclose(ang[0, 32], 1.0 / math.sqrt(5.0e5), rtol=1e-14)
+    np.testing.assert_allclose(ang[1, 63], 10.0 * 5.0e5 ** (-126.0 / 128.0), rtol=1e-14)
+
+
+def test_rope_preserves_norm_and_inner_product_depends_on_distance_only():
+    r = _rng(1)
+    x = r.standard_normal((5, 3, 16))
+    pos = np.array([0, 1, 7, 100, 4095])
+    y = oracle.rope(x, pos, 1e4)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-13)
+    a = r.standard_normal((1, 1, 16)); b = r.standard_normal((1, 1, 16))
+    d1 = (oracle.rope(a, [9], 1e4) * oracle.rope(b, [4], 1e4)).sum()
+    d2 = (oracle.rope(a, [1009], 1e4) * oracle.rope(b, [1004], 1e4)).sum()
+    np.testing.assert_allclose(d1, d2, rtol=1e-10)
+
+
+# ------------------------------------------------------------------ Eq. 1-2 local attention
+def _brute_force_causal(q, k, v, scale):
+    """Pure Python loops, explicit probabilities, no running max."""
+    L, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    o = np.zeros((L, Hq, v.shape[2]))
+    lse = np.zeros((L, Hq))
+    P = np.zeros((L, Hq, L))
+    for r in range(L):
+        for h in range(Hq):
+            g = h // G
+            w = []
+            for j in range(r + 1):
+                dot = 0.0
+                for d in range(D):
+                    dot += q[r, h, d] * k[j, g, d]
+                w.append(math.exp(dot * scale))
+            z = sum(w)
+            lse[r, h] = math.log(z)
+            for j in range(r + 1):
+                P[r, h, j] = w[j] / z
+                for d in range(v.shape[2]):
+                    o[r, h, d] += P[r, h, j] * v[j, g, d]
+    return o, lse, P
+
+
+def test_local_attention_vs_brute_force_gqa():
+    r = _rng(2)
+    L, Hq, Hkv, D = 11, 4, 2, 6
+    q, k, v = r.standard_normal((L, Hq, D)), r.standard_normal((L, Hkv, D)), r.standard_normal((L, Hkv, D))
+    scale = 0.37
+    o, lse, P = oracle.local_attention(q, k, v, scale=scale, return_probs=True)
+    ob, lb, Pb = _brute_force_causal(q, k, v, scale)
+    np.testing.assert_allclose(o, ob, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, lb, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(P, Pb, rtol=1e-12, atol=1e-15)
+    # a subset of rows gives the same rows
+    rows = np.array([0, 5, 10])
+    o2, l2 = oracle.local_attention(q, k, v, scale=scale, rows=rows)
+    np.testing.assert_allclose(o2, ob[rows], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(l2, lb[rows], rtol=1e-12, atol=1e-13)
+
+
+def test_local_attention_default_scale_is_inverse_sqrt_head_dim():
+    r = _rng(3)
+    q, k, v = r.standard_normal((5, 1, 16)), r.standard_normal((5, 1, 16)), r.standard_normal((5, 1, 16))
+    o1, l1 = oracle.local_attention(q, k, v)
+    ob, lb, _ = _brute_force_causal(q, k, v, 0.25)
+    np.testing.assert_allclose(o1, ob, rtol=1e-12)
+    np.testing.assert_allclose(l1, lb, rtol=1e-12)
+
+
+def test_local_attention_closed_forms():
+    r = _rng(4)
+    L, H, D = 9, 2, 4
+    q = r.standard_normal((L, H, D))
+    k = r.standard_normal((L, H, D))
+    v = r.standard_normal((L, H, D))
+    # rows of P sum to one and V == 1 gives o == 1
+    o, _, P = oracle.local_attention(q, k, np.ones_like(v), return_probs=True)
+    np.testing.assert_allclose(P.sum(-1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(o, 1.0, rtol=1e-14)
+    assert np.all(np.triu(np.ones((L, L)), 1)[:, None, :].repeat(H, 1) * P == 0.0)   # causal
+    # K == 0: uniform over the causal prefix
+    o, lse = oracle.local_attention(q, np.zeros_like(k), v)
+    for row in range(L):
+        np.testing.assert_allclose(o[row], v[:row + 1].mean(axis=0), rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(lse[row], math.log(row + 1), rtol=1e-13, atol=1e-15)
+
+
+def test_invariant_one_chunk_no_eviction_is_standard_causal_rope_attention():
+    """Invariant A: C = 1 without eviction is ordinary causal RoPE attention; checked against
+    torch's scaled_dot_product_attention (a library routine) in fp64."""
+    r = _rng(5)
+    L, Hq, Hkv, D, base = 70, 4, 2, 16, 1e4
+    q, k, v = r.standard_normal((1, L, Hq, D)), r.standard_normal((1, L, Hkv, D)), r.standard_normal((1, L, Hkv, D))
+    out = oracle.parallelcomp_layer(q, k, v, chunk_len=L - 6, obs_window=3, keep_chunks=0,
+                                    keep_tokens=0, rope_base=base)
+    # library route: rotate with complex multiplication (independent of the oracle's RoPE code)
+    def rot(x):
+        half = D // 2
+        th = base ** (-2.0 * np.arange(half) / D)
+        z = (x[..., :half] + 1j * x[..., half:]) * np.exp(1j * np.arange(L)[:, None, None] * th)
+        return np.concatenate([z.real, z.imag], axis=-1)
+    tq = torch.from_numpy(rot(q[0])).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(rot(k[0])).permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    tv = torch.from_numpy(v[0]).permute(1, 0, 2)[None].repeat_interleave(Hq // Hkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    ref = ref[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(out["o"][0], ref, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(out["k_rope"][0], rot(k[0]), rtol=1e-12, atol=1e-14)
+
+
+def test_local_attention_shift_invariance_of_positions():
+    r = _rng(6)
+    L = 12
+    q, k, v = r.standard_normal((L, 2, 8)), r.standard_normal((L, 2, 8)), r.standard_normal((L, 2, 8))
+    pos = np.arange(L)
+    o1, l1 = oracle.local_attention(oracle.rope(q, pos, 1e4), oracle.rope(k, pos, 1e4), v)
+    o2, l2 = oracle.local_attention(oracle.rope(q, pos + 500, 1e4), oracle.rope(k, pos + 500, 1e4), v)
+    np.testing.assert_allclose(o1, o2, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(l1, l2, rtol=1e-9, atol=1e-11)
+
+
+# ------------------------------------------------------------------ Eq. 5-6 cumulative scores
+def test_query_scores_vs_brute_force_and_mass_conservation():
+    r = _rng(7)
+    L, w, Hq, Hkv, D, wobs = 14, 9, 4, 2, 6, 3
+    q, k = r.standard_normal((L, Hq, D)), r.standard_normal((L, Hkv, D))
+    scale = 0.41
+    tok, chunk = oracle.query_scores(q, k, w, wobs, Hkv, scale=scale)
+    _, _, P = _brute_force_causal(q, k, np.zeros((L, Hkv, 1)), scale)
+    ref = np.zeros((Hkv, w))
+    for h in range(Hq):
+        for row in range(L - wobs, L):
+            for j in range(w):
+                ref[h // (Hq // Hkv), j] += P[row, h, j]
+    np.testing.assert_allclose(tok, ref, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(chunk, ref.sum(), rtol=1e-12)
+    # every voting row's probabilities sum to 1 over ALL keys: chunk mass + self mass = H_q * w_obs
+    self_mass = P[L - wobs:, :, w:].sum()
+    np.testing.assert_allclose(chunk + self_mass, Hq * wobs, rtol=1e-12)
+    assert chunk < Hq * wobs
+
+
+def test_query_scores_closed_form_zero_keys_and_single_voter():
+    r = _rng(8)
+    L, w, Hq, Hkv, D, wobs = 20, 13, 6, 2, 4, 5
+    q = r.standard_normal((L, Hq, D))
+    tok, chunk = oracle.query_scores(q, np.zeros((L, Hkv, D)), w, wobs, Hkv)
+    expect = (Hq // Hkv) * sum(1.0 / (row + 1) for row in range(L - wobs, L))
+    np.testing.assert_allclose(tok, expect, rtol=1e-13)
+    np.testing.assert_allclose(chunk, expect * Hkv * w, rtol=1e-13)
+    # w_obs = 1, MHA: the score is the last row of P
+    k = r.standard_normal((L, Hq, D))
+    tok1, _ = oracle.query_scores(q, k, w, 1, Hq, scale=0.5)
+    _, _, P = _brute_force_causal(q, k, np.zeros((L, Hq, 1)), 0.5)
+    np.testing.assert_allclose(tok1, P[L - 1, :, :w], rtol=1e-12)
+
+
+# ------------------------------------------------------------------ Eq. 3-4 / Eq. 7 selection
+def _brute_topk(score, k):
+    return sorted(range(len(score)), key=lambda i: (-score[i], i))[:k]
+
+
+def test_select_chunks_ties_rank_order_and_bruteforce():
+    s = np.array([0.5, 2.0, 2.0, -1.0, 2.0, 0.5])
+    np.testing.assert_array_equal(oracle.select_chunks(s, 2), [1, 2])
+    np.testing.assert_array_equal(oracle.select_chunks(s, 4), [1, 2, 4, 0])
+    np.testing.assert_array_equal(oracle.select_chunks(s, 6), [1, 2, 4, 0, 5, 3])
+    r = _rng(9)
+    for n in (1, 2, 7, 33):
+        sc = np.round(r.standard_normal(n), 1)           # many ties
+        for k in {1, n // 2 or 1, n}:
+            np.testing.assert_array_equal(oracle.select_chunks(sc, k), _brute_topk(list(sc), k))
+
+
+def test_select_tokens_ties_ascending_identity_and_permutation():
+    s = np.array([[1.0, 3.0, 3.0, 0.0, 3.0, 1.0], [0.0, 0.0, 0.0, 0.0, 0.0, 0.0]])
+    out = oracle.select_tokens(s, 2)
+    np.testing.assert_array_equal(out, [[1, 2], [0, 1]])
+    np.testing.assert_array_equal(oracle.select_tokens(s, 6), [list(range(6))] * 2)   # k = n
+    r = _rng(10)
+    sc = np.round(r.random((3, 4, 50)), 2)
+    out = oracle.select_tokens(sc, 17)
+    assert out.shape == (3, 4, 17) and out.dtype == np.int32
+    for a in range(3):
+        for b in range(4):
+            assert list(out[a, b]) == sorted(_brute_topk(list(sc[a, b]), 17))
+    # distinct scores: permuting the input permutes the answer
+    x = r.permutation(40).astype(np.float64)
+    perm = r.permutation(40)
+    base = set(oracle.select_tokens(x[None], 9)[0])
+    moved = set(perm[i] for i in oracle.select_tokens(x[perm][None], 9)[0])
+    assert base == moved
+
+
+# ------------------------------------------------------------------ Eq. 7 gather
+def test_gather_is_a_pure_permutation():
+    r = _rng(11)
+    C, rows, H, D = 3, 10, 2, 4
+    k = r.integers(0, 2 ** 16, size=(C, rows, H, D)).astype(np.uint16)
+    v = r.integers(0, 2 ** 16, size=(C, rows, H, D)).astype(np.uint16)
+    chunk_idx = np.array([2, 0])
+    tok_idx = np.stack([np.stack([np.sort(r.choice(rows, 6, replace=False)) for _ in range(H)])
+                        for _ in range(2)]).astype(np.int32)
+    kd, vd = oracle.gather_kv(k, v, chunk_idx, tok_idx)
+    assert kd.dtype == np.uint16 and kd.shape == (2, H, 6, D)
+    for s in range(2):
+        for g in range(H):
+            for t in range(6):
+                assert np.array_equal(kd[s, g, t], k[chunk_idx[s], tok_idx[s, g, t], g])
+                assert np.array_equal(vd[s, g, t], v[chunk_idx[s], tok_idx[s, g, t], g])
+    # k = rows with identity indices is the transpose [C, H, rows, D] of the source
+    ident = np.broadcast_to(np.arange(rows, dtype=np.int32), (C, H, rows)).copy()
+    kd, _ = oracle.gather_kv(k, v, np.arange(C), ident)
+    np.testing.assert_array_equal(kd, k.transpose(0, 2, 1, 3))
+
+
+# ------------------------------------------------------------------ Eq. 9-11 global attention
+def test_invariant_merge_equals_one_softmax_over_concatenation():
+    """Invariant B: per-segment softmaxes merged by logsumexp equal one softmax over all keys;
+    the concatenated form is itself checked against torch's attention with an explicit mask."""
+    r = _rng(12)
+    nq, Hq, Hkv, D, S, kt = 7, 4, 2, 8, 3, 11
+    q = r.standard_normal((nq, Hq, D))
+    kc, vc = r.standard_normal((S, Hkv, kt, D)), r.standard_normal((S, Hkv, kt, D))
+    ks, vs = r.standard_normal((nq, Hkv, D)), r.standard_normal((nq, Hkv, D))
+    seg_len = np.array([11, 4, 9])
+    o1, l1 = oracle.global_attention_concat(q, kc, vc, ks, vs, seg_len=seg_len, scale=0.3)
+    o2, l2 = oracle.global_attention_merged(q, kc, vc, ks, vs, seg_len=seg_len, scale=0.3)
+    np.testing.assert_allclose(o1, o2, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(l1, l2, rtol=1e-12, atol=1e-14)
+    G = Hq // Hkv
+    for h in range(Hq):
+        g = h // G
+        K = np.concatenate([kc[s, g, :seg_len[s]] for s in range(S)] + [ks[:, g]])
+        V = np.concatenate([vc[s, g, :seg_len[s]] for s in range(S)] + [vs[:, g]])
+        n_ctx = int(seg_len.sum())
+        mask = np.ones((nq, n_ctx + nq), dtype=bool)
+        mask[:, n_ctx:] = np.tril(np.ones((nq, nq), dtype=bool))
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q[:, h])[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+            attn_mask=torch.from_numpy(mask)[None], scale=0.3)[0].numpy()
+        np.testing.assert_allclose(o1[:, h], ref, rtol=1e-10, atol=1e-12)
+
+
+def test_merge_invariant_to_segment_order_and_splitting():
+    r = _rng(13)
+    nq, H, D, S, kt = 3, 2, 4, 4, 6
+    q = r.standard_normal((nq, H, D))
+    kc, vc = r.standard_normal((S, H, kt, D)), r.standard_normal((S, H, kt, D))
+    o, l = oracle.global_attention_merged(q, kc, vc)
+    perm = np.array([2, 0, 3, 1])
+    o2, l2 = oracle.global_attention_merged(q, kc[perm], vc[perm])
+    np.testing.assert_allclose(o, o2, rtol=1e-12)
+    np.testing.assert_allclose(l, l2, rtol=1e-12)
+    # split every segment in two halves: 2S segments of k_t/2
+    kc3 = kc.reshape(S, H, 2, kt // 2, D).transpose(0, 2, 1, 3, 4).reshape(2 * S, H, kt // 2, D)
+    vc3 = vc.reshape(S, H, 2, kt // 2, D).transpose(0, 2, 1, 3, 4).reshape(2 * S, H, kt // 2, D)
+    o3, l3 = oracle.global_attention_merged(q, kc3, vc3)
+    np.testing.assert_allclose(o, o3, rtol=1e-12)
+    np.testing.assert_allclose(l, l3, rtol=1e-12)
+    # one segment, no self segment: plain softmax attention
+    o4, l4 = oracle.global_attention_merged(q[:1], kc[:1], vc[:1], scale=1.0)
+    s = kc[0, 0] @ q[0, 0]
+    p = np.exp(s) / np.exp(s).sum()
+    np.testing.assert_allclose(o4[0, 0], p @ vc[0, 0], rtol=1e-12)
+    np.testing.assert_allclose(l4[0, 0], math.log(np.exp(s).sum()), rtol=1e-12)
+
+
+def test_lse_merge_closed_form():
+    o, l = oracle.lse_merge(np.array([[1.0], [3.0]])[:, None, :], np.array([[0.0], [math.log(3.0)]]))
+    np.testing.assert_allclose(o, [[2.5]], rtol=1e-15)            # (1*1 + 3*3) / 4
+    np.testing.assert_allclose(l, [math.log(4.0)], rtol=1e-15)
+    o, l = oracle.lse_merge(np.array([[[5.0]], [[7.0]]]), np.array([[-np.inf], [1.0]]))
+    np.testing.assert_allclose(o, [[7.0]])
+    np.testing.assert_allclose(l, [1.0])
+
+
+def test_layer_keeping_everything_is_one_softmax_over_all_chunks():
+    """Invariant B at layer level: k_c = C and k_t = w (nothing evicted) makes the global
+    attention one softmax over all C*w context keys plus the causal query keys."""
+    r = _rng(14)
+    C, w, wq, Hq, Hkv, D, base = 3, 10, 4, 4, 2, 8, 1e4
+    L = w + wq
+    q = r.standard_normal((C, L, Hq, D))
+    k = r.standard_normal((C, L, Hkv, D))
+    v = r.standard_normal((C, L, Hkv, D))
+    q[:, w:], k[:, w:], v[:, w:] = q[0, w:], k[0, w:], v[0, w:]    # same query rows everywhere
+    out = oracle.parallelcomp_layer(q, k, v, w, 2, C, w, base)
+    assert sorted(out["chunk_idx"]) == [0, 1, 2]
+    np.testing.assert_array_equal(out["tok_idx"], np.broadcast_to(np.arange(w), (C, Hkv, w)))
+    pos = np.arange(L)
+    G = Hq // Hkv
+    for h in range(Hq):
+        g = h // G
+        K = np.concatenate([oracle.rope(k[c], pos, base)[:w, g] for c in out["chunk_idx"]]
+                           + [oracle.rope(k[0], pos, base)[w:, g]])
+        V = np.concatenate([v[c, :w, g] for c in out["chunk_idx"]] + [v[0, w:, g]])
+        qh = oracle.rope(q[0], pos, base)[w:, h]
+        mask = np.ones((wq, C * w + wq), dtype=bool)
+        mask[:, C * w:] = np.tril(np.ones((wq, wq), dtype=bool))
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qh)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+            attn_mask=torch.from_numpy(mask)[None])[0].numpy()
+        np.testing.assert_allclose(out["global_o"][:, h], ref, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ planted relevance
+def test_planted_relevance_selects_known_chunks_and_tokens():
+    """Chunks 1 and 3 carry keys aligned with the query (1 stronger than 3) at known token
+    positions; everything else is tiny noise.  The first rotary pair (theta_0 = 1) is kept
+    empty and the base is huge, so rotation is numerically the identity and the answer is
+    known by construction."""
+    r = _rng(15)
+    C, w, wq, H, D, base = 5, 24, 4, 2, 8, 1e30
+    L = w + wq
+    u = np.array([0, 1, 0, 0, 0, 0, 1, 0], dtype=np.float64) / math.sqrt(2)
+    q = 1e-3 * r.standard_normal((C, L, H, D))
+    k = 1e-3 * r.standard_normal((C, L, H, D))
+    v = r.standard_normal((C, L, H, D))
+    q[..., 0] = q[..., 4] = k[..., 0] = k[..., 4] = 0.0
+    q[:, w:] = 6.0 * u
+    k[:, w:] = k[0, w:]; v[:, w:] = v[0, w:]
+    strong, weak = [3, 7, 11, 20], [2, 5, 22]
+    k[1, strong] += 3.0 * u
+    k[3, weak] += 2.0 * u
+    out = oracle.parallelcomp_layer(q, k, v, w, wq, 2, 4, base)
+    np.testing.assert_array_equal(out["chunk_idx"], [1, 3])
+    np.testing.assert_array_equal(out["tok_idx"][0], [strong] * H)
+    assert all(set(weak) <= set(out["tok_idx"][1, g]) for g in range(H))
+    assert out["chunk_score"][1] > out["chunk_score"][3] > out["chunk_score"][[0, 2, 4]].max()
+
+
+def test_workload_plant_makes_relevant_chunks_win():
+    """The unit-variance tiny config: the planted chunk must be the top chunk of the oracle."""
+    cfg = CFG0U
+    q, k, v = (bf16_bits_to_f64(x) for x in prefill_inputs(cfg))
+    out = oracle.parallelcomp_layer(q, k, v, cfg.chunk_len, cfg.obs_window, cfg.keep_chunks,
+                                    cfg.keep_tokens, cfg.rope_base, attn_rows=[0, cfg.seq_len - 1])
+    assert out["chunk_idx"][0] == 2
+    # the sink (key 0, 4x norm) is kept by every head of every kept chunk
+    assert np.all(out["tok_idx"][:, :, 0] == 0)
+
+
+# ------------------------------------------------------------------ generators
+def test_bf16_rounding_is_nearest_even_and_exact_round_trip():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -7, 1.0 + 3 * 2 ** -8, -2.5, 0.0], dtype=np.float32)
+    b = f32_to_bf16_bits(x)
+    np.testing.assert_array_equal(bf16_bits_to_f32(b),
+                                  np.array([1.0, 1.0, 1.0 + 2 ** -7, 1.0 + 2 ** -6, -2.5, 0.0], np.float32))
+    t = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(b, t)
+    y = _rng(16).standard_normal(1000).astype(np.float32)
+    np.testing.assert_array_equal(f32_to_bf16_bits(y),
+                                  torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+def test_generators_are_seeded_and_structured():
+    q1, k1, v1 = prefill_inputs(CFG1_SMALL)
+    q2, k2, v2 = prefill_inputs(CFG1_SMALL, threads=1)
+    assert np.array_equal(q1, q2) and np.array_equal(k1, k2) and np.array_equal(v1, v2)
+    w = CFG1_SMALL.chunk_len
+    assert np.array_equal(q1[0, w:], q1[3, w:]) and np.array_equal(k1[0, w:], k1[4, w:])
+    kf = bf16_bits_to_f64(k1)
+    nrm = np.linalg.norm(kf, axis=-1)
+    assert np.all(nrm[:, 0] > 3.0 * np.median(nrm))                      # sink at key 0
+    assert len(relevant_chunks(CFG1_SMALL)) == 2
+    k2f = bf16_bits_to_f64(prefill_inputs(CFG2_SMALL)[1])
+    n2 = np.linalg.norm(k2f, axis=-1)
+    w2 = CFG2_SMALL.chunk_len
+    assert np.median(n2[:, w2 - 64:w2]) > 1.7 * np.median(n2[:, :w2 - 64])   # recency bump
+    np.testing.assert_allclose(np.std(np.log(n2[:, :w2 - 64])), 0.5, rtol=0.1)  # log-normal sigma
