@@ -1,0 +1,153 @@
+/*
+ * parallelcomp.h - C ABI of the MI355X (gfx950) ParallelComp hot path.
+ *
+ * One transformer layer of the paper's method (section 3.1):
+ *   chunked local attention with chunk-local RoPE positions   (Eq. 1-2, "Parallel attention")
+ *   cumulative query->key attention scores                     (Eq. 5-6, "Parallel KV cache eviction")
+ *   chunk selection by a per-chunk score, fixed count          (Eq. 3-4 mechanics, "Chunk eviction")
+ *   per-head token selection and KV compaction                 (Eq. 7)
+ *   global attention of the query over all surviving KV        (Eq. 9-11, "Global attention")
+ *
+ * Conventions for every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps them.  Scratch memory comes from the caller's workspace `ws`
+ *     (device memory, 256-byte aligned), whose minimum size the matching *_workspace_bytes
+ *     function returns; it may be reused between calls on the same stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work and return; they never synchronise with the host.
+ *   - bf16 tensors are raw 16-bit patterns.  All layouts are row-major with the head
+ *     dimension D innermost and contiguous.  Supported D: 64 and 128.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - RoPE pairs dimension i with i + D/2 and uses theta_i = rope_base^(-2i/D).
+ *   - Return value: PC_OK or a negative pc_status.  Host-visible arguments are validated
+ *     before any GPU work; nothing is launched when an error is returned.  The contents of
+ *     device buffers are not validated, except that selection indices handed to pc_gather_kv
+ *     that fall outside the source are read as rows of zeros instead of faulting.
+ *   - No call throws or aborts across this boundary.
+ */
+#ifndef PARALLELCOMP_H
+#define PARALLELCOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pc_status {
+  PC_OK = 0,
+  PC_ERR_NULL = -1,        /* a required pointer is NULL                                    */
+  PC_ERR_SHAPE = -2,       /* a size is out of range or inconsistent                        */
+  PC_ERR_WORKSPACE = -3,   /* ws is NULL, misaligned or smaller than *_workspace_bytes      */
+  PC_ERR_HIP = -4,         /* a HIP call failed; see pc_last_hip_error()                    */
+  PC_ERR_UNSUPPORTED = -5  /* valid request this build has no kernel for                    */
+} pc_status;
+
+/* Shape of a chunk batch (section 3.1): C sequences, each = [w context rows ; w_q query rows],
+ * L = w + w_q, the position id of a row is its index in [0, L) and restarts in every chunk. */
+typedef struct pc_shape {
+  int32_t n_chunks;      /* C  >= 1                                                          */
+  int32_t chunk_len;     /* w  >= 1                                                          */
+  int32_t query_len;     /* w_q >= 0                                                         */
+  int32_t n_q_heads;     /* H_q, multiple of n_kv_heads                                      */
+  int32_t n_kv_heads;    /* H_kv                                                             */
+  int32_t head_dim;      /* D in {64, 128}                                                   */
+  int32_t obs_window;    /* w_obs: the last w_obs rows of each sequence vote; 1..min(L, 64)  */
+  float   rope_base;     /* e.g. 1e4, 5e5                                                    */
+  float   softmax_scale; /* 0 => 1/sqrt(D)                                                   */
+} pc_shape;
+
+/* ---- Eq. 1-2 (+ Eq. 5-6 when tok_score != NULL) --------------------------------------------
+ * Local attention inside every chunk sequence, all chunks in one launch: rotate q and k at the
+ * chunk-local positions, o = softmax(q' k'^T * scale, causal j <= r) v, lse = row logsumexp.
+ *   q  [C, L, H_q, D]  bf16, before RoPE            k, v [C, L, H_kv, D] bf16, k before RoPE
+ *   o  [C, L, H_q, D]  bf16 out                     lse  [C, H_q, L]     fp32 out (natural log)
+ *   k_rope [C, L, H_kv, D] bf16 out, nullable: the rotated keys (the KV cache the later
+ *          steps gather from); when NULL the rotated keys live only in the workspace.
+ *   tok_score [C, H_kv, w] fp32 out, nullable; chunk_score [C] fp32 out, nullable (needs
+ *          tok_score): exactly what pc_chunk_query_scores writes, from the same launch queue.
+ * Arithmetic: bf16 MFMA products of the bf16-rounded rotated q and k, fp32 softmax and
+ * accumulation.  Workspace: pc_chunk_prefill_workspace_bytes(shape). */
+int pc_chunk_prefill_attn(const pc_shape* shape, const void* q, const void* k, const void* v,
+                          void* o, float* lse, void* k_rope, float* tok_score,
+                          float* chunk_score, void* ws, size_t ws_bytes, void* stream);
+size_t pc_chunk_prefill_workspace_bytes(const pc_shape* shape);
+
+/* ---- Eq. 5-6 -------------------------------------------------------------------------------
+ * Cumulative attention of the voting rows R = {L - w_obs, ..., L - 1} to every chunk key:
+ *   tok_score[c, g, j] = sum_{h in group g} sum_{r in R} P[c, h, r, j],  j < w
+ *   chunk_score[c]     = sum_g sum_j tok_score[c, g, j]                    (nullable)
+ * where P[c, h, r, :] is row r of Eq. 1 (softmax over all causal keys j <= r of the sequence,
+ * query keys included).  q, k as in pc_chunk_prefill_attn (before RoPE).  The probability
+ * block is never written to memory.  Logits are computed from split bf16 (hi + lo) operands
+ * with fp32 accumulation, i.e. to about fp32 accuracy, so that selections are stable.
+ * Workspace: pc_chunk_query_scores_workspace_bytes(shape). */
+int pc_chunk_query_scores(const pc_shape* shape, const void* q, const void* k,
+                          float* tok_score, float* chunk_score,
+                          void* ws, size_t ws_bytes, void* stream);
+size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* shape);
+
+/* ---- Eq. 3-4 mechanics ---------------------------------------------------------------------
+ * Keep a fixed number of chunks: out_idx[0..k) = indices of the k largest chunk_score under
+ * the total order (score descending, index ascending), in that rank order; out_score
+ * (nullable) the matching scores.  NaN orders below every number.  1 <= k <= n <= 4096.
+ * The score is the caller's choice (here: the query's attention mass on the chunk, larger is
+ * better; the paper's self-information would be passed negated). */
+int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_t k,
+                          int32_t* out_idx, float* out_score, void* stream);
+
+/* ---- Eq. 7 (index sets) --------------------------------------------------------------------
+ * For every selected chunk s < n_sel and KV head g: the k tokens of
+ * tok_score[chunk_idx[s], g, 0:chunk_len] that are largest under (score descending, index
+ * ascending), written in ascending index order.
+ *   tok_score [n_chunks_total, H_kv, chunk_len] fp32   chunk_idx [n_sel] int32, NULL => s
+ *   out_idx   [n_sel, H_kv, k] int32.        1 <= k <= chunk_len <= 32768.   No workspace. */
+int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,
+                          int32_t n_kv_heads, int32_t chunk_len, int32_t k,
+                          int32_t* out_idx, void* stream);
+
+/* ---- Eq. 7 (compressed KV cache) -----------------------------------------------------------
+ * dst[b, s, g, t, :] = src[b, chunk_idx[b, s], tok_idx[b, s, g, t], g, :]  for K and V.
+ *   k_src, v_src [batch, n_chunks, rows_per_chunk, H_kv, D] bf16 (a pure 16-bit copy)
+ *   chunk_idx [batch, n_sel] int32, NULL => s      tok_idx [batch, n_sel, H_kv, k] int32
+ *   k_dst, v_dst [batch, n_sel, H_kv, k, D].   Indices outside the source give zero rows. */
+int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
+                 const int32_t* tok_idx, int32_t batch, int32_t n_chunks,
+                 int32_t rows_per_chunk, int32_t n_sel, int32_t n_kv_heads, int32_t k,
+                 int32_t head_dim, void* k_dst, void* v_dst, void* stream);
+
+/* ---- Eq. 9-11 ------------------------------------------------------------------------------
+ * Global ("parallel") attention of n_q query rows over the concatenation of S compressed
+ * segments and, optionally, the causal self segment of the query's own keys:
+ *   out[b, t, h, :] = softmax over { kc[b, s, g, 0:seg_len[b,s]] for all s } U
+ *                                  { k_self[b, 0..t, g] } of q . k * scale, times the values.
+ * Computed as independent per-segment (and per-split) softmaxes merged exactly by logsumexp:
+ *   LSE = log sum_p exp(lse_p),  out = sum_p exp(lse_p - LSE) o_p.
+ *   q [B, n_q, H_q, D] bf16; if q_pos0 >= 0 it is rotated here at positions q_pos0 + t,
+ *     if q_pos0 < 0 it is taken as already rotated.
+ *   kc, vc [B, S, H_kv, k_t, D] bf16, keys already rotated (chunk-local positions kept)
+ *   seg_len [B, S] int32 valid rows per segment, NULL => k_t
+ *   k_self, v_self [B, n_q, H_kv, D] bf16 rotated keys / values of the query rows, both NULL
+ *     for no self segment (decode)
+ *   out [B, n_q, H_q, D] bf16;  lse_out [B, H_q, n_q] fp32, nullable.
+ * n_q * (H_q / H_kv) <= 16 runs the HBM-bound split-KV kernel; larger n_q the MFMA tile kernel.
+ * Workspace: pc_parallel_attn_workspace_bytes(...). */
+int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
+                     const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                     int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
+                     int32_t head_dim, int32_t q_pos0, float rope_base, float softmax_scale,
+                     void* out, float* lse_out, void* ws, size_t ws_bytes, void* stream);
+size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
+                                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                        int32_t has_self);
+
+/* ---- housekeeping -------------------------------------------------------------------------- */
+const char* pc_status_string(int status);   /* static string, never NULL                       */
+int         pc_last_hip_error(void);        /* hipError_t of the last PC_ERR_HIP on this thread */
+const char* pc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARALLELCOMP_H */

@@ -1,0 +1,8 @@
+"""MI355X-native ParallelComp hot path: a C-ABI HIP library (csrc/, include/parallelcomp.h)
+and its thin Python binding.  Importing the package does not load the library; the first call
+does, and raises if the library has not been built (there is no CPU fallback)."""
+from .binding import (lib, make_shape, alloc_workspace, pc_shape, PcError, SYMBOLS,
+                      pc_chunk_prefill_attn, pc_chunk_prefill_workspace_bytes,
+                      pc_chunk_query_scores, pc_chunk_query_scores_workspace_bytes,
+                      pc_select_chunks_topk, pc_select_tokens_topk, pc_gather_kv,
+                      pc_parallel_attn, pc_parallel_attn_workspace_bytes)

@@ -1,0 +1,164 @@
+"""Thin ctypes binding of libparallelcomp.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (include/parallelcomp.h)
+and takes torch tensors that already live on the GPU; PyTorch is used for device memory and
+the current stream, nothing else.  Every step of the path runs in the library's HIP kernels.
+There is no fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_float, c_int, c_int32, c_size_t, c_void_p
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libparallelcomp.so")
+
+PC_OK = 0
+SYMBOLS = [
+    "pc_chunk_prefill_attn", "pc_chunk_prefill_workspace_bytes", "pc_chunk_query_scores",
+    "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
+    "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
+    "pc_last_hip_error", "pc_version",
+]
+
+
+class pc_shape(Structure):
+    _fields_ = [("n_chunks", c_int32), ("chunk_len", c_int32), ("query_len", c_int32),
+                ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
+                ("obs_window", c_int32), ("rope_base", c_float), ("softmax_scale", c_float)]
+
+
+class PcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().pc_status_string(status).decode()
+        if status == -4:
+            msg += f" (hipError {lib().pc_last_hip_error()})"
+        super().__init__(f"{where}: {msg}")
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2502_14317_amd.build` "
+            "(the HIP extension is required; there is no CPU fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    P = c_void_p
+    L.pc_chunk_prefill_attn.argtypes = [POINTER(pc_shape), P, P, P, P, P, P, P, P, P, c_size_t, P]
+    L.pc_chunk_prefill_attn.restype = c_int
+    L.pc_chunk_prefill_workspace_bytes.argtypes = [POINTER(pc_shape)]
+    L.pc_chunk_prefill_workspace_bytes.restype = c_size_t
+    L.pc_chunk_query_scores.argtypes = [POINTER(pc_shape), P, P, P, P, P, c_size_t, P]
+    L.pc_chunk_query_scores.restype = c_int
+    L.pc_chunk_query_scores_workspace_bytes.argtypes = [POINTER(pc_shape)]
+    L.pc_chunk_query_scores_workspace_bytes.restype = c_size_t
+    L.pc_select_chunks_topk.argtypes = [P, c_int32, c_int32, P, P, P]
+    L.pc_select_chunks_topk.restype = c_int
+    L.pc_select_tokens_topk.argtypes = [P, P, c_int32, c_int32, c_int32, c_int32, P, P]
+    L.pc_select_tokens_topk.restype = c_int
+    L.pc_gather_kv.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P]
+    L.pc_gather_kv.restype = c_int
+    L.pc_parallel_attn.argtypes = [P] * 6 + [c_int32] * 8 + [c_float, c_float, P, P, P, c_size_t, P]
+    L.pc_parallel_attn.restype = c_int
+    L.pc_parallel_attn_workspace_bytes.argtypes = [c_int32] * 8
+    L.pc_parallel_attn_workspace_bytes.restype = c_size_t
+    L.pc_status_string.argtypes = [c_int]
+    L.pc_status_string.restype = c_char_p
+    L.pc_last_hip_error.argtypes = []
+    L.pc_last_hip_error.restype = c_int
+    L.pc_version.argtypes = []
+    L.pc_version.restype = c_char_p
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous GPU tensors")
+    return c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(ws):
+    return (_ptr(ws), c_size_t(ws.numel() * ws.element_size())) if ws is not None else (None, c_size_t(0))
+
+
+def _check(rc, where):
+    if rc != PC_OK:
+        raise PcError(rc, where)
+
+
+def make_shape(n_chunks, chunk_len, query_len, n_q_heads, n_kv_heads, head_dim, obs_window,
+               rope_base, softmax_scale=0.0):
+    return pc_shape(n_chunks, chunk_len, query_len, n_q_heads, n_kv_heads, head_dim, obs_window,
+                    rope_base, softmax_scale)
+
+
+def alloc_workspace(n_bytes, device="cuda"):
+    """Device scratch for a call (torch allocations are 256-byte aligned or better)."""
+    return torch.empty(max(int(n_bytes), 256), dtype=torch.uint8, device=device)
+
+
+def pc_chunk_prefill_workspace_bytes(shape):
+    return lib().pc_chunk_prefill_workspace_bytes(ctypes.byref(shape))
+
+
+def pc_chunk_query_scores_workspace_bytes(shape):
+    return lib().pc_chunk_query_scores_workspace_bytes(ctypes.byref(shape))
+
+
+def pc_parallel_attn_workspace_bytes(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, has_self):
+    return lib().pc_parallel_attn_workspace_bytes(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
+                                                  head_dim, int(has_self))
+
+
+def pc_chunk_prefill_attn(shape, q, k, v, o, lse, k_rope, tok_score, chunk_score, ws):
+    p, n = _ws(ws)
+    _check(lib().pc_chunk_prefill_attn(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                       _ptr(lse), _ptr(k_rope), _ptr(tok_score), _ptr(chunk_score),
+                                       p, n, _stream()), "pc_chunk_prefill_attn")
+
+
+def pc_chunk_query_scores(shape, q, k, tok_score, chunk_score, ws):
+    p, n = _ws(ws)
+    _check(lib().pc_chunk_query_scores(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(tok_score),
+                                       _ptr(chunk_score), p, n, _stream()), "pc_chunk_query_scores")
+
+
+def pc_select_chunks_topk(chunk_score, n, k, out_idx, out_score=None):
+    _check(lib().pc_select_chunks_topk(_ptr(chunk_score), n, k, _ptr(out_idx), _ptr(out_score),
+                                       _stream()), "pc_select_chunks_topk")
+
+
+def pc_select_tokens_topk(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, out_idx):
+    _check(lib().pc_select_tokens_topk(_ptr(tok_score), _ptr(chunk_idx), n_sel, n_kv_heads,
+                                       chunk_len, k, _ptr(out_idx), _stream()),
+           "pc_select_tokens_topk")
+
+
+def pc_gather_kv(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
+                 n_kv_heads, k, head_dim, k_dst, v_dst):
+    _check(lib().pc_gather_kv(_ptr(k_src), _ptr(v_src), _ptr(chunk_idx), _ptr(tok_idx), batch,
+                              n_chunks, rows_per_chunk, n_sel, n_kv_heads, k, head_dim,
+                              _ptr(k_dst), _ptr(v_dst), _stream()), "pc_gather_kv")
+
+
+def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t, n_q_heads,
+                     n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out, lse_out, ws):
+    p, n = _ws(ws)
+    _check(lib().pc_parallel_attn(_ptr(q), _ptr(kc), _ptr(vc), _ptr(seg_len), _ptr(k_self),
+                                  _ptr(v_self), batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
+                                  head_dim, q_pos0, rope_base, softmax_scale, _ptr(out),
+                                  _ptr(lse_out), p, n, _stream()), "pc_parallel_attn")

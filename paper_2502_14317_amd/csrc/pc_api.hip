@@ -1,0 +1,316 @@
+// C ABI of the ParallelComp library: argument validation, workspace carving, kernel dispatch.
+// Every host-visible argument is checked before any GPU work is enqueued.
+#include "pc_common.h"
+#include <math.h>
+
+static thread_local int g_last_hip_error = 0;
+void pc_set_hip_error(int err) { g_last_hip_error = err; }
+
+extern "C" int pc_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" const char* pc_version(void) { return "parallelcomp-gfx950 0.1"; }
+
+extern "C" const char* pc_status_string(int status) {
+  switch (status) {
+    case PC_OK: return "PC_OK";
+    case PC_ERR_NULL: return "PC_ERR_NULL: a required pointer is NULL";
+    case PC_ERR_SHAPE: return "PC_ERR_SHAPE: a size is out of range or inconsistent";
+    case PC_ERR_WORKSPACE: return "PC_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case PC_ERR_HIP: return "PC_ERR_HIP: a HIP call failed (see pc_last_hip_error)";
+    case PC_ERR_UNSUPPORTED: return "PC_ERR_UNSUPPORTED: no kernel for this request";
+    default: return "unknown pc_status";
+  }
+}
+
+static const size_t kAlign = 256;
+
+static int check_shape(const pc_shape* s) {
+  if (!s) return PC_ERR_NULL;
+  if (s->n_chunks < 1 || s->chunk_len < 1 || s->query_len < 0) return PC_ERR_SHAPE;
+  if (s->n_kv_heads < 1 || s->n_q_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return PC_ERR_SHAPE;
+  if (s->head_dim != 64 && s->head_dim != 128) return PC_ERR_SHAPE;
+  const long long L = (long long)s->chunk_len + s->query_len;
+  if (L > (1 << 20) || s->n_chunks > (1 << 20) || s->n_q_heads > 1024) return PC_ERR_SHAPE;
+  if (!(s->rope_base > 1.0f) || !isfinite(s->rope_base)) return PC_ERR_SHAPE;
+  if (!(s->softmax_scale >= 0.0f) || !isfinite(s->softmax_scale)) return PC_ERR_SHAPE;
+  return PC_OK;
+}
+
+static int check_obs(const pc_shape* s) {
+  const int L = s->chunk_len + s->query_len;
+  if (s->obs_window < 1 || s->obs_window > 64 || s->obs_window > L) return PC_ERR_SHAPE;
+  if ((s->n_q_heads / s->n_kv_heads) * s->obs_window > 512) return PC_ERR_UNSUPPORTED;
+  return PC_OK;
+}
+
+static float eff_scale(float scale, int head_dim) {
+  return scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+}
+
+struct PrefillWs {
+  size_t table, v_t, k_rope, ml, total;
+  int Lp;
+};
+
+static PrefillWs prefill_ws_layout(const pc_shape* s) {
+  PrefillWs w;
+  const size_t L = (size_t)s->chunk_len + s->query_len;
+  w.Lp = (int)((L + 63) / 64 * 64);
+  size_t off = 0;
+  w.table = off; off = pc_align_up(off + L * (s->head_dim / 2) * sizeof(float2), kAlign);
+  w.v_t = off;   off = pc_align_up(off + (size_t)s->n_chunks * s->n_kv_heads * s->head_dim * w.Lp * 2, kAlign);
+  w.k_rope = off; off = pc_align_up(off + (size_t)s->n_chunks * L * s->n_kv_heads * s->head_dim * 2, kAlign);
+  w.ml = off;    off = pc_align_up(off + pc_scores_ml_bytes(s), kAlign);
+  w.total = off;
+  return w;
+}
+
+extern "C" size_t pc_chunk_prefill_workspace_bytes(const pc_shape* s) {
+  if (check_shape(s) != PC_OK) return 0;
+  pc_shape t = *s;
+  if (t.obs_window < 1) t.obs_window = 1;
+  if (t.obs_window > 64) t.obs_window = 64;
+  return prefill_ws_layout(&t).total;
+}
+
+extern "C" size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* s) {
+  if (check_shape(s) != PC_OK || check_obs(s) != PC_OK) return 0;
+  const size_t L = (size_t)s->chunk_len + s->query_len;
+  return pc_align_up(L * (s->head_dim / 2) * sizeof(float2), kAlign) +
+         pc_align_up(pc_scores_ml_bytes(s), kAlign);
+}
+
+extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const void* k, const void* v,
+                                     void* o, float* lse, void* k_rope, float* tok_score,
+                                     float* chunk_score, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s);
+  if (rc != PC_OK) return rc;
+  if (!q || !k || !v || !o || !lse) return PC_ERR_NULL;
+  if (chunk_score && !tok_score) return PC_ERR_NULL;
+  if (tok_score) {
+    rc = check_obs(s);
+    if (rc != PC_OK) return rc;
+  }
+  pc_shape t = *s;
+  if (!tok_score) t.obs_window = 1;
+  const PrefillWs w = prefill_ws_layout(&t);
+  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  float2* table = (float2*)(base + w.table);
+  void* v_t = base + w.v_t;
+  void* kr = k_rope ? k_rope : (void*)(base + w.k_rope);
+  const int L = s->chunk_len + s->query_len, D = s->head_dim;
+
+  rc = pc_launch_rope_table(table, L, D, s->rope_base, st);
+  if (rc != PC_OK) return rc;
+  rc = pc_launch_kv_prepass(k, v, table, kr, v_t, s->n_chunks, L, w.Lp, s->n_kv_heads, D, st);
+  if (rc != PC_OK) return rc;
+
+  PcFlashArgs a = {};
+  a.q = q; a.k = kr; a.v_t = v_t; a.table = table; a.o = o; a.lse = lse;
+  a.part_o = nullptr; a.part_lse = nullptr; a.part_len = nullptr;
+  a.k_seq_stride = (long long)L * s->n_kv_heads * D; a.k_part_stride = 0;
+  a.k_head_stride = D; a.k_row_stride = (long long)s->n_kv_heads * D;
+  a.vt_seq_stride = (long long)s->n_kv_heads * D * w.Lp; a.vt_part_stride = 0;
+  a.vt_head_stride = (long long)D * w.Lp; a.vt_d_stride = w.Lp;
+  a.n_seq = s->n_chunks; a.n_rows = L; a.n_keys = L;
+  a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads; a.head_dim = D;
+  a.n_parts_grid = 1; a.n_parts_total = 1; a.part0 = 0;
+  a.causal_offset = 0; a.q_pos0 = 0;
+  a.scale = eff_scale(s->softmax_scale, D);
+  rc = pc_launch_flash(a, st);
+  if (rc != PC_OK) return rc;
+
+  if (tok_score) {
+    rc = pc_launch_scores(s, q, k, table, base + w.ml, tok_score, chunk_score, st);
+    if (rc != PC_OK) return rc;
+  }
+  return PC_OK;
+}
+
+extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const void* k,
+                                     float* tok_score, float* chunk_score, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  int rc = check_shape(s);
+  if (rc != PC_OK) return rc;
+  rc = check_obs(s);
+  if (rc != PC_OK) return rc;
+  if (!q || !k || !tok_score) return PC_ERR_NULL;
+  const size_t need = pc_chunk_query_scores_workspace_bytes(s);
+  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < need) return PC_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int L = s->chunk_len + s->query_len;
+  float2* table = (float2*)ws;
+  void* ml = (char*)ws + pc_align_up((size_t)L * (s->head_dim / 2) * sizeof(float2), kAlign);
+  rc = pc_launch_rope_table(table, L, s->head_dim, s->rope_base, st);
+  if (rc != PC_OK) return rc;
+  return pc_launch_scores(s, q, k, table, ml, tok_score, chunk_score, st);
+}
+
+extern "C" int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_t k,
+                                     int32_t* out_idx, float* out_score, void* stream) {
+  if (!chunk_score || !out_idx) return PC_ERR_NULL;
+  if (n < 1 || n > 4096 || k < 1 || k > n) return PC_ERR_SHAPE;
+  return pc_launch_select_chunks(chunk_score, n, k, out_idx, out_score, (hipStream_t)stream);
+}
+
+extern "C" int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,
+                                     int32_t n_kv_heads, int32_t chunk_len, int32_t k,
+                                     int32_t* out_idx, void* stream) {
+  if (!tok_score || !out_idx) return PC_ERR_NULL;
+  if (n_sel < 0 || n_kv_heads < 1 || chunk_len < 1 || chunk_len > 32768 || k < 1 || k > chunk_len)
+    return PC_ERR_SHAPE;
+  if ((long long)n_sel * n_kv_heads > 0x7fffffffLL) return PC_ERR_SHAPE;
+  if (n_sel == 0) return PC_OK;
+  return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, out_idx,
+                                 (hipStream_t)stream);
+}
+
+extern "C" int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
+                            const int32_t* tok_idx, int32_t batch, int32_t n_chunks,
+                            int32_t rows_per_chunk, int32_t n_sel, int32_t n_kv_heads, int32_t k,
+                            int32_t head_dim, void* k_dst, void* v_dst, void* stream) {
+  if (!k_src || !v_src || !tok_idx || !k_dst || !v_dst) return PC_ERR_NULL;
+  if (batch < 0 || n_chunks < 1 || rows_per_chunk < 1 || n_sel < 0 || n_kv_heads < 1 || k < 0)
+    return PC_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
+  if (!pc_aligned(k_src, 16) || !pc_aligned(v_src, 16) || !pc_aligned(k_dst, 16) || !pc_aligned(v_dst, 16))
+    return PC_ERR_SHAPE;
+  return pc_launch_gather(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
+                          n_kv_heads, k, head_dim, k_dst, v_dst, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------- parallel attention
+struct ParWs {
+  size_t q_rot, part_o, part_lse, vt_seg, vt_self, total;
+  int n_parts, ktp, nqp;
+  bool small;
+};
+
+static ParWs par_ws_layout(int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                           int D, int has_self) {
+  ParWs w;
+  const int G = n_q_heads / n_kv_heads;
+  w.small = (long long)n_q * G <= 16;
+  w.ktp = (k_t + 63) / 64 * 64;
+  w.nqp = (n_q + 63) / 64 * 64;
+  if (w.small) {
+    const int kpw = pc_decode_keys_per_wg(k_t);
+    w.n_parts = n_seg * ((k_t + kpw - 1) / kpw);
+  } else {
+    w.n_parts = n_seg + (has_self ? 1 : 0);
+  }
+  size_t off = 0;
+  const size_t rows = (size_t)batch * n_q * n_q_heads;
+  w.q_rot = off;    off = pc_align_up(off + rows * D * 2, kAlign);
+  w.part_o = off;   off = pc_align_up(off + rows * (size_t)w.n_parts * D * sizeof(float), kAlign);
+  w.part_lse = off; off = pc_align_up(off + rows * (size_t)w.n_parts * sizeof(float), kAlign);
+  w.vt_seg = off;
+  w.vt_self = off;
+  if (!w.small) {
+    off = pc_align_up(off + (size_t)batch * n_seg * n_kv_heads * D * w.ktp * 2, kAlign);
+    w.vt_self = off;
+    if (has_self) off = pc_align_up(off + (size_t)batch * n_kv_heads * D * w.nqp * 2, kAlign);
+  }
+  w.total = off;
+  return w;
+}
+
+static int check_par(int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads, int D) {
+  if (batch < 1 || n_q < 1 || n_seg < 0 || k_t < 1) return PC_ERR_SHAPE;
+  if (n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % n_kv_heads != 0) return PC_ERR_SHAPE;
+  if (D != 64 && D != 128) return PC_ERR_SHAPE;
+  if (n_q > (1 << 20) || k_t > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
+  return PC_OK;
+}
+
+extern "C" size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg,
+                                                   int32_t k_t, int32_t n_q_heads,
+                                                   int32_t n_kv_heads, int32_t head_dim,
+                                                   int32_t has_self) {
+  if (check_par(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim) != PC_OK) return 0;
+  return par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, has_self).total;
+}
+
+extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
+                                const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                                int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t head_dim, int32_t q_pos0, float rope_base,
+                                float softmax_scale, void* out, float* lse_out, void* ws,
+                                size_t ws_bytes, void* stream) {
+  int rc = check_par(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim);
+  if (rc != PC_OK) return rc;
+  if (!q || !out) return PC_ERR_NULL;
+  if (n_seg > 0 && (!kc || !vc)) return PC_ERR_NULL;
+  if ((k_self == nullptr) != (v_self == nullptr)) return PC_ERR_NULL;
+  const int has_self = k_self != nullptr;
+  if (n_seg == 0 && !has_self) return PC_ERR_SHAPE;
+  if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
+  if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
+  const int D = head_dim;
+  const ParWs w = par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, D, has_self);
+  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  const float scale = eff_scale(softmax_scale, D);
+
+  const void* q_rot = q;
+  if (q_pos0 >= 0) {
+    rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
+                          q_pos0, rope_base, st);
+    if (rc != PC_OK) return rc;
+    q_rot = base + w.q_rot;
+  }
+  float* part_o = (float*)(base + w.part_o);
+  float* part_lse = (float*)(base + w.part_lse);
+
+  if (w.small) {
+    if (n_seg > 0) {
+      rc = pc_launch_decode(q_rot, kc, vc, seg_len, batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
+                            D, scale, part_o, part_lse, w.n_parts, st);
+      if (rc != PC_OK) return rc;
+    }
+    return pc_launch_merge(part_o, part_lse, q_rot, k_self, v_self, out, lse_out, batch, n_q,
+                           n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
+  }
+
+  // ---- many query rows: MFMA tile kernel per (segment), partials merged afterwards
+  PcFlashArgs a = {};
+  a.q = q_rot; a.table = nullptr; a.o = nullptr; a.lse = nullptr;
+  a.part_o = part_o; a.part_lse = part_lse;
+  a.n_seq = batch; a.n_rows = n_q; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
+  a.head_dim = D; a.n_parts_total = w.n_parts; a.q_pos0 = 0; a.scale = scale;
+  if (n_seg > 0) {
+    void* vt = base + w.vt_seg;
+    rc = pc_launch_kv_prepass(nullptr, vc, nullptr, nullptr, vt, batch * n_seg * n_kv_heads, k_t,
+                              w.ktp, 1, D, st);
+    if (rc != PC_OK) return rc;
+    a.k = kc; a.v_t = vt; a.part_len = seg_len;
+    a.k_seq_stride = (long long)n_seg * n_kv_heads * k_t * D;
+    a.k_part_stride = (long long)n_kv_heads * k_t * D;
+    a.k_head_stride = (long long)k_t * D; a.k_row_stride = D;
+    a.vt_seq_stride = (long long)n_seg * n_kv_heads * D * w.ktp;
+    a.vt_part_stride = (long long)n_kv_heads * D * w.ktp;
+    a.vt_head_stride = (long long)D * w.ktp; a.vt_d_stride = w.ktp;
+    a.n_keys = k_t; a.n_parts_grid = n_seg; a.part0 = 0; a.causal_offset = PC_NO_CAUSAL;
+    rc = pc_launch_flash(a, st);
+    if (rc != PC_OK) return rc;
+  }
+  if (has_self) {
+    void* vt = base + w.vt_self;
+    rc = pc_launch_kv_prepass(nullptr, v_self, nullptr, nullptr, vt, batch, n_q, w.nqp, n_kv_heads,
+                              D, st);
+    if (rc != PC_OK) return rc;
+    a.k = k_self; a.v_t = vt; a.part_len = nullptr;
+    a.k_seq_stride = (long long)n_q * n_kv_heads * D; a.k_part_stride = 0;
+    a.k_head_stride = D; a.k_row_stride = (long long)n_kv_heads * D;
+    a.vt_seq_stride = (long long)n_kv_heads * D * w.nqp; a.vt_part_stride = 0;
+    a.vt_head_stride = (long long)D * w.nqp; a.vt_d_stride = w.nqp;
+    a.n_keys = n_q; a.n_parts_grid = 1; a.part0 = n_seg; a.causal_offset = 0;
+    rc = pc_launch_flash(a, st);
+    if (rc != PC_OK) return rc;
+  }
+  return pc_launch_merge(part_o, part_lse, q_rot, nullptr, nullptr, out, lse_out, batch, n_q,
+                         n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
+}

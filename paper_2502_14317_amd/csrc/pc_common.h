@@ -1,0 +1,109 @@
+// Internal helpers shared by the HIP translation units of the ParallelComp library (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "parallelcomp.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+#define PC_WAVE 64
+
+// ---------------------------------------------------------------- host-side error plumbing
+void pc_set_hip_error(int err);
+#define PC_HIP_TRY(expr)                                   \
+  do {                                                     \
+    hipError_t _e = (expr);                                \
+    if (_e != hipSuccess) {                                \
+      pc_set_hip_error((int)_e);                           \
+      return PC_ERR_HIP;                                   \
+    }                                                      \
+  } while (0)
+#define PC_LAUNCH_CHECK() PC_HIP_TRY(hipGetLastError())
+
+static inline size_t pc_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline bool pc_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// ---------------------------------------------------------------- bf16 <-> fp32 (device)
+__device__ __forceinline__ float bf16_lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; inputs are finite by contract (NaN keeps a NaN pattern)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// fp32 score -> uint32 key whose unsigned order is the float order; NaN -> 0 (below everything),
+// -0.0 and +0.0 map to the same key
+__device__ __forceinline__ uint32_t pc_order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;
+  if ((u << 1) == 0u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---------------------------------------------------------------- kernels' host launchers
+// (each defined in its own translation unit; all arguments already validated)
+int pc_launch_gather(const void* k_src, const void* v_src, const int32_t* chunk_idx,
+                     const int32_t* tok_idx, int batch, int n_chunks, int rows, int n_sel,
+                     int n_kv_heads, int k, int head_dim, void* k_dst, void* v_dst,
+                     hipStream_t st);
+int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, float* out_score,
+                            hipStream_t st);
+int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
+                            int n_kv_heads, int chunk_len, int k, int32_t* out_idx,
+                            hipStream_t st);
+
+int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st);
+
+// K/V pre-pass: rotate K (skipped when k == nullptr), transpose V into [n_seq, H_kv, D, Lp].
+int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void* k_rope,
+                         void* v_t, int n_seq, int L, int Lp, int n_kv_heads, int head_dim,
+                         hipStream_t st);
+
+// Flash-style tile kernel.  A workgroup handles (sequence, query head, 256-row Q tile, part);
+// a "part" is an independent key set (a compressed segment) with its own softmax.
+struct PcFlashArgs {
+  const void* q;            // [n_seq, n_rows, H_q, D] bf16
+  const void* k;            // rotated keys: k + seq*k_seq_stride + part*k_part_stride + g*k_head_stride + row*k_row_stride
+  const void* v_t;          // transposed values: v_t + seq*.. + part*.. + g*vt_head_stride + d*vt_d_stride + key
+  const float2* table;      // rope table (rotate q at q_pos0 + row) or nullptr (q already rotated)
+  void* o;                  // [n_seq, n_rows, H_q, D] bf16 (final output mode)
+  float* lse;               // [n_seq, H_q, n_rows] or nullptr
+  float* part_o;            // partial mode: [n_seq, n_parts_total, n_rows, H_q, D] fp32, else nullptr
+  float* part_lse;          // [n_seq, n_parts_total, n_rows, H_q]
+  const int32_t* part_len;  // [n_seq, n_parts_grid] valid keys per part or nullptr (= n_keys)
+  long long k_seq_stride, k_part_stride, k_head_stride, k_row_stride;      // elements
+  long long vt_seq_stride, vt_part_stride, vt_head_stride, vt_d_stride;    // elements
+  int n_seq, n_rows, n_keys, n_q_heads, n_kv_heads, head_dim;
+  int n_parts_grid, n_parts_total, part0;
+  int causal_offset;        // key j visible to row r iff j <= r + causal_offset; >= 2^29: no mask
+  int q_pos0;
+  float scale;
+};
+#define PC_NO_CAUSAL (1 << 29)
+int pc_launch_flash(const PcFlashArgs& a, hipStream_t st);
+
+size_t pc_scores_ml_bytes(const pc_shape* s);
+int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const float2* table,
+                     void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st);
+
+int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
+                     int pos0, float base, hipStream_t st);
+int pc_decode_keys_per_wg(int k_t);
+int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
+                     int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                     int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
+                     hipStream_t st);
+int pc_launch_merge(const float* part_o, const float* part_lse, const void* q_rot,
+                    const void* k_self, const void* v_self, void* out, float* lse_out, int batch,
+                    int n_q, int n_q_heads, int n_kv_heads, int head_dim, int n_parts, float scale,
+                    hipStream_t st);

@@ -1,0 +1,298 @@
+// Cumulative query->key attention scores (Eq. 5-6):
+//   tok_score[c, g, j] = sum over the query heads h of KV group g and over the voting rows r
+//                        (the last w_obs rows of the chunk sequence) of P[c, h, r, j],  j < w,
+// where P[c, h, r, :] is the causal softmax row of Eq. 1 over ALL keys of the sequence.
+// The probability block [H_q, w_obs, L] is never written to memory: it is recomputed.
+//
+// Accuracy.  The scores decide which tokens are kept, so logits are computed to about fp32
+// accuracy although they run on the bf16 matrix cores: q and k are rotated in fp32 and split
+// into bf16 hi + lo parts, and q.k = hi.hi + hi.lo + lo.hi (three MFMAs; the lo.lo term is
+// below 2^-16 relative).
+//
+// Two passes over the keys, both fully parallel over 256-key blocks:
+//   pass 1  (S^T = K Q^T, a lane owns a voting row)  per-block running max / sum of every
+//           voting row -> workspace [c, g, key block, column] (m, l)
+//   pass 2  (S = Q K^T, a lane owns a key)           combine the blocks' (m, l) into the row
+//           logsumexp, recompute the logits, p = exp2(s - lse) and sum p over the columns
+//           (voting rows x heads of the group) for each key -> tok_score
+// A third kernel sums tok_score per chunk in a fixed order (deterministic) -> chunk_score.
+#include "pc_common.h"
+#include <math.h>
+
+#define PC_SC_THREADS 256
+#define PC_SC_WAVES 4
+#define PC_SC_KB 256        // keys per workgroup
+#define PC_SC_TILE 64       // keys staged in LDS at a time
+#define PC_SC_LOG2E 1.4426950408889634f
+
+struct PcScoreArgs {
+  const uint16_t* q;       // [C, L, H_q, D] before RoPE
+  const uint16_t* k;       // [C, L, H_kv, D] before RoPE
+  const float2* table;     // [L, D/2] (cos, sin)
+  float2* ml;              // workspace [C, H_kv, n_kb, n_cols] (max in log2 units, sum)
+  float* tok_score;        // [C, H_kv, w]
+  int L, w, w_obs, n_q_heads, n_kv_heads, n_kb, n_cols;
+  float scale_log2;
+};
+
+__device__ __forceinline__ void split_bf16(float x, uint32_t& hi, uint32_t& lo) {
+  hi = f32_to_bf16_bits(x);
+  lo = f32_to_bf16_bits(x - __uint_as_float(hi << 16));
+}
+
+template <int D, int PASS>
+__global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
+  constexpr int KS = D / 16, HALF = D / 2, KSTRIDE = D + 8;
+  __shared__ __attribute__((aligned(16))) uint16_t k_hi[PC_SC_TILE * KSTRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t k_lo[PC_SC_TILE * KSTRIDE];
+  __shared__ float lse2_lds[512];
+  __shared__ float tok_part[PC_SC_WAVES][PC_SC_KB];
+
+  const int c = blockIdx.x, g = blockIdx.y, kblock = blockIdx.z;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int tid = threadIdx.x, lane = tid % PC_WAVE, wave = tid / PC_WAVE;
+  const int hf = lane / 32, n = lane % 32;
+  const int n_cb = (a.n_cols + 31) / 32;
+  const int first_obs = a.L - a.w_obs;
+  const long long ml_base = (((long long)c * a.n_kv_heads + g) * a.n_kb) * a.n_cols;
+
+  if (PASS == 2) {
+    for (int col = tid; col < a.n_cols; col += PC_SC_THREADS) {
+      float M = -INFINITY;
+      for (int kb = 0; kb < a.n_kb; ++kb) M = fmaxf(M, a.ml[ml_base + (long long)kb * a.n_cols + col].x);
+      float sum = 0.f;
+      for (int kb = 0; kb < a.n_kb; ++kb) {
+        const float2 v = a.ml[ml_base + (long long)kb * a.n_cols + col];
+        if (v.y > 0.f) sum += v.y * exp2f(v.x - M);
+      }
+      lse2_lds[col] = M + log2f(sum);
+    }
+  }
+
+  float tok_acc[PC_SC_KB / PC_SC_TILE][2];
+#pragma unroll
+  for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) tok_acc[t][0] = tok_acc[t][1] = 0.f;
+
+  const int n_rounds = (n_cb + PC_SC_WAVES - 1) / PC_SC_WAVES;
+  for (int round = 0; round < n_rounds; ++round) {
+    const int cb = round * PC_SC_WAVES + wave;
+    const bool active = cb < n_cb;
+    // ---- this lane's column as an MFMA operand: rotate at the row's position, split hi/lo
+    const int col = min(32 * cb + n, a.n_cols - 1);
+    const int hg = col / a.w_obs, qrow_idx = first_obs + col % a.w_obs;
+    bf16x8 qhi[KS], qlo[KS];
+    if (active) {
+      const uint16_t* qrow = a.q + (((long long)c * a.L + qrow_idx) * a.n_q_heads + g * G + hg) * D;
+      const float2* cs = a.table + (long long)qrow_idx * HALF;
+#pragma unroll
+      for (int ks = 0; ks < KS / 2; ++ks) {
+        const int i0 = 16 * ks + 8 * hf;
+        const uint4 x1 = *(const uint4*)(qrow + i0);
+        const uint4 x2 = *(const uint4*)(qrow + HALF + i0);
+        const uint32_t aw[4] = {x1.x, x1.y, x1.z, x1.w}, bw[4] = {x2.x, x2.y, x2.z, x2.w};
+        uint32_t h1[4], l1[4], h2[4], l2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
+          const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
+          const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
+          uint32_t ha, la, hb, lb;
+          split_bf16(x1l * c0.x - x2l * c0.y, ha, la);
+          split_bf16(x1h * c1.x - x2h * c1.y, hb, lb);
+          h1[e] = ha | (hb << 16); l1[e] = la | (lb << 16);
+          split_bf16(x2l * c0.x + x1l * c0.y, ha, la);
+          split_bf16(x2h * c1.x + x1h * c1.y, hb, lb);
+          h2[e] = ha | (hb << 16); l2[e] = la | (lb << 16);
+        }
+        uint4 t;
+        t = make_uint4(h1[0], h1[1], h1[2], h1[3]); qhi[ks] = *(bf16x8*)&t;
+        t = make_uint4(l1[0], l1[1], l1[2], l1[3]); qlo[ks] = *(bf16x8*)&t;
+        t = make_uint4(h2[0], h2[1], h2[2], h2[3]); qhi[ks + KS / 2] = *(bf16x8*)&t;
+        t = make_uint4(l2[0], l2[1], l2[2], l2[3]); qlo[ks + KS / 2] = *(bf16x8*)&t;
+      }
+    }
+    // pass 1: this lane's voting row (column) and its running statistics
+    const int my_qrow = qrow_idx;
+    float m_run = -INFINITY, l_run = 0.f;
+    // pass 2: the voting rows / logsumexp of the 16 result registers (rows of S)
+    float lse_r[16];
+    int qrow_r[16];
+    if (PASS == 2) {
+      __syncthreads();       // lse2_lds ready (first round) / K tiles free (later rounds)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int cc = 32 * cb + 8 * (r / 4) + 4 * hf + (r % 4);
+        const bool ok = active && cc < a.n_cols;
+        lse_r[r] = ok ? lse2_lds[cc] : INFINITY;            // exp2(-inf) = 0 for padding columns
+        qrow_r[r] = ok ? first_obs + cc % a.w_obs : -1;
+      }
+    }
+
+#pragma unroll
+    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) {
+      const int key0 = kblock * PC_SC_KB + t * PC_SC_TILE;
+      if (key0 >= a.L) break;                               // uniform over the workgroup
+      __syncthreads();                                      // previous tile fully consumed
+      // ---- stage 64 keys: rotate in fp32, split hi / lo
+      for (int it = tid; it < PC_SC_TILE * (HALF / 8); it += PC_SC_THREADS) {
+        const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
+        const int row = min(key0 + r, a.L - 1);
+        const uint16_t* krow = a.k + (((long long)c * a.L + row) * a.n_kv_heads + g) * D;
+        const uint4 x1 = *(const uint4*)(krow + i0);
+        const uint4 x2 = *(const uint4*)(krow + HALF + i0);
+        const uint32_t aw[4] = {x1.x, x1.y, x1.z, x1.w}, bw[4] = {x2.x, x2.y, x2.z, x2.w};
+        const float2* cs = a.table + (long long)row * HALF + i0;
+        uint32_t h1[4], l1[4], h2[4], l2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+          const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
+          const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
+          uint32_t ha, la, hb, lb;
+          split_bf16(x1l * c0.x - x2l * c0.y, ha, la);
+          split_bf16(x1h * c1.x - x2h * c1.y, hb, lb);
+          h1[e] = ha | (hb << 16); l1[e] = la | (lb << 16);
+          split_bf16(x2l * c0.x + x1l * c0.y, ha, la);
+          split_bf16(x2h * c1.x + x1h * c1.y, hb, lb);
+          h2[e] = ha | (hb << 16); l2[e] = la | (lb << 16);
+        }
+        *(uint4*)(k_hi + r * KSTRIDE + i0) = make_uint4(h1[0], h1[1], h1[2], h1[3]);
+        *(uint4*)(k_lo + r * KSTRIDE + i0) = make_uint4(l1[0], l1[1], l1[2], l1[3]);
+        *(uint4*)(k_hi + r * KSTRIDE + HALF + i0) = make_uint4(h2[0], h2[1], h2[2], h2[3]);
+        *(uint4*)(k_lo + r * KSTRIDE + HALF + i0) = make_uint4(l2[0], l2[1], l2[2], l2[3]);
+      }
+      __syncthreads();
+      if (!active) continue;
+
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        floatx16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        const uint16_t* ph = k_hi + (32 * kb + n) * KSTRIDE + 8 * hf;
+        const uint16_t* pl = k_lo + (32 * kb + n) * KSTRIDE + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 kh = *(const bf16x8*)(ph + 16 * ks);
+          const bf16x8 kl = *(const bf16x8*)(pl + 16 * ks);
+          if (PASS == 1) {     // rows = keys, columns = voting rows
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qhi[ks], s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qlo[ks], s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qhi[ks], s, 0, 0, 0);
+          } else {             // rows = voting rows, columns = keys
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qhi[ks], kl, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qlo[ks], kh, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qhi[ks], kh, s, 0, 0, 0);
+          }
+        }
+        if (PASS == 1) {
+          float sv[16], tmax = -INFINITY;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * hf + (r % 4);
+            sv[r] = (key <= my_qrow) ? s[r] * a.scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, sv[r]);
+          }
+          const float m_new = fmaxf(m_run, tmax);
+          if (m_new > -INFINITY) {
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += exp2f(sv[r] - m_new);
+            l_run = l_run * exp2f(m_run - m_new) + sum;
+            m_run = m_new;
+          }
+        } else {
+          const int key = key0 + 32 * kb + n;
+          float sum = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = exp2f(s[r] * a.scale_log2 - lse_r[r]);
+            sum += (key <= qrow_r[r]) ? p : 0.f;
+          }
+          tok_acc[t][kb] += sum;
+        }
+      }
+    }
+
+    if (PASS == 1 && active) {
+      const float m_o = __shfl_xor(m_run, 32), l_o = __shfl_xor(l_run, 32);
+      const float M = fmaxf(m_run, m_o);
+      float l = 0.f;
+      if (l_run > 0.f) l += l_run * exp2f(m_run - M);
+      if (l_o > 0.f) l += l_o * exp2f(m_o - M);
+      const int cc = 32 * cb + n;
+      if (hf == 0 && cc < a.n_cols)
+        a.ml[ml_base + (long long)kblock * a.n_cols + cc] = make_float2(M, l);
+    }
+  }
+
+  if (PASS == 2) {
+#pragma unroll
+    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const float x = tok_acc[t][kb] + __shfl_xor(tok_acc[t][kb], 32);
+        if (hf == 0) tok_part[wave][t * PC_SC_TILE + 32 * kb + n] = x;
+      }
+    __syncthreads();
+    const int key = kblock * PC_SC_KB + tid;
+    if (key < a.w) {
+      float x = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < PC_SC_WAVES; ++wv) x += tok_part[wv][tid];
+      a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = x;
+    }
+  }
+}
+
+// chunk_score[c] = sum of tok_score[c, :, :], summed in a fixed order.
+__global__ __launch_bounds__(256) void chunk_score_kernel(const float* __restrict__ tok_score,
+                                                          float* __restrict__ chunk_score,
+                                                          long long per_chunk) {
+  __shared__ float red[256];
+  const float* src = tok_score + (long long)blockIdx.x * per_chunk;
+  float x = 0.f;
+  for (long long i = threadIdx.x; i < per_chunk; i += 256) x += src[i];
+  red[threadIdx.x] = x;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) chunk_score[blockIdx.x] = red[0];
+}
+
+size_t pc_scores_ml_bytes(const pc_shape* s) {
+  const int L = s->chunk_len + s->query_len;
+  const int n_kb = (L + PC_SC_KB - 1) / PC_SC_KB;
+  const int n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
+  return (size_t)s->n_chunks * s->n_kv_heads * n_kb * n_cols * sizeof(float2);
+}
+
+int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const float2* table,
+                     void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st) {
+  PcScoreArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.table = table;
+  a.ml = (float2*)ml_ws; a.tok_score = tok_score;
+  a.L = s->chunk_len + s->query_len; a.w = s->chunk_len; a.w_obs = s->obs_window;
+  a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads;
+  a.n_kb = (a.L + PC_SC_KB - 1) / PC_SC_KB;
+  a.n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
+  const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+  a.scale_log2 = scale * PC_SC_LOG2E;
+  dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
+  if (s->head_dim == 128) {
+    hipLaunchKernelGGL((scores_kernel<128, 1>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((scores_kernel<128, 2>), grid, block, 0, st, a);
+  } else {
+    hipLaunchKernelGGL((scores_kernel<64, 1>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((scores_kernel<64, 2>), grid, block, 0, st, a);
+  }
+  PC_LAUNCH_CHECK();
+  if (chunk_score) {
+    hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(256), 0, st, tok_score,
+                       chunk_score, (long long)s->n_kv_heads * s->chunk_len);
+    PC_LAUNCH_CHECK();
+  }
+  return PC_OK;
+}

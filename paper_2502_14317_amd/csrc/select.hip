@@ -1,0 +1,140 @@
+// Top-k selection of chunks (Eq. 3-4: a fixed number of best chunks) and of tokens per KV
+// head (Eq. 7), under the total order (score descending, index ascending): of equal scores
+// the lower index wins.  Scores are mapped to unsigned keys whose integer order is the float
+// order, so every comparison is exact integer work.
+#include "pc_common.h"
+
+// ------------------------------------------------------------------------------------------
+// Chunks: n <= 4096.  One workgroup; rank by counting.  rank(i) = #{j : key_j > key_i or
+// (key_j == key_i and j < i)}; item i is kept iff rank(i) < k and lands at out[rank(i)].
+__global__ __launch_bounds__(256) void select_chunks_kernel(const float* __restrict__ score, int n,
+                                                            int k, int32_t* __restrict__ out_idx,
+                                                            float* __restrict__ out_score) {
+  __shared__ uint32_t keys[4096];
+  for (int i = threadIdx.x; i < n; i += blockDim.x) keys[i] = pc_order_key(score[i]);
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const uint32_t ki = keys[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t kj = keys[j];
+      rank += (kj > ki) || (kj == ki && j < i);
+    }
+    if (rank < k) {
+      out_idx[rank] = i;
+      if (out_score) out_score[rank] = score[i];
+    }
+  }
+}
+
+int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, float* out_score,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(select_chunks_kernel, dim3(1), dim3(256), 0, st, score, n, k, out_idx,
+                     out_score);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Tokens: one workgroup per (selected chunk, KV head).  The n keys sit in LDS.
+//  1. Radix select, 4 passes of 8 bits from the top: after the passes T is the k-th largest
+//     key and `need_eq` the number of keys equal to T that still fit (1 <= need_eq).
+//  2. Ordered compaction: each wavefront owns a contiguous index range; it counts its keys
+//     above T and equal to T, the counts are prefix-summed over wavefronts, and a second sweep
+//     emits index i iff key_i > T, or key_i == T and fewer than need_eq equal keys precede it.
+//     Output is ascending by construction and ties go to the lower index.
+#define PC_SEL_THREADS 512
+#define PC_SEL_WAVES (PC_SEL_THREADS / PC_WAVE)
+
+__global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
+    const float* __restrict__ tok_score, const int32_t* __restrict__ chunk_idx, int n_kv_heads,
+    int n, int k, int32_t* __restrict__ out_idx) {
+  extern __shared__ uint32_t keys[];   // n
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_bin, sh_need;
+  __shared__ uint32_t wave_gt[PC_SEL_WAVES], wave_eq[PC_SEL_WAVES];
+
+  const int s = blockIdx.x / n_kv_heads;
+  const int g = blockIdx.x % n_kv_heads;
+  const int c = chunk_idx ? chunk_idx[s] : s;
+  const float* src = tok_score + ((long long)c * n_kv_heads + g) * n;
+  int32_t* dst = out_idx + (long long)blockIdx.x * k;
+
+  for (int i = threadIdx.x; i < n; i += PC_SEL_THREADS) keys[i] = pc_order_key(src[i]);
+
+  uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += PC_SEL_THREADS) {
+      const uint32_t key = keys[i];
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t above = 0;
+      int b = 255;
+      for (; b > 0; --b) {
+        const uint32_t h = hist[b];
+        if (above + h >= need) break;
+        above += h;
+      }
+      sh_bin = (uint32_t)b;
+      sh_need = need - above;
+    }
+    __syncthreads();
+    prefix |= sh_bin << shift;
+    mask |= 255u << shift;
+    need = sh_need;
+  }
+  const uint32_t T = prefix;       // k-th largest key
+  const uint32_t need_eq = need;   // how many keys equal to T are admitted
+
+  const int wave = threadIdx.x / PC_WAVE, lane = threadIdx.x % PC_WAVE;
+  const int per_wave = ((n + PC_SEL_WAVES - 1) / PC_SEL_WAVES + PC_WAVE - 1) / PC_WAVE * PC_WAVE;
+  const int begin = wave * per_wave;
+  const int end = min(n, begin + per_wave);
+
+  uint32_t cnt_gt = 0, cnt_eq = 0;
+  for (int i0 = begin; i0 < end; i0 += PC_WAVE) {
+    const int i = i0 + lane;
+    const uint32_t key = (i < end) ? keys[i] : 0u;
+    const bool gt = (i < end) && key > T, eq = (i < end) && key == T;
+    cnt_gt += (uint32_t)__popcll(__ballot(gt));
+    cnt_eq += (uint32_t)__popcll(__ballot(eq));
+  }
+  if (lane == 0) { wave_gt[wave] = cnt_gt; wave_eq[wave] = cnt_eq; }
+  __syncthreads();
+  uint32_t base_gt = 0, base_eq = 0;
+  for (int w = 0; w < wave; ++w) { base_gt += wave_gt[w]; base_eq += wave_eq[w]; }
+
+  for (int i0 = begin; i0 < end; i0 += PC_WAVE) {
+    const int i = i0 + lane;
+    const uint32_t key = (i < end) ? keys[i] : 0u;
+    const bool gt = (i < end) && key > T, eq = (i < end) && key == T;
+    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const uint32_t gt_before = base_gt + (uint32_t)__popcll(bg & below);
+    const uint32_t eq_before = base_eq + (uint32_t)__popcll(be & below);
+    if (gt || (eq && eq_before < need_eq)) {
+      const uint32_t pos = gt_before + min(eq_before, need_eq);
+      dst[pos] = i;
+    }
+    base_gt += (uint32_t)__popcll(bg);
+    base_eq += (uint32_t)__popcll(be);
+  }
+}
+
+int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
+                            int n_kv_heads, int chunk_len, int k, int32_t* out_idx,
+                            hipStream_t st) {
+  const size_t lds = (size_t)chunk_len * sizeof(uint32_t);
+  if (lds > 48 * 1024) {
+    PC_HIP_TRY(hipFuncSetAttribute((const void*)select_tokens_kernel,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  }
+  hipLaunchKernelGGL(select_tokens_kernel, dim3(n_sel * n_kv_heads), dim3(PC_SEL_THREADS), lds, st,
+                     tok_score, chunk_idx, n_kv_heads, chunk_len, k, out_idx);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}

@@ -1,0 +1,85 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_14317_amd as pc
+from paper_2502_14317_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "parallelcomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = pc.lib()
+    names = _declared_symbols()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(L, name), name
+    assert set(names) == set(binding.SYMBOLS)
+    assert L.pc_version().startswith(b"parallelcomp")
+
+
+def test_status_strings():
+    L = pc.lib()
+    for code in range(-5, 1):
+        assert L.pc_status_string(code)
+    assert b"unknown" in L.pc_status_string(-99)
+
+
+def test_null_and_shape_errors_before_any_gpu_work():
+    L = pc.lib()
+    one = ctypes.c_void_p(256)            # never dereferenced: validation fails first
+    # select chunks
+    assert L.pc_select_chunks_topk(None, 4, 2, one, None, None) == -1
+    assert L.pc_select_chunks_topk(one, 4, 5, one, None, None) == -2
+    assert L.pc_select_chunks_topk(one, 0, 0, one, None, None) == -2
+    assert L.pc_select_chunks_topk(one, 5000, 1, one, None, None) == -2
+    # select tokens
+    assert L.pc_select_tokens_topk(None, None, 1, 1, 8, 2, one, None) == -1
+    assert L.pc_select_tokens_topk(one, None, 1, 1, 8, 9, one, None) == -2
+    assert L.pc_select_tokens_topk(one, None, 1, 1, 40000, 2, one, None) == -2
+    # gather
+    assert L.pc_gather_kv(one, one, None, None, 1, 1, 8, 1, 1, 2, 128, one, one, None) == -1
+    assert L.pc_gather_kv(one, one, None, one, 1, 1, 8, 1, 1, 2, 96, one, one, None) == -2
+    # prefill
+    good = pc.make_shape(2, 64, 16, 8, 2, 128, 8, 1e4)
+    assert L.pc_chunk_prefill_attn(None, one, one, one, one, one, None, None, None, one, 1 << 30, None) == -1
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), None, one, one, one, one, None, None, None, one, 1 << 30, None) == -1
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, None, one, 16, None) == -3
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, None, None, 0, None) == -3
+    for field, value in (("head_dim", 96), ("n_q_heads", 7), ("n_chunks", 0), ("rope_base", 0.5)):
+        bad = pc.make_shape(2, 64, 16, 8, 2, 128, 8, 1e4)
+        setattr(bad, field, value)
+        assert L.pc_chunk_prefill_attn(ctypes.byref(bad), one, one, one, one, one, None, None, None, one, 1 << 30, None) == -2
+        assert pc.pc_chunk_prefill_workspace_bytes(bad) == 0
+    bad = pc.make_shape(2, 64, 16, 8, 2, 128, 100, 1e4)     # obs_window too large
+    assert L.pc_chunk_query_scores(ctypes.byref(bad), one, one, one, None, one, 1 << 30, None) == -2
+    # chunk_score without tok_score
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, one, one, 1 << 30, None) == -1
+    # parallel attention
+    args = (1, 1, 2, 64, 8, 2, 128, -1, 1e4, 0.0)
+    assert L.pc_parallel_attn(None, one, one, None, None, None, *args, one, None, one, 1 << 30, None) == -1
+    assert L.pc_parallel_attn(one, one, one, None, one, None, *args, one, None, one, 1 << 30, None) == -1
+    assert L.pc_parallel_attn(one, one, one, None, None, None, *args, one, None, one, 8, None) == -3
+    bad_args = (1, 1, 2, 64, 8, 3, 128, -1, 1e4, 0.0)
+    assert L.pc_parallel_attn(one, one, one, None, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
+
+
+def test_workspace_sizes_are_positive_and_monotone():
+    s1 = pc.make_shape(2, 64, 16, 8, 2, 128, 8, 1e4)
+    s2 = pc.make_shape(4, 64, 16, 8, 2, 128, 8, 1e4)
+    assert 0 < pc.pc_chunk_prefill_workspace_bytes(s1) < pc.pc_chunk_prefill_workspace_bytes(s2)
+    assert pc.pc_chunk_query_scores_workspace_bytes(s1) > 0
+    a = pc.pc_parallel_attn_workspace_bytes(1, 1, 4, 256, 8, 2, 128, 0)
+    b = pc.pc_parallel_attn_workspace_bytes(2, 1, 4, 256, 8, 2, 128, 0)
+    assert 0 < a < b
+    assert pc.pc_parallel_attn_workspace_bytes(1, 64, 4, 256, 8, 2, 128, 1) > a
