@@ -142,6 +142,24 @@ size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_se
                                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                         int32_t has_self);
 
+/* ---- per-kernel timing (measurement aid; off by default) ------------------------------------
+ * While enabled, every kernel the library launches is bracketed by a pair of HIP events recorded
+ * on the stream of the call.  pc_profile_begin resets the record list (at most 4096 records are
+ * kept, later launches are not recorded); pc_profile_end stops recording; pc_profile_get waits
+ * for record i and returns its kernel id (pc_kernel_id) and elapsed milliseconds.
+ * Not thread-safe; meant for one benchmarking thread. */
+typedef enum pc_kernel_id {
+  PC_KERNEL_ROPE_TABLE = 0, PC_KERNEL_KV_PREPASS = 1, PC_KERNEL_FLASH = 2, PC_KERNEL_SCORES_P1 = 3,
+  PC_KERNEL_SCORES_P2 = 4, PC_KERNEL_CHUNK_SCORE = 5, PC_KERNEL_SELECT_CHUNKS = 6,
+  PC_KERNEL_SELECT_TOKENS = 7, PC_KERNEL_GATHER = 8, PC_KERNEL_ROPE_Q = 9, PC_KERNEL_DECODE = 10,
+  PC_KERNEL_MERGE = 11, PC_KERNEL_COUNT = 12
+} pc_kernel_id;
+int         pc_profile_begin(void);
+int         pc_profile_end(void);
+int         pc_profile_count(void);
+int         pc_profile_get(int i, int* kernel_id, float* ms);
+const char* pc_kernel_name(int kernel_id);
+
 /* ---- housekeeping -------------------------------------------------------------------------- */
 const char* pc_status_string(int status);   /* static string, never NULL                       */
 int         pc_last_hip_error(void);        /* hipError_t of the last PC_ERR_HIP on this thread */

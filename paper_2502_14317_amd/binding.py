@@ -18,7 +18,8 @@ SYMBOLS = [
     "pc_chunk_prefill_attn", "pc_chunk_prefill_workspace_bytes", "pc_chunk_query_scores",
     "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
     "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
-    "pc_last_hip_error", "pc_version",
+    "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
+    "pc_profile_get", "pc_kernel_name",
 ]
 
 
@@ -75,6 +76,9 @@ def lib():
     L.pc_last_hip_error.restype = c_int
     L.pc_version.argtypes = []
     L.pc_version.restype = c_char_p
+    L.pc_profile_get.argtypes = [c_int, POINTER(c_int), POINTER(c_float)]
+    L.pc_kernel_name.argtypes = [c_int]
+    L.pc_kernel_name.restype = c_char_p
     _lib = L
     return L
 
@@ -162,3 +166,22 @@ def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t,
                                   _ptr(v_self), batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
                                   head_dim, q_pos0, rope_base, softmax_scale, _ptr(out),
                                   _ptr(lse_out), p, n, _stream()), "pc_parallel_attn")
+
+
+def pc_profile_begin():
+    _check(lib().pc_profile_begin(), "pc_profile_begin")
+
+
+def pc_profile_end():
+    _check(lib().pc_profile_end(), "pc_profile_end")
+
+
+def pc_profile_records():
+    """[(kernel name, milliseconds)] of every kernel launched between begin and end."""
+    L = lib()
+    out = []
+    kid, ms = c_int(0), c_float(0.0)
+    for i in range(L.pc_profile_count()):
+        _check(L.pc_profile_get(i, ctypes.byref(kid), ctypes.byref(ms)), "pc_profile_get")
+        out.append((L.pc_kernel_name(kid.value).decode(), float(ms.value)))
+    return out

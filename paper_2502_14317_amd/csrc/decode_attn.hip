@@ -328,6 +328,7 @@ int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int 
                      int pos0, float base, hipStream_t st) {
   const long long n_pairs = n_rows * (D / 2);
   if (n_pairs == 0) return PC_OK;
+  PcProfScope prof(PC_KERNEL_ROPE_Q, st);
   hipLaunchKernelGGL(rope_q_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)q, (uint16_t*)q_rot, n_pairs, n_q, n_heads, D, pos0,
                      log((double)base));
@@ -341,6 +342,7 @@ static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStre
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(PC_DEC_WAVES * PC_WAVE);
+  PcProfScope prof(PC_KERNEL_DECODE, st);
   if (nq_pad == 4) hipLaunchKernelGGL((decode_attn_kernel<D, 4>), grid, block, 0, st, a);
   else if (nq_pad == 8) hipLaunchKernelGGL((decode_attn_kernel<D, 8>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((decode_attn_kernel<D, 16>), grid, block, 0, st, a);
@@ -386,6 +388,7 @@ int pc_launch_merge(const float* part_o, const float* part_lse, const void* q_ro
   const long long blocks = (long long)batch * n_q * n_q_heads;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
+  PcProfScope prof(PC_KERNEL_MERGE, st);
   if (head_dim == 128) hipLaunchKernelGGL(merge_kernel<128>, dim3((unsigned)blocks), dim3(128), 0, st, a);
   else hipLaunchKernelGGL(merge_kernel<64>, dim3((unsigned)blocks), dim3(64), 0, st, a);
   PC_LAUNCH_CHECK();

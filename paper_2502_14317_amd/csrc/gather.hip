@@ -62,6 +62,7 @@ int pc_launch_gather(const void* k_src, const void* v_src, const int32_t* chunk_
   const long long blocks = (n_dst_rows + rows_per_block - 1) / rows_per_block;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(256);
+  PcProfScope prof(PC_KERNEL_GATHER, st);
   if (lanes == 16) {
     hipLaunchKernelGGL(gather_kv_kernel<16>, grid, block, 0, st, (const uint4*)k_src,
                        (const uint4*)v_src, chunk_idx, tok_idx, (uint4*)k_dst, (uint4*)v_dst,

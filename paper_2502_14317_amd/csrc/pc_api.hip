@@ -22,6 +22,48 @@ extern "C" const char* pc_status_string(int status) {
   }
 }
 
+// ---------------------------------------------------------------------------- profiling
+#define PC_PROF_MAX 4096
+static bool g_prof_on = false;
+static int g_prof_n = 0;
+static int g_prof_created = 0;
+static hipEvent_t g_prof_ev[PC_PROF_MAX][2];
+static int g_prof_id[PC_PROF_MAX];
+
+PcProfScope::PcProfScope(int kernel_id, hipStream_t stream) : slot(-1), st(stream) {
+  if (!g_prof_on || g_prof_n >= PC_PROF_MAX) return;
+  if (g_prof_n >= g_prof_created) {
+    if (hipEventCreate(&g_prof_ev[g_prof_n][0]) != hipSuccess) return;
+    if (hipEventCreate(&g_prof_ev[g_prof_n][1]) != hipSuccess) return;
+    g_prof_created = g_prof_n + 1;
+  }
+  slot = g_prof_n++;
+  g_prof_id[slot] = kernel_id;
+  (void)hipEventRecord(g_prof_ev[slot][0], st);
+}
+PcProfScope::~PcProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof_ev[slot][1], st);
+}
+
+extern "C" int pc_profile_begin(void) { g_prof_n = 0; g_prof_on = true; return PC_OK; }
+extern "C" int pc_profile_end(void) { g_prof_on = false; return PC_OK; }
+extern "C" int pc_profile_count(void) { return g_prof_n; }
+extern "C" int pc_profile_get(int i, int* kernel_id, float* ms) {
+  if (!kernel_id || !ms) return PC_ERR_NULL;
+  if (i < 0 || i >= g_prof_n) return PC_ERR_SHAPE;
+  PC_HIP_TRY(hipEventSynchronize(g_prof_ev[i][1]));
+  PC_HIP_TRY(hipEventElapsedTime(ms, g_prof_ev[i][0], g_prof_ev[i][1]));
+  *kernel_id = g_prof_id[i];
+  return PC_OK;
+}
+extern "C" const char* pc_kernel_name(int id) {
+  static const char* names[PC_KERNEL_COUNT] = {
+      "rope_table_kernel", "kv_prepass_kernel", "flash_fwd_kernel", "scores_kernel<1>",
+      "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
+      "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel"};
+  return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
+}
+
 static const size_t kAlign = 256;
 
 static int check_shape(const pc_shape* s) {

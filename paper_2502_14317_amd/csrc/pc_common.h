@@ -22,6 +22,14 @@ void pc_set_hip_error(int err);
   } while (0)
 #define PC_LAUNCH_CHECK() PC_HIP_TRY(hipGetLastError())
 
+// Brackets the kernel launches of one scope with HIP events when profiling is enabled.
+struct PcProfScope {
+  int slot;
+  hipStream_t st;
+  PcProfScope(int kernel_id, hipStream_t stream);
+  ~PcProfScope();
+};
+
 static inline size_t pc_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline bool pc_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 

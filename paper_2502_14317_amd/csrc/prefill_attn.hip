@@ -46,6 +46,7 @@ __global__ void rope_table_kernel(float2* __restrict__ table, int n_pos, int D, 
 
 int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st) {
   const int n = n_pos * (head_dim / 2);
+  PcProfScope prof(PC_KERNEL_ROPE_TABLE, st);
   hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, table, n_pos,
                      head_dim, log((double)base));
   PC_LAUNCH_CHECK();
@@ -121,6 +122,7 @@ int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void
                          void* v_t, int n_seq, int L, int Lp, int n_kv_heads, int head_dim,
                          hipStream_t st) {
   dim3 grid(n_seq, n_kv_heads, Lp / 64), block(256);
+  PcProfScope prof(PC_KERNEL_KV_PREPASS, st);
   if (head_dim == 128)
     hipLaunchKernelGGL(kv_prepass_kernel<128>, grid, block, 0, st, (const uint16_t*)k,
                        (const uint16_t*)v, table, (uint16_t*)k_rope, (uint16_t*)v_t, L, Lp,
@@ -401,6 +403,7 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   const long long blocks = (groups + 7) / 8 * per_group * 8;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
+  PcProfScope prof(PC_KERNEL_FLASH, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES, st, a);
   PC_LAUNCH_CHECK();
   return PC_OK;

@@ -281,15 +281,19 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const floa
   const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   a.scale_log2 = scale * PC_SC_LOG2E;
   dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
-  if (s->head_dim == 128) {
-    hipLaunchKernelGGL((scores_kernel<128, 1>), grid, block, 0, st, a);
-    hipLaunchKernelGGL((scores_kernel<128, 2>), grid, block, 0, st, a);
-  } else {
-    hipLaunchKernelGGL((scores_kernel<64, 1>), grid, block, 0, st, a);
-    hipLaunchKernelGGL((scores_kernel<64, 2>), grid, block, 0, st, a);
+  {
+    PcProfScope prof(PC_KERNEL_SCORES_P1, st);
+    if (s->head_dim == 128) hipLaunchKernelGGL((scores_kernel<128, 1>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((scores_kernel<64, 1>), grid, block, 0, st, a);
+  }
+  {
+    PcProfScope prof(PC_KERNEL_SCORES_P2, st);
+    if (s->head_dim == 128) hipLaunchKernelGGL((scores_kernel<128, 2>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((scores_kernel<64, 2>), grid, block, 0, st, a);
   }
   PC_LAUNCH_CHECK();
   if (chunk_score) {
+    PcProfScope prof(PC_KERNEL_CHUNK_SCORE, st);
     hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(256), 0, st, tok_score,
                        chunk_score, (long long)s->n_kv_heads * s->chunk_len);
     PC_LAUNCH_CHECK();

@@ -29,6 +29,7 @@ __global__ __launch_bounds__(256) void select_chunks_kernel(const float* __restr
 
 int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, float* out_score,
                             hipStream_t st) {
+  PcProfScope prof(PC_KERNEL_SELECT_CHUNKS, st);
   hipLaunchKernelGGL(select_chunks_kernel, dim3(1), dim3(256), 0, st, score, n, k, out_idx,
                      out_score);
   PC_LAUNCH_CHECK();
@@ -133,6 +134,7 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
     PC_HIP_TRY(hipFuncSetAttribute((const void*)select_tokens_kernel,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   }
+  PcProfScope prof(PC_KERNEL_SELECT_TOKENS, st);
   hipLaunchKernelGGL(select_tokens_kernel, dim3(n_sel * n_kv_heads), dim3(PC_SEL_THREADS), lds, st,
                      tok_score, chunk_idx, n_kv_heads, chunk_len, k, out_idx);
   PC_LAUNCH_CHECK();
