@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the ParallelComp hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: chunk-batched local
+attention with chunk-local RoPE and the fused query-score reduction, chunk top-k, per-head
+token top-k, KV compaction gather, and the query's parallel attention over the kept KV.
+Inputs are resident in HBM before the timed region.  One JSON line is printed:
+  value      context tokens per second per layer for the whole step
+  roofline   the dominant kernel (flash_fwd_kernel) against the bf16 MFMA peak, its duration
+             measured with HIP events recorded inside the library on the launch stream
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload
+  secondary  the HBM-bound kernels (split-KV decode attention, KV gather) on the decode config
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15      # MI355X dense bf16 MFMA
+PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# per workload; see profiles/.  None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def flash_flops(cfg):
+    """Algorithmic flops of the causal local attention: QK^T and PV on the causal pairs only."""
+    L = cfg.seq_len
+    return 4.0 * cfg.head_dim * (L * (L + 1) / 2.0) * cfg.n_q_heads * cfg.n_chunks
+
+
+def cpu_baseline(cfg, q, k, v, n_rows_sample=768, n_grows_sample=128):
+    """Time the oracle (as it stands) on a bounded sample and scale to the whole step.
+
+    Sample: chunk 0 only; local attention on n_rows_sample evenly spaced rows (each row costs
+    the same in the oracle: it evaluates all L logits and masks), scaled by L / n_rows_sample;
+    the score reduction, token selection and gather of that chunk in full; global attention on
+    n_grows_sample evenly spaced query rows scaled by w_q / n_grows_sample.  Every chunk costs
+    the same, so the step is C times the chunk part plus the global part."""
+    import numpy as np
+    import oracle
+    from workloads import bf16_bits_to_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    L, w = cfg.seq_len, cfg.chunk_len
+    qf, kf, vf = bf16_bits_to_f64(q[0]), bf16_bits_to_f64(k[0]), bf16_bits_to_f64(v[0])
+    pos = np.arange(L)
+    t0 = time.perf_counter()
+    q_rot = oracle.rope(qf, pos, cfg.rope_base)
+    k_rot = oracle.rope(kf, pos, cfg.rope_base)
+    t_rope = time.perf_counter() - t0
+    rows = np.linspace(0, L - 1, n_rows_sample).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.local_attention(q_rot, k_rot, vf, rows=rows)
+    t_attn = (time.perf_counter() - t0) * (L / float(n_rows_sample))
+    t0 = time.perf_counter()
+    tok, _ = oracle.query_scores(q_rot, k_rot, w, cfg.obs_window, cfg.n_kv_heads)
+    t_score = time.perf_counter() - t0
+    t_chunk = t_rope + t_attn + t_score
+    t_global = 0.0
+    if cfg.keep_chunks > 0:
+        t0 = time.perf_counter()
+        tidx = oracle.select_tokens(tok[None], cfg.keep_tokens)
+        kc, vc = oracle.gather_kv(k_rot[None], vf[None], np.zeros(1, dtype=np.int64), tidx)
+        t_sel = (time.perf_counter() - t0) * cfg.keep_chunks
+        kc = np.repeat(kc, cfg.keep_chunks, axis=0)
+        vc = np.repeat(vc, cfg.keep_chunks, axis=0)
+        grows = np.linspace(0, cfg.query_len - 1, n_grows_sample).astype(np.int64)
+        t0 = time.perf_counter()
+        # rows of the query block: the self segment of a sampled row t holds t + 1 keys; the
+        # context part dominates, so sampled rows are evaluated without the self segment
+        oracle.global_attention_merged(q_rot[w:][grows], kc, vc)
+        t_global = t_sel + (time.perf_counter() - t0) * (cfg.query_len / float(n_grows_sample))
+    total = cfg.n_chunks * t_chunk + t_global
+    return {"value": cfg.context_tokens / total, "unit": "tokens/s/layer", "cores": int(cores),
+            "kind": "oracle",
+            "sample": (f"chunk 0 of {cfg.n_chunks}: RoPE in full, local attention on "
+                       f"{n_rows_sample} of {L} rows x L/{n_rows_sample}, scores/selection/gather "
+                       f"in full, global attention on {n_grows_sample} of {cfg.query_len} rows "
+                       f"x {cfg.query_len}/{n_grows_sample}; step = {cfg.n_chunks} x chunk + global; "
+                       f"est. {total:.1f} s per step")}
+
+
+def bench_secondary(pc, torch, steps, warmup):
+    """HBM-bound kernels on the decode config: split-KV attention + merge, and the KV gather."""
+    from workloads import CFG4
+    cfg = CFG4
+    g = torch.Generator(device="cuda").manual_seed(2502)
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf = torch.bfloat16
+    out = {}
+    q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(B):
+        kc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+        vc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    o = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(B, 1, S, kt, Hq, Hkv, D, 0))
+    run = lambda: pc.pc_parallel_attn(q, kc, vc, None, None, None, B, 1, S, kt, Hq, Hkv, D, -1,
+                                      1.0e4, 0.0, o, None, ws)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    pc.pc_profile_end()
+    recs = pc.pc_profile_records()
+    k_ms = [ms for name, ms in recs if name == "decode_attn_kernel"]
+    k_avg = sum(k_ms) / len(k_ms) * 1e-3
+    kv_bytes = 2.0 * kc.numel() * 2
+    out["decode_attn"] = {
+        "workload": cfg.name, "ms_per_step": dt * 1e3, "tokens_per_s_per_layer": B / dt,
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": kv_bytes / k_avg / 1e9,
+                     "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": kv_bytes / k_avg / PEAK_HBM_BYTES,
+                     "kernel_ms": k_avg * 1e3, "traffic": None}}
+    del kc, vc
+    torch.cuda.empty_cache()
+    # gather: source [B, S, rows, H_kv, D], sorted random k_t-subsets of the rows
+    R = cfg.src_rows
+    ks = torch.empty((B, S, R, Hkv, D), dtype=bf, device="cuda")
+    for b in range(B):
+        ks[b] = (torch.randn(ks.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    vs = ks.flip(0).contiguous()
+    idx = torch.rand((B, S, Hkv, R), generator=g, device="cuda").argsort(dim=-1)[..., :kt]
+    idx = idx.sort(dim=-1).values.to(torch.int32).contiguous()
+    kd = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vd = torch.empty_like(kd)
+    run = lambda: pc.pc_gather_kv(ks, vs, None, idx, B, S, R, S, Hkv, kt, D, kd, vd)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    k_ms = [ms for name, ms in pc.pc_profile_records() if name == "gather_kv_kernel"]
+    k_avg = sum(k_ms) / len(k_ms) * 1e-3
+    rows = B * S * Hkv * kt
+    g_bytes = 2.0 * (rows * D * 2 * 2) + rows * 4          # K and V rows read + written, + indices
+    out["gather_kv"] = {
+        "workload": cfg.name, "roofline": {"bound": "hbm", "kernel": "gather_kv_kernel",
+                                           "achieved": g_bytes / k_avg / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
+                                           "unit": "GB/s", "frac": g_bytes / k_avg / PEAK_HBM_BYTES,
+                                           "kernel_ms": k_avg * 1e3, "traffic": None}}
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg1_llama3_8b_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="time only the chunk prefill + score reduction (the stress config's step)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2502_14317_amd as pc
+    from paper_2502_14317_amd.layer import ParallelCompLayer
+    from workloads import PREFILL_CONFIGS, prefill_inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    pc.lib()
+    cfg = PREFILL_CONFIGS[args.workload]
+    prefill_only = args.prefill_only or cfg.keep_chunks == 0
+    t0 = time.perf_counter()
+    q, k, v = prefill_inputs(cfg, threads=min(16, os.cpu_count() or 8))
+    print(f"[bench] generated {cfg.name} inputs in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    to_dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
+                              cfg.n_kv_heads, cfg.head_dim, cfg.obs_window, cfg.rope_base,
+                              0 if prefill_only else cfg.keep_chunks, cfg.keep_tokens)
+    step = (lambda: layer.chunk_prefill(qd, kd, vd, True)) if prefill_only else (lambda: layer.forward(qd, kd, vd))
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pc.pc_profile_end()
+    recs = pc.pc_profile_records()
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    # flash_fwd_kernel runs once per step for the local attention and (full path) twice more in
+    # the global attention; the local-attention launch is the first one of every step
+    n_flash = len(per_kernel["flash_fwd_kernel"]) // args.steps
+    flash_ms = per_kernel["flash_fwd_kernel"][0::n_flash]
+    flash_avg = sum(flash_ms) / len(flash_ms) * 1e-3
+    flops = flash_flops(cfg)
+    ms_per_step = elapsed / args.steps * 1e3
+    breakdown = {}
+    for name, lst in per_kernel.items():
+        breakdown[name] = round(sum(lst) / args.steps, 4)        # ms per step, all launches
+    result = {
+        "metric": "chunk-prefill tokens/s/layer at 128K ctx (Llama-3-8B shape) + % bf16 MFMA peak",
+        "value": cfg.context_tokens / (elapsed / args.steps),
+        "unit": "tokens/s/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_chunks": cfg.n_chunks, "chunk_len": cfg.chunk_len,
+                   "query_len": cfg.query_len, "n_q_heads": cfg.n_q_heads, "n_kv_heads": cfg.n_kv_heads,
+                   "head_dim": cfg.head_dim, "keep_chunks": cfg.keep_chunks, "keep_tokens": cfg.keep_tokens,
+                   "obs_window": cfg.obs_window,
+                   "step": "chunk prefill + scores" if prefill_only else
+                           "chunk prefill + scores + chunk/token top-k + gather + parallel attention"},
+        "roofline": {"bound": "mfma", "kernel": "flash_fwd_kernel", "achieved": flops / flash_avg / 1e12,
+                     "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
+                     "frac": flops / flash_avg / PEAK_BF16_FLOPS, "kernel_ms": flash_avg * 1e3,
+                     "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(cfg.name)},
+        "kernel_ms_per_step": breakdown,
+    }
+    print(f"[bench] {cfg.name}: {ms_per_step:.3f} ms/step, flash {flash_avg * 1e3:.3f} ms "
+          f"({result['roofline']['frac'] * 100:.1f}% of bf16 MFMA peak)", file=sys.stderr, flush=True)
+    del layer
+    torch.cuda.empty_cache()
+    if not args.no_secondary:
+        del qd, kd, vd
+        torch.cuda.empty_cache()
+        result["secondary"] = bench_secondary(pc, torch, max(args.steps, 5), args.warmup)
+        print(f"[bench] secondary done", file=sys.stderr, flush=True)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
