@@ -8,6 +8,8 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte register quad
+
 #define PC_WAVE 64
 
 // ---------------------------------------------------------------- host-side error plumbing
@@ -45,8 +47,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
 }
+// two fp32 -> packed bf16 pair (round-to-nearest-even) in one v_cvt_pk_bf16_f32
+typedef __bf16 pc_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float pc_f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+  pc_f32x2 v = {lo, hi};
+  pc_bf16x2 r = __builtin_convertvector(v, pc_bf16x2);
+  return *(uint32_t*)&r;
 }
 
 // fp32 score -> uint32 key whose unsigned order is the float order; NaN -> 0 (below everything),

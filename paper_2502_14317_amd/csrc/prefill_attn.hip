@@ -230,40 +230,40 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     }
   }
 
-  // ---- cooperative tile loads: global -> registers -> LDS
-  constexpr int K_LD = (PC_FA_BN * D / 8) / PC_FA_THREADS;     // 16-byte pieces per thread
+  // ---- cooperative tile loads: global -> registers -> LDS (16-byte pieces)
+  constexpr int K_LD = (PC_FA_BN * D / 8) / PC_FA_THREADS;
   constexpr int V_LD = (D * PC_FA_BN / 8) / PC_FA_THREADS;
-  uint4 kreg[K_LD], vreg[V_LD];
-  auto load_tile = [&](int t) {
-    const int key0 = key_begin + t * PC_FA_BN;
+  u32x4 kreg[K_LD], vreg[V_LD];
+  int k_ld_row[K_LD], k_ld_c8[K_LD], v_ld_d[V_LD], v_ld_c8[V_LD];
 #pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      const int piece = tid + i * PC_FA_THREADS;
-      const int r = piece / (D / 8), c8 = (piece % (D / 8)) * 8;
-      const int key = min(key0 + r, a.n_keys - 1);
-      kreg[i] = *(const uint4*)(kbase + (long long)key * a.k_row_stride + c8);
-    }
+  for (int i = 0; i < K_LD; ++i) {
+    const int piece = tid + i * PC_FA_THREADS;
+    k_ld_row[i] = piece / (D / 8);
+    k_ld_c8[i] = (piece % (D / 8)) * 8;
+  }
 #pragma unroll
-    for (int i = 0; i < V_LD; ++i) {
-      const int piece = tid + i * PC_FA_THREADS;
-      const int d = piece / (PC_FA_BN / 8), c8 = (piece % (PC_FA_BN / 8)) * 8;
-      vreg[i] = *(const uint4*)(vtbase + (long long)d * a.vt_d_stride + key0 + c8);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      const int piece = tid + i * PC_FA_THREADS;
-      const int r = piece / (D / 8), c8 = (piece % (D / 8)) * 8;
-      *(uint4*)(k_lds(buf) + r * SM::KSTRIDE + c8) = kreg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_LD; ++i) {
-      const int piece = tid + i * PC_FA_THREADS;
-      const int d = piece / (PC_FA_BN / 8), c8 = (piece % (PC_FA_BN / 8)) * 8;
-      *(uint4*)(v_lds(buf) + d * SM::VSTRIDE + c8) = vreg[i];
-    }
-  };
+  for (int i = 0; i < V_LD; ++i) {
+    const int piece = tid + i * PC_FA_THREADS;
+    v_ld_d[i] = piece / (PC_FA_BN / 8);
+    v_ld_c8[i] = (piece % (PC_FA_BN / 8)) * 8;
+  }
+#define PC_FA_LOAD_TILE(T)                                                                    \
+  {                                                                                           \
+    const int key0_ = key_begin + (T) * PC_FA_BN;                                             \
+    _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                        \
+      const int key_ = min(key0_ + k_ld_row[i], a.n_keys - 1);                                \
+      kreg[i] = *(const u32x4*)(kbase + (long long)key_ * a.k_row_stride + k_ld_c8[i]);       \
+    }                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                          \
+      vreg[i] = *(const u32x4*)(vtbase + (long long)v_ld_d[i] * a.vt_d_stride + key0_ + v_ld_c8[i]); \
+  }
+#define PC_FA_STORE_TILE(BUF)                                                                 \
+  {                                                                                           \
+    _Pragma("unroll") for (int i = 0; i < K_LD; ++i)                                          \
+      *(u32x4*)(k_lds(BUF) + k_ld_row[i] * SM::KSTRIDE + k_ld_c8[i]) = kreg[i];               \
+    _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                          \
+      *(u32x4*)(v_lds(BUF) + v_ld_d[i] * SM::VSTRIDE + v_ld_c8[i]) = vreg[i];                 \
+  }
 
   floatx16 o_acc[DB];
 #pragma unroll
@@ -278,14 +278,14 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   const int wave_min_vis = min(row0 + a.causal_offset, n_valid - 1); // visible to every row of the wave
 
   if (n_tiles > 0) {
-    load_tile(0);
-    store_tile(0);
+    PC_FA_LOAD_TILE(0);
+    PC_FA_STORE_TILE(0);
   }
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     const int buf = t & 1;
-    if (t + 1 < n_tiles) load_tile(t + 1);
+    if (t + 1 < n_tiles) PC_FA_LOAD_TILE(t + 1);
     const int key0 = key_begin + t * PC_FA_BN;
     if (key0 <= wave_max_key) {
       // ---- S^T = K Q^T for two 32-key blocks
@@ -316,14 +316,23 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[kb][r]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m_run, tmax * c_log2);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * c_log2;
+      // Lazy rescale: the reference m_run only moves when some row's tile maximum exceeds it by
+      // more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l stay in the old scale.
+      if (__any(tmax > m_run + 8.0f)) {
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+      }
       // rows with no visible key yet keep m = -inf; use 0 as the reference to avoid inf - inf
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
-      m_run = m_new;
+      const float neg_ref = (m_run == -INFINITY) ? 0.f : -m_run;
       float psum = 0.f;
-      bf16x8 pb[4];                                // B operands: [kb][k-step] -> index 2kb + t
+      bf16x8 pb[4];                                // B operands: [kb][k-step] -> index 2kb + ts
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -331,20 +340,18 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
           uint32_t pk[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e], c_log2, -m_ref));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e + 1], c_log2, -m_ref));
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e], c_log2, neg_ref));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e + 1], c_log2, neg_ref));
             psum += p0 + p1;
             pk[e] = pack_bf16x2(p0, p1);
           }
           uint4 pv = make_uint4(pk[0], pk[1], pk[2], pk[3]);
           pb[2 * kb + ts] = *(bf16x8*)&pv;
         }
-      l_run = l_run * alpha + psum;
-      // ---- O^T = O^T * alpha + V^T P^T
+      l_run += psum;
+      // ---- O^T += V^T P^T
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
         const uint16_t* vp = v_lds(buf) + (32 * db + n) * SM::VSTRIDE + 8 * hf;
 #pragma unroll
         for (int ksp = 0; ksp < 4; ++ksp) {
@@ -353,7 +360,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
         }
       }
     }
-    if (t + 1 < n_tiles) store_tile(buf ^ 1);
+    if (t + 1 < n_tiles) PC_FA_STORE_TILE(buf ^ 1);
     __syncthreads();
   }
 
