@@ -11,7 +11,9 @@ from ctypes import POINTER, Structure, c_char_p, c_float, c_int, c_int32, c_size
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libparallelcomp.so")
+# PARALLELCOMP_LIB overrides the in-tree library (e.g. to time an experimental build)
+_LIB_PATH = os.environ.get("PARALLELCOMP_LIB") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libparallelcomp.so")
 
 PC_OK = 0
 SYMBOLS = [
