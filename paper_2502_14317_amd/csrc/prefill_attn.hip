@@ -24,10 +24,11 @@
 // stay in that XCD's L2) and takes the long (late) Q tiles first.
 #include "pc_common.h"
 #include <math.h>
+#include <type_traits>
 
-#define PC_FA_WAVES 8
+#define PC_FA_WAVES 4
 #define PC_FA_THREADS (PC_FA_WAVES * PC_WAVE)
-#define PC_FA_BM (PC_FA_WAVES * 32)
+#define PC_FA_BM (PC_FA_WAVES * 64)
 #define PC_FA_BN 64
 #define PC_LOG2E 1.4426950408889634f
 #define PC_LN2 0.6931471805599453f
@@ -136,14 +137,23 @@ int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void
 }
 
 // ------------------------------------------------------------------------------------------
+// LDS tiles are filled by direct global->LDS loads (a wavefront instruction writes 64 x 16 B
+// contiguously), so rows cannot be padded.  Bank conflicts are avoided by an XOR swizzle of the
+// 16-byte granules inside a row instead: granule c of row r is stored in slot c ^ f(r).
+//   K tile   [64 keys][D]:   f(r) = r & 15 (D = 128, 256-byte rows), (r >> 1) & 7 (D = 64)
+//   V^T tile [D][64 keys]:   f(d) = (d >> 1) & 7 (128-byte rows)
+// With these, the 16 lanes served together by a 16-byte LDS read hit 16 distinct bank groups.
 template <int D>
 struct FlashSmem {
-  static constexpr int KSTRIDE = D + 8;            // bf16 elements per K row (16 B pad)
-  static constexpr int VSTRIDE = PC_FA_BN + 8;     // bf16 elements per V^T row (16 B pad)
-  static constexpr int K_ELEMS = PC_FA_BN * KSTRIDE;
-  static constexpr int V_ELEMS = D * VSTRIDE;
-  static constexpr int BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
+  static constexpr int KBUF = 3;                   // K tile t lives in buffer t % 3
+  static constexpr int VBUF = 4;                   // V^T tile t in buffer t % 4 (read one period early)
+  static constexpr int K_ELEMS = PC_FA_BN * D;
+  static constexpr int V_ELEMS = D * PC_FA_BN;
+  static constexpr int BYTES = (KBUF * K_ELEMS + VBUF * V_ELEMS) * 2;
 };
+template <int D>
+__device__ __forceinline__ int pc_k_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+__device__ __forceinline__ int pc_v_swz(int d) { return (d >> 1) & 7; }
 
 // row index of the first MFMA's A operand -> key within a 32-key block (swap bits 2 and 3)
 __device__ __forceinline__ int pc_key_of_row(int m) {
@@ -157,18 +167,20 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   constexpr int DB = D / 32;        // 32-row blocks of O^T (over head_dim)
   constexpr int HALF = D / 2;
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  auto k_lds = [&](int buf) { return smem + buf * SM::K_ELEMS; };
-  auto v_lds = [&](int buf) { return smem + 2 * SM::K_ELEMS + buf * SM::V_ELEMS; };
+  auto k_lds = [&](int t) __attribute__((always_inline)) { return smem + (t % SM::KBUF) * SM::K_ELEMS; };
+  auto v_lds = [&](int t) __attribute__((always_inline)) {
+    return smem + SM::KBUF * SM::K_ELEMS + (t % SM::VBUF) * SM::V_ELEMS;
+  };
 
   // ---- which (sequence, head, Q tile): one XCD (blockIdx % 8) works through whole
   //      (sequence, KV head) groups, heavy Q tiles first, the group's query heads adjacent
   const int G = a.n_q_heads / a.n_kv_heads;
   const int n_qt = (a.n_rows + PC_FA_BM - 1) / PC_FA_BM;
   const int per_group = G * n_qt * a.n_parts_grid;
-  const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
-  const int cg = (j / per_group) * 8 + xcd;
+  const int xcd = blockIdx.x % 8, jb = blockIdx.x / 8;
+  const int cg = (jb / per_group) * 8 + xcd;
   if (cg >= a.n_seq * a.n_kv_heads) return;
-  int within = j % per_group;
+  int within = jb % per_group;
   const int part = within % a.n_parts_grid; within /= a.n_parts_grid;
   const int qt = n_qt - 1 - within / G;
   const int hg = within % G;
@@ -177,222 +189,343 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 
   const int tid = threadIdx.x, lane = tid % PC_WAVE, wave = tid / PC_WAVE;
   const int hf = lane / 32, n = lane % 32;
-  const int rb = wave < 4 ? wave : 11 - wave;     // row blocks (i, 7 - i) share a SIMD
   const int row0_wg = qt * PC_FA_BM;
-  const int row0 = row0_wg + 32 * rb;             // first query row of this wavefront
-  const int my_row = row0 + n;
-  const int ld_row = min(my_row, a.n_rows - 1);
+  const int row0 = row0_wg + 64 * wave;           // first query row of this wavefront
+  int my_row[2], max_key[2];
 
   // ---- keys of this workgroup: [0, key_end) of the part
-  const int key_begin = 0;
   const int n_valid = a.part_len ? min(max(a.part_len[seq * a.n_parts_grid + part], 0), a.n_keys)
                                  : a.n_keys;
   int key_end = n_valid;
   if (a.causal_offset < PC_NO_CAUSAL) key_end = min(key_end, row0_wg + PC_FA_BM + a.causal_offset);
-  const int n_tiles = (key_end - key_begin + PC_FA_BN - 1) / PC_FA_BN;
+  const int T = (key_end + PC_FA_BN - 1) / PC_FA_BN;          // 64-key tiles
+  // steps of 32 keys: steps [0, J0) are visible to every row of the workgroup (no mask)
+  const int J0 = (min(row0_wg + a.causal_offset, n_valid - 1) + 1) / 32;
 
   const uint16_t* kbase = (const uint16_t*)a.k + seq * a.k_seq_stride + part * a.k_part_stride +
                           g * a.k_head_stride;
   const uint16_t* vtbase = (const uint16_t*)a.v_t + seq * a.vt_seq_stride +
                            part * a.vt_part_stride + g * a.vt_head_stride;
 
-  // ---- Q^T as B operand: lane holds query n, d = 16*ks + 8*hf .. +7
-  bf16x8 bq[KS];
-  {
+  // ---- Q^T as B operand, two 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7
+  bf16x8 bq[2][KS];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    my_row[nb] = row0 + 32 * nb + n;
+    max_key[nb] = min(my_row[nb] + a.causal_offset, n_valid - 1);
+    const int ld_row = min(my_row[nb], a.n_rows - 1);
     const uint16_t* qrow = (const uint16_t*)a.q + (((long long)seq * a.n_rows + ld_row) * a.n_q_heads + h) * D;
     if (ROPE_Q) {
       const float2* cs = a.table + (long long)(a.q_pos0 + ld_row) * HALF;
 #pragma unroll
       for (int ks = 0; ks < KS / 2; ++ks) {
         const int i0 = 16 * ks + 8 * hf;          // pair index of the first half
-        const uint4 x1 = *(const uint4*)(qrow + i0);
-        const uint4 x2 = *(const uint4*)(qrow + HALF + i0);
-        const uint32_t aw[4] = {x1.x, x1.y, x1.z, x1.w}, bw[4] = {x2.x, x2.y, x2.z, x2.w};
-        uint32_t ra[4], rbv[4];
+        const u32x4 x1 = *(const u32x4*)(qrow + i0);
+        const u32x4 x2 = *(const u32x4*)(qrow + HALF + i0);
+        u32x4 ra, rbv;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
-          const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
-          const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
+          const float x1l = bf16_lo_to_f32(x1[e]), x1h = bf16_hi_to_f32(x1[e]);
+          const float x2l = bf16_lo_to_f32(x2[e]), x2h = bf16_hi_to_f32(x2[e]);
           ra[e] = pack_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y);
           rbv[e] = pack_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y);
         }
-        uint4 pa = make_uint4(ra[0], ra[1], ra[2], ra[3]), pb = make_uint4(rbv[0], rbv[1], rbv[2], rbv[3]);
-        bq[ks] = *(bf16x8*)&pa;
-        bq[ks + KS / 2] = *(bf16x8*)&pb;
+        bq[nb][ks] = *(bf16x8*)&ra;
+        bq[nb][ks + KS / 2] = *(bf16x8*)&rbv;
       }
     } else {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const uint4 x = *(const uint4*)(qrow + 16 * ks + 8 * hf);
-        bq[ks] = *(bf16x8*)&x;
+        const u32x4 x = *(const u32x4*)(qrow + 16 * ks + 8 * hf);
+        bq[nb][ks] = *(bf16x8*)&x;
       }
     }
   }
 
-  // ---- cooperative tile loads: global -> registers -> LDS (16-byte pieces)
-  constexpr int K_LD = (PC_FA_BN * D / 8) / PC_FA_THREADS;
-  constexpr int V_LD = (D * PC_FA_BN / 8) / PC_FA_THREADS;
-  u32x4 kreg[K_LD], vreg[V_LD];
-  int k_ld_row[K_LD], k_ld_c8[K_LD], v_ld_d[V_LD], v_ld_c8[V_LD];
+  // ---- cooperative tile loads, straight from global memory into LDS.  Wavefront w issues
+  //      instruction i for the 1 KiB block b = 4 i + w of the tile; lane l fills granule
+  //      64 b + l of the tile and therefore fetches the source granule the swizzle puts there.
+  constexpr int T_LD = D / 32;                     // load instructions per thread per tile
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  // Per-lane byte offset of the source granule relative to the block's first row: the same for
+  // every load instruction i (the swizzle of row r + 16 i equals that of r) and every tile, so a
+  // tile load is a scalar base plus one constant vector offset.
+  constexpr int K_ROWS_PER_LD = 4 * 512 / D;       // tile rows covered by one instruction of all 4 waves
+  constexpr int V_ROWS_PER_LD = 4 * 512 / PC_FA_BN;
+  uint32_t k_goff, v_goff;
+  {
+    const int gi = 64 * wave_s + lane;
+    const int r = gi / (D / 8), c = (gi % (D / 8)) ^ pc_k_swz<D>(r);
+    k_goff = (uint32_t)(r * a.k_row_stride * 2 + 16 * c);
+    const int d = gi / 8, cv = (gi % 8) ^ pc_v_swz(d);
+    v_goff = (uint32_t)(d * a.vt_d_stride * 2 + 16 * cv);
+  }
+  auto load_k = [&](int t) __attribute__((always_inline)) {
+    if ((t + 1) * PC_FA_BN <= a.n_keys) {
 #pragma unroll
-  for (int i = 0; i < K_LD; ++i) {
-    const int piece = tid + i * PC_FA_THREADS;
-    k_ld_row[i] = piece / (D / 8);
-    k_ld_c8[i] = (piece % (D / 8)) * 8;
-  }
+      for (int i = 0; i < T_LD; ++i) {
+        const char* blk = (const char*)(kbase + ((long long)t * PC_FA_BN + i * K_ROWS_PER_LD) * a.k_row_stride);
+        __builtin_amdgcn_global_load_lds((gptr_t)(blk + k_goff),
+                                         (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
+      }
+    } else {   // last, partial tile: rows past the end are clamped to the last row (masked later)
 #pragma unroll
-  for (int i = 0; i < V_LD; ++i) {
-    const int piece = tid + i * PC_FA_THREADS;
-    v_ld_d[i] = piece / (PC_FA_BN / 8);
-    v_ld_c8[i] = (piece % (PC_FA_BN / 8)) * 8;
-  }
-#define PC_FA_LOAD_TILE(T)                                                                    \
-  {                                                                                           \
-    const int key0_ = key_begin + (T) * PC_FA_BN;                                             \
-    _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                        \
-      const int key_ = min(key0_ + k_ld_row[i], a.n_keys - 1);                                \
-      kreg[i] = *(const u32x4*)(kbase + (long long)key_ * a.k_row_stride + k_ld_c8[i]);       \
-    }                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                          \
-      vreg[i] = *(const u32x4*)(vtbase + (long long)v_ld_d[i] * a.vt_d_stride + key0_ + v_ld_c8[i]); \
-  }
-#define PC_FA_STORE_TILE(BUF)                                                                 \
-  {                                                                                           \
-    _Pragma("unroll") for (int i = 0; i < K_LD; ++i)                                          \
-      *(u32x4*)(k_lds(BUF) + k_ld_row[i] * SM::KSTRIDE + k_ld_c8[i]) = kreg[i];               \
-    _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                          \
-      *(u32x4*)(v_lds(BUF) + v_ld_d[i] * SM::VSTRIDE + v_ld_c8[i]) = vreg[i];                 \
-  }
+      for (int i = 0; i < T_LD; ++i) {
+        const int gi = 64 * (4 * i + wave_s) + lane;
+        const int r = gi / (D / 8), c = (gi % (D / 8)) ^ pc_k_swz<D>(r);
+        const int key = min(t * PC_FA_BN + r, a.n_keys - 1);
+        const uint16_t* src = kbase + (long long)key * a.k_row_stride + 8 * c;
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
+      }
+    }
+  };
+  auto load_v = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < T_LD; ++i) {
+      const char* blk = (const char*)(vtbase + (long long)i * V_ROWS_PER_LD * a.vt_d_stride + t * PC_FA_BN);
+      __builtin_amdgcn_global_load_lds((gptr_t)(blk + v_goff),
+                                       (lptr_t)(v_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
+    }
+  };
+  // s_waitcnt vmcnt(N): N newest loads of this wavefront may still be in flight
+#define PC_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
 
-  floatx16 o_acc[DB];
+  floatx16 o_acc[2][DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[nb][db][r] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
   const float c_log2 = a.scale * PC_LOG2E;
   const int krow = pc_key_of_row(n);               // LDS row this lane feeds into MFMA row n
-  const int max_key = min(my_row + a.causal_offset, n_valid - 1);     // last visible key of my query
-  const int wave_max_key = min(row0 + 31 + a.causal_offset, n_valid - 1);
-  const int wave_min_vis = min(row0 + a.causal_offset, n_valid - 1); // visible to every row of the wave
 
-  if (n_tiles > 0) {
-    PC_FA_LOAD_TILE(0);
-    PC_FA_STORE_TILE(0);
-  }
-  __syncthreads();
+  // A step is 32 keys.  Step j reads K rows / V^T columns 32 (j & 1) .. + 31 of tile j >> 1.
+  // S^T of step j lives in s_buf[j & 1], its probabilities P^T (bf16) in p_buf[j & 1].
+  floatx16 s_buf[2][2];                            // [step parity][row block]
+  bf16x8 p_buf[2][2][2];                           // [step parity][row block][16-key k-step]
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < n_tiles) PC_FA_LOAD_TILE(t + 1);
-    const int key0 = key_begin + t * PC_FA_BN;
-    if (key0 <= wave_max_key) {
-      // ---- S^T = K Q^T for two 32-key blocks
-      floatx16 s_acc[2];
+  // Per-lane element offsets of the MFMA A operands inside a tile.  The swizzle is an XOR on the
+  // granule bits only, so one base per operand kind suffices: offset(c) = base ^ (8 c) with the
+  // lane's own swizzle and half-select folded into the base.
+  int k_base = krow * D + 8 * (hf ^ pc_k_swz<D>(krow));
+  int v_base = n * PC_FA_BN + 8 * (hf ^ pc_v_swz(n));
+
+  // MFMA A operands, read from LDS one region ahead of their use
+  bf16x8 ka[KS], va[2][DB];                        // K rows of a step; V^T [16-key k-step][d block]
+  auto qk_read = [&](int j) __attribute__((always_inline)) {
+    const uint16_t* kp = k_lds(j >> 1) + 32 * D * (j & 1);    // swizzle of row r + 32 = that of r
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+    for (int ks = 0; ks < KS; ++ks) ka[ks] = *(const bf16x8*)(kp + (k_base ^ (16 * ks)));
+  };
+  // S^T(j) = K(j) Q^T for both row blocks; the K operand is read once and used twice
+  auto qk_mma = [&](floatx16(&s)[2]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
-        const uint16_t* kp = k_lds(buf) + (32 * kb + krow) * SM::KSTRIDE + 8 * hf;
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 ka = *(const bf16x8*)(kp + 16 * ks);
-          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, bq[ks], s_acc[kb], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], s[nb], 0, 0, 0);
+  };
+  auto pv_read = [&](int j) __attribute__((always_inline)) {
+    const uint16_t* vp = v_lds(j >> 1);                       // swizzle of row d + 32 = that of d
+#pragma unroll
+    for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        va[ts][db] = *(const bf16x8*)(vp + 32 * db * PC_FA_BN + (v_base ^ (32 * (j & 1) + 16 * ts)));
+  };
+  // O^T += V^T(j) P^T(j); the V^T operand is read once and used for both row blocks
+  auto pv_mma = [&](const bf16x8(&p)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ts][db], p[nb][ts], o_acc[nb][db], 0, 0, 0);
+  };
+  // Softmax of step j, in two parts.  Register r of a row block at lane half hf is key
+  // 32 j + 16 (r / 8) + 8 hf + (r % 8).
+  // Part A: mask, row maximum of the step (in log2 units); returns whether any row needs a
+  // new reference.  Lazy rescale: the reference m_run only moves when a row's step maximum
+  // exceeds it by more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l keep their scale.
+  float tmax[2];
+  auto softmax_max = [&](auto mask_tag, int j, floatx16(&s)[2]) __attribute__((always_inline)) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    const int key0 = 32 * j;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      if (MASK) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + 16 * (r / 8) + 8 * hf + (r % 8);
+          if (key > max_key[nb]) s[nb][r] = -INFINITY;
         }
       }
-      // register r of block kb at lane half hf is key key0 + 32kb + 16(r/8) + 8hf + (r%8)
-      if (key0 + PC_FA_BN - 1 > wave_min_vis) {
+      float t = s[nb][0];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int r = 1; r < 16; ++r) t = fmaxf(t, s[nb][r]);
+      tmax[nb] = t;
+    }
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key0 + 32 * kb + 16 * (r / 8) + 8 * hf + (r % 8);
-            if (key > max_key) s_acc[kb][r] = -INFINITY;
-          }
-      }
-      float tmax = -INFINITY;
+    for (int nb = 0; nb < 2; ++nb) tmax[nb] = fmaxf(tmax[nb], __shfl_xor(tmax[nb], 32)) * c_log2;
+  };
+  auto rescale_if_needed = [&]() __attribute__((always_inline)) {
+    if (__any(tmax[0] > m_run[0] + 8.0f || tmax[1] > m_run[1] + 8.0f)) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int nb = 0; nb < 2; ++nb) {
+        const float m_new = fmaxf(m_run[nb], tmax[nb]);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+        m_run[nb] = m_new;
+        l_run[nb] *= alpha;
+        // O sits in the accumulation registers; walk it one 16-register block at a time so
+        // this rare path needs only a handful of temporaries
 #pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s_acc[kb][r]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * c_log2;
-      // Lazy rescale: the reference m_run only moves when some row's tile maximum exceeds it by
-      // more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l stay in the old scale.
-      if (__any(tmax > m_run + 8.0f)) {
-        const float m_new = fmaxf(m_run, tmax);
-        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
+        for (int db = 0; db < DB; ++db) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
-      }
-      // rows with no visible key yet keep m = -inf; use 0 as the reference to avoid inf - inf
-      const float neg_ref = (m_run == -INFINITY) ? 0.f : -m_run;
-      float psum = 0.f;
-      bf16x8 pb[4];                                // B operands: [kb][k-step] -> index 2kb + ts
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int ts = 0; ts < 2; ++ts) {
-          uint32_t pk[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e], c_log2, neg_ref));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * ts + 2 * e + 1], c_log2, neg_ref));
-            psum += p0 + p1;
-            pk[e] = pack_bf16x2(p0, p1);
-          }
-          uint4 pv = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-          pb[2 * kb + ts] = *(bf16x8*)&pv;
-        }
-      l_run += psum;
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const uint16_t* vp = v_lds(buf) + (32 * db + n) * SM::VSTRIDE + 8 * hf;
-#pragma unroll
-        for (int ksp = 0; ksp < 4; ++ksp) {
-          const bf16x8 va = *(const bf16x8*)(vp + 16 * ksp);
-          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ksp], o_acc[db], 0, 0, 0);
+          for (int r = 0; r < 16; ++r) o_acc[nb][db][r] *= alpha;
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-    if (t + 1 < n_tiles) PC_FA_STORE_TILE(buf ^ 1);
+  };
+  // Part B: p = exp2(s - m_run) rounded to bf16 (the B operand of the second product), row sums
+  auto softmax_exp = [&](floatx16(&s)[2], bf16x8(&p)[2][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      // rows with no visible key yet keep m = -inf; use 0 as the reference to avoid inf - inf
+      const float neg_ref = (m_run[nb] == -INFINITY) ? 0.f : -m_run[nb];
+      float psum = 0.f;
+#pragma unroll
+      for (int ts = 0; ts < 2; ++ts) {
+        u32x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[nb][8 * ts + 2 * e], c_log2, neg_ref));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[nb][8 * ts + 2 * e + 1], c_log2, neg_ref));
+          psum += p0 + p1;
+          pk[e] = pack_bf16x2(p0, p1);
+        }
+        p[nb][ts] = *(bf16x8*)&pk;
+      }
+      l_run[nb] += psum;
+    }
+  };
+  using no_mask = std::integral_constant<bool, false>;
+  using with_mask = std::integral_constant<bool, true>;
+
+  // One step of the software pipeline, j = the step whose softmax runs now.  On entry `va`
+  // holds the V^T operands of step j - 1 (read during the previous step).
+  //   region 1:  LDS   K(j+1) operands   MFMA  O^T += V^T(j-1) P^T(j-1)   ||  VALU  row maxima of S^T(j)
+  //   (rare)     move the reference, rescale O and l
+  //   region 2:  LDS   V^T(j) operands   MFMA  S^T(j+1) = K(j+1) Q^T      ||  VALU  P^T(j) = exp2(S^T(j) - m)
+  // The streams of a region are independent, so they overlap inside the wavefront, and every
+  // operand read has a whole region to arrive.
+  // has_pv / has_qk are compile-time: the first step has no previous P V, the last no next K Q^T.
+  // Steps that lie wholly above a wavefront's rows on the diagonal are not skipped: their
+  // logits are masked to -inf, so they add exact zeros (straight-line code keeps the register
+  // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
+  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, int j, floatx16(&s_cur)[2],
+                  floatx16(&s_next)[2], bf16x8(&p_cur)[2][2],
+                  const bf16x8(&p_prev)[2][2]) __attribute__((always_inline)) {
+    if (decltype(has_qk)::value) qk_read(j + 1);
+    if (decltype(has_pv)::value) pv_mma(p_prev);
+    softmax_max(mask_tag, j, s_cur);
+    __builtin_amdgcn_sched_barrier(0);
+    rescale_if_needed();
+    __builtin_amdgcn_sched_barrier(0);
+    pv_read(j);
+    if (decltype(has_qk)::value) qk_mma(s_next);
+    softmax_exp(s_cur, p_cur);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using yes = std::integral_constant<bool, true>;
+  using no = std::integral_constant<bool, false>;
+
+  if (T > 0) {
+    // ---- prologue: tiles 0 and 1 must have landed before the first step; tile 2 stays in flight
+    load_k(0);
+    load_v(0);
+    if (T > 1) load_k(1);
+    if (T > 1) load_v(1);
+    if (T > 2) load_k(2);
+    if (T > 2) load_v(2);
+    if (T > 2) { PC_WAIT_VMCNT(2 * T_LD); } else { PC_WAIT_VMCNT(0); }
     __syncthreads();
+    qk_read(0);
+    qk_mma(s_buf[0]);
+    step(with_mask{}, no{}, yes{}, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
+
+    // One period = two steps.  Period p runs steps 2p+1 and 2p+2: it reads K tile p + 1 and the
+    // V^T tiles p and p + 1 (the latter only its first half, for the next period's first step).
+    // Right after its barrier it issues the loads of K(p + 3) and V(p + 3) into the buffers that
+    // held K(p) and V(p - 1), both last read before that barrier.  Tiles are first read two
+    // periods after their loads were issued, so before a barrier a wavefront only waits for the
+    // loads it issued one period earlier.
+    auto period = [&](auto mask_tag, int p) __attribute__((always_inline)) {
+      // Opaque no-ops on the address seeds: they stop the compiler from hoisting two dozen
+      // loop-invariant per-lane addresses out of the loop into registers the loop cannot spare;
+      // recomputing them costs a few vector-ALU instructions per period.
+      asm volatile("" : "+v"(k_base), "+v"(v_base));
+      if (p + 2 < T) { PC_WAIT_VMCNT(2 * T_LD); } else { PC_WAIT_VMCNT(0); }
+      __syncthreads();
+      if (p + 3 < T) load_k(p + 3);
+      if (p + 3 < T) load_v(p + 3);
+      step(mask_tag, yes{}, yes{}, 2 * p + 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
+      step(mask_tag, yes{}, yes{}, 2 * p + 2, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
+    };
+    const int n_plain = min(T - 1, max(0, (J0 - 1) / 2));   // periods whose steps need no mask
+    int p = 0;
+    for (; p < n_plain; ++p) period(no_mask{}, p);
+    for (; p < T - 1; ++p) period(with_mask{}, p);
+    // ---- last period: step 2T-1 and the trailing P V
+    PC_WAIT_VMCNT(0);
+    __syncthreads();
+    step(with_mask{}, yes{}, no{}, 2 * T - 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
+    pv_mma(p_buf[1]);
   }
 
   // ---- epilogue: lane halves hold disjoint key subsets of the same query
-  l_run += __shfl_xor(l_run, 32);
-  const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
-  const float lse = l_run > 0.f ? m_run * PC_LN2 + logf(l_run) : -INFINITY;
-  if (my_row < a.n_rows) {
-    if (PARTIAL) {
-      const long long prow = ((((long long)seq * a.n_parts_total + a.part0 + part) * a.n_rows) + my_row) * a.n_q_heads + h;
-      float* po = a.part_o + prow * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+  for (int nb = 0; nb < 2; ++nb) {
+    float l = l_run[nb];
+    l += __shfl_xor(l, 32);
+    const float inv_l = l > 0.f ? 1.f / l : 0.f;
+    const float lse = l > 0.f ? m_run[nb] * PC_LN2 + logf(l) : -INFINITY;
+    if (my_row[nb] < a.n_rows) {
+      if (PARTIAL) {
+        const long long prow = ((((long long)seq * a.n_parts_total + a.part0 + part) * a.n_rows) + my_row[nb]) * a.n_q_heads + h;
+        float* po = a.part_o + prow * D;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float4 x = make_float4(o_acc[db][4 * i] * inv_l, o_acc[db][4 * i + 1] * inv_l,
-                                 o_acc[db][4 * i + 2] * inv_l, o_acc[db][4 * i + 3] * inv_l);
-          *(float4*)(po + 32 * db + 8 * i + 4 * hf) = x;
-        }
-      if (hf == 0) a.part_lse[prow] = lse;
-    } else {
-      uint16_t* orow = (uint16_t*)a.o + (((long long)seq * a.n_rows + my_row) * a.n_q_heads + h) * D;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+          for (int i = 0; i < 4; ++i) {
+            floatx4 x = {o_acc[nb][db][4 * i] * inv_l, o_acc[nb][db][4 * i + 1] * inv_l,
+                         o_acc[nb][db][4 * i + 2] * inv_l, o_acc[nb][db][4 * i + 3] * inv_l};
+            *(floatx4*)(po + 32 * db + 8 * i + 4 * hf) = x;
+          }
+        if (hf == 0) a.part_lse[prow] = lse;
+      } else {
+        uint16_t* orow = (uint16_t*)a.o + (((long long)seq * a.n_rows + my_row[nb]) * a.n_q_heads + h) * D;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          uint2 x;
-          x.x = pack_bf16x2(o_acc[db][4 * i] * inv_l, o_acc[db][4 * i + 1] * inv_l);
-          x.y = pack_bf16x2(o_acc[db][4 * i + 2] * inv_l, o_acc[db][4 * i + 3] * inv_l);
-          *(uint2*)(orow + 32 * db + 8 * i + 4 * hf) = x;
-        }
-      if (hf == 0 && a.lse) a.lse[((long long)seq * a.n_q_heads + h) * a.n_rows + my_row] = lse;
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            uint2 x;
+            x.x = pack_bf16x2(o_acc[nb][db][4 * i] * inv_l, o_acc[nb][db][4 * i + 1] * inv_l);
+            x.y = pack_bf16x2(o_acc[nb][db][4 * i + 2] * inv_l, o_acc[nb][db][4 * i + 3] * inv_l);
+            *(uint2*)(orow + 32 * db + 8 * i + 4 * hf) = x;
+          }
+        if (hf == 0 && a.lse) a.lse[((long long)seq * a.n_q_heads + h) * a.n_rows + my_row[nb]] = lse;
+      }
     }
   }
 }
