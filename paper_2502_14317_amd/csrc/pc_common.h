@@ -56,6 +56,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return *(uint32_t*)&r;
 }
 
+// Exchange between lane l and lane l ^ 32 without going through LDS: v_permlane32_swap leaves
+// the low half's values in both halves of the first result and the high half's in the second.
+__device__ __forceinline__ float pc_xhalf_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pc_xhalf_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // fp32 score -> uint32 key whose unsigned order is the float order; NaN -> 0 (below everything),
 // -0.0 and +0.0 map to the same key
 __device__ __forceinline__ uint32_t pc_order_key(float f) {

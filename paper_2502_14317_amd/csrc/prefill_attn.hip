@@ -145,8 +145,8 @@ int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void
 // With these, the 16 lanes served together by a 16-byte LDS read hit 16 distinct bank groups.
 template <int D>
 struct FlashSmem {
-  static constexpr int KBUF = 3;                   // K tile t lives in buffer t % 3
-  static constexpr int VBUF = 4;                   // V^T tile t in buffer t % 4 (read one period early)
+  static constexpr int KBUF = 4;                   // K tile t lives in buffer t % 4
+  static constexpr int VBUF = 5;                   // V^T tile t in buffer t % 5 (read one period early)
   static constexpr int K_ELEMS = PC_FA_BN * D;
   static constexpr int V_ELEMS = D * PC_FA_BN;
   static constexpr int BYTES = (KBUF * K_ELEMS + VBUF * V_ELEMS) * 2;
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       tmax[nb] = t;
     }
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) tmax[nb] = fmaxf(tmax[nb], __shfl_xor(tmax[nb], 32)) * c_log2;
+    for (int nb = 0; nb < 2; ++nb) tmax[nb] = pc_xhalf_max(tmax[nb]) * c_log2;
   };
   auto rescale_if_needed = [&]() __attribute__((always_inline)) {
     if (__any(tmax[0] > m_run[0] + 8.0f || tmax[1] > m_run[1] + 8.0f)) {
@@ -451,14 +451,16 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   using no = std::integral_constant<bool, false>;
 
   if (T > 0) {
-    // ---- prologue: tiles 0 and 1 must have landed before the first step; tile 2 stays in flight
+    // ---- prologue: tiles 0 and 1 must have landed before the first step; tiles 2, 3 stay in flight
     load_k(0);
     load_v(0);
     if (T > 1) load_k(1);
     if (T > 1) load_v(1);
     if (T > 2) load_k(2);
     if (T > 2) load_v(2);
-    if (T > 2) { PC_WAIT_VMCNT(2 * T_LD); } else { PC_WAIT_VMCNT(0); }
+    if (T > 3) load_k(3);
+    if (T > 3) load_v(3);
+    if (T > 3) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
     __syncthreads();
     qk_read(0);
     qk_mma(s_buf[0]);
@@ -466,19 +468,19 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 
     // One period = two steps.  Period p runs steps 2p+1 and 2p+2: it reads K tile p + 1 and the
     // V^T tiles p and p + 1 (the latter only its first half, for the next period's first step).
-    // Right after its barrier it issues the loads of K(p + 3) and V(p + 3) into the buffers that
-    // held K(p) and V(p - 1), both last read before that barrier.  Tiles are first read two
+    // Right after its barrier it issues the loads of K(p + 4) and V(p + 4) into the buffers that
+    // held K(p) and V(p - 1), both last read before that barrier.  Tiles are first read three
     // periods after their loads were issued, so before a barrier a wavefront only waits for the
-    // loads it issued one period earlier.
+    // loads it issued two periods earlier (the two newest batches may stay in flight).
     auto period = [&](auto mask_tag, int p) __attribute__((always_inline)) {
-      // Opaque no-ops on the address seeds: they stop the compiler from hoisting two dozen
+      // Opaque no-ops on the address seeds: they stop the compiler from hoisting a dozen
       // loop-invariant per-lane addresses out of the loop into registers the loop cannot spare;
       // recomputing them costs a few vector-ALU instructions per period.
       asm volatile("" : "+v"(k_base), "+v"(v_base));
-      if (p + 2 < T) { PC_WAIT_VMCNT(2 * T_LD); } else { PC_WAIT_VMCNT(0); }
+      if (p + 3 < T) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
       __syncthreads();
-      if (p + 3 < T) load_k(p + 3);
-      if (p + 3 < T) load_v(p + 3);
+      if (p + 4 < T) load_k(p + 4);
+      if (p + 4 < T) load_v(p + 4);
       step(mask_tag, yes{}, yes{}, 2 * p + 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
       step(mask_tag, yes{}, yes{}, 2 * p + 2, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
     };
@@ -496,8 +498,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // ---- epilogue: lane halves hold disjoint key subsets of the same query
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    float l = l_run[nb];
-    l += __shfl_xor(l, 32);
+    const float l = pc_xhalf_sum(l_run[nb]);
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
     const float lse = l > 0.f ? m_run[nb] * PC_LN2 + logf(l) : -INFINITY;
     if (my_row[nb] < a.n_rows) {
