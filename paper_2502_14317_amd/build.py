@@ -11,7 +11,10 @@ SOURCES = ["pc_api.hip", "gather.hip", "select.hip", "decode_attn.hip", "prefill
            "scores.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument"]
+               "-Wno-unused-command-line-argument",
+               # keep MFMA results in architectural VGPRs where the vector ALU consumes them
+               # (softmax of S^T): avoids hundreds of accumulator<->VGPR copies per tile
+               "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def build_library(verbose: bool = True, jobs: int = 6) -> str:
