@@ -24,9 +24,14 @@ if ROOT not in sys.path:
 PEAK_BF16_FLOPS = 2.5e15      # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# per workload; see profiles/.  None until measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by what the same
+# counters read for a plain 1 GiB copy (2048 B per FETCH_SIZE count, 1024 B per WRITE_SIZE count);
+# commands and raw counts: profiles/pmc_hbm_traffic.md.  Keyed by (kernel, workload).
+MEASURED_TRAFFIC = {
+    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.4264e6 * 2048 + 1.0651e6 * 1024,
+    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.0980e6 * 2048 + 1.66e4 * 1024,
+    ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1151e6 * 2048 + 4.1943e6 * 1024,
+}
 
 
 def flash_flops(cfg):
@@ -126,7 +131,8 @@ def bench_secondary(pc, torch, steps, warmup):
         "workload": cfg.name, "ms_per_step": dt * 1e3, "tokens_per_s_per_layer": B / dt,
         "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": kv_bytes / k_avg / 1e9,
                      "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": kv_bytes / k_avg / PEAK_HBM_BYTES,
-                     "kernel_ms": k_avg * 1e3, "traffic": None}}
+                     "kernel_ms": k_avg * 1e3,
+                     "traffic": MEASURED_TRAFFIC.get(("decode_attn_kernel", cfg.name))}}
     del kc, vc
     torch.cuda.empty_cache()
     # gather: source [B, S, rows, H_kv, D], sorted random k_t-subsets of the rows
@@ -156,7 +162,8 @@ def bench_secondary(pc, torch, steps, warmup):
         "workload": cfg.name, "roofline": {"bound": "hbm", "kernel": "gather_kv_kernel",
                                            "achieved": g_bytes / k_avg / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
                                            "unit": "GB/s", "frac": g_bytes / k_avg / PEAK_HBM_BYTES,
-                                           "kernel_ms": k_avg * 1e3, "traffic": None}}
+                                           "kernel_ms": k_avg * 1e3,
+                                           "traffic": MEASURED_TRAFFIC.get(("gather_kv_kernel", cfg.name))}}
     return out
 
 
@@ -170,6 +177,9 @@ def main():
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time only the chunk prefill + score reduction (the stress config's step)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times: the reference the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled against")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -184,6 +194,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")    # 1 GiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4, "copies": 3}))
+        return
     pc.lib()
     cfg = PREFILL_CONFIGS[args.workload]
     prefill_only = args.prefill_only or cfg.keep_chunks == 0
@@ -236,7 +254,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "flash_fwd_kernel", "achieved": flops / flash_avg / 1e12,
                      "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                      "frac": flops / flash_avg / PEAK_BF16_FLOPS, "kernel_ms": flash_avg * 1e3,
-                     "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(cfg.name)},
+                     "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(("flash_fwd_kernel", cfg.name))},
         "kernel_ms_per_step": breakdown,
     }
     print(f"[bench] {cfg.name}: {ms_per_step:.3f} ms/step, flash {flash_avg * 1e3:.3f} ms "
