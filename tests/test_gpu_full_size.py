@@ -1,0 +1,173 @@
+"""GPU parity at the full sizes of the configs, in the launch configuration bench.py times.
+The oracle cannot compute whole outputs at these sizes, so it is evaluated on sampled outputs
+(rows of sampled chunks and heads, computed one by one from the definition), on complete score
+tensors (cheap: only the voting rows), and on selections; gather is checked bit-exactly."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_14317_amd as pc
+from paper_2502_14317_amd.layer import ParallelCompLayer
+from workloads import CFG1, CFG2, CFG3, CFG4, prefill_inputs, bf16_bits_to_f64
+from helpers import (O_ATOL, O_RTOL, S_RTOL, S_ATOL, LSE_ATOL, bits_to_dev, dev_to_bits,
+                     dev_bf16_to_f64, assert_close, assert_selection_matches)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _sample_rows(cfg):
+    L, w = cfg.seq_len, cfg.chunk_len
+    fixed = [0, 1, 31, 32, 63, 64, 255, 256, 257, L // 2, w - 1, w, w + 1, L - 33, L - 2, L - 1]
+    rng = np.random.default_rng([99, cfg.cfg_id])
+    return np.unique(np.concatenate([np.array(fixed), rng.integers(0, L, size=16)]))
+
+
+def _check_prefill_samples(cfg, layer, q, k, v, chunks, score_chunks):
+    """Sampled rows of o / lse / k_rope and whole score tensors of the given chunks."""
+    pos = np.arange(cfg.seq_len)
+    rows = _sample_rows(cfg)
+    ref_tok = {}
+    for c in sorted(set(chunks) | set(score_chunks)):
+        _say(f"  oracle chunk {c}")
+        q_rot = oracle.rope(bf16_bits_to_f64(q[c]), pos, cfg.rope_base)
+        k_rot = oracle.rope(bf16_bits_to_f64(k[c]), pos, cfg.rope_base)
+        if c in chunks:
+            ro, rl = oracle.local_attention(q_rot, k_rot, bf16_bits_to_f64(v[c]), rows=rows)
+            assert_close(dev_bf16_to_f64(layer.o[c, rows]), ro, O_ATOL, O_RTOL, f"o[c={c}]")
+            assert_close(layer.lse[c][:, rows].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"lse[c={c}]")
+            assert_close(dev_bf16_to_f64(layer.k_rope[c, rows]), k_rot[rows], 1e-5, 2.0 ** -8, f"k_rope[c={c}]")
+        if c in score_chunks:
+            tok, chunk = oracle.query_scores(q_rot, k_rot, cfg.chunk_len, cfg.obs_window, cfg.n_kv_heads)
+            assert_close(layer.tok_score[c].cpu().numpy(), tok, S_ATOL, S_RTOL, f"tok_score[c={c}]")
+            assert_close(layer.chunk_score[c].cpu().numpy(), chunk, S_ATOL, S_RTOL, f"chunk_score[c={c}]")
+            ref_tok[c] = (tok, chunk, q_rot if c == 0 else None, k_rot)
+    return ref_tok
+
+
+def _finite_and_bounded(cfg, layer):
+    """Properties that hold at any size."""
+    assert torch.isfinite(layer.o.float()).all() and torch.isfinite(layer.lse).all()
+    cs = layer.chunk_score.cpu().numpy()
+    ts = layer.tok_score
+    assert (ts >= 0).all() and torch.isfinite(ts).all()
+    # every voting row's probabilities sum to one over all keys: chunk mass < H_q * w_obs
+    assert np.all(cs > 0) and np.all(cs < cfg.n_q_heads * cfg.obs_window)
+    # row 0 attends to key 0 only: o[0] = v[0], lse[0] = q0.k0 * scale
+    return cs
+
+
+@pytest.mark.parametrize("cfg", [CFG1, CFG2], ids=lambda c: c.name)
+def test_full_layer_sampled(cfg):
+    _say(f"full layer {cfg.name}: generating inputs")
+    q, k, v = prefill_inputs(cfg, threads=16)
+    layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
+                              cfg.n_kv_heads, cfg.head_dim, cfg.obs_window, cfg.rope_base,
+                              cfg.keep_chunks, cfg.keep_tokens)
+    qd, kd, vd = bits_to_dev(q), bits_to_dev(k), bits_to_dev(v)
+    layer.forward(qd, kd, vd)
+    torch.cuda.synchronize()
+    _say("  GPU pass done")
+    _finite_and_bounded(cfg, layer)
+    C = cfg.n_chunks
+    # Eq. 5-6 on every chunk (the oracle only needs the voting rows), Eq. 1-2 on three chunks
+    ref = _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, C // 2, C - 1], score_chunks=range(C))
+    ref_chunk_score = np.array([ref[c][1] for c in range(C)])
+    # Eq. 3-4 mechanics
+    g_cidx = layer.chunk_idx.cpu().numpy()
+    ref_cidx = oracle.select_chunks(ref_chunk_score, cfg.keep_chunks)
+    n_diff = assert_selection_matches(g_cidx, ref_cidx, ref_chunk_score, "chunk selection")
+    # Eq. 7 index sets
+    g_tidx = layer.tok_idx.cpu().numpy()
+    for s_ in range(cfg.keep_chunks):
+        tok = ref[int(g_cidx[s_])][0]
+        ref_t = oracle.select_tokens(tok, cfg.keep_tokens)
+        for g in range(cfg.n_kv_heads):
+            assert list(g_tidx[s_, g]) == sorted(set(g_tidx[s_, g]))
+            n_diff += assert_selection_matches(g_tidx[s_, g], ref_t[g], tok[g], f"tokens chunk {g_cidx[s_]} head {g}")
+    _say(f"  selection differences inside the tie zone: {n_diff}")
+    # Eq. 7 gather: bit-exact on the GPU's own rotated keys at the GPU's indices
+    kr = dev_to_bits(layer.k_rope)
+    rk, rv = oracle.gather_kv(kr, v, g_cidx, g_tidx)
+    assert np.array_equal(dev_to_bits(layer.kc[0]), rk) and np.array_equal(dev_to_bits(layer.vc[0]), rv)
+    del kr, rk, rv
+    # Eq. 9-11 on sampled query rows: one softmax over [kept K of every kept chunk, own keys 0..t]
+    w, wq = cfg.chunk_len, cfg.query_len
+    q_rot0, k_rot0 = ref[0][2], ref[0][3]
+    kc_ref = np.stack([np.stack([ref[int(c)][3][g_tidx[s_, g], g] for g in range(cfg.n_kv_heads)])
+                       for s_, c in enumerate(g_cidx)])
+    vf = {int(c): bf16_bits_to_f64(v[int(c)]) for c in g_cidx}
+    vc_ref = np.stack([np.stack([vf[int(c)][g_tidx[s_, g], g] for g in range(cfg.n_kv_heads)])
+                       for s_, c in enumerate(g_cidx)])
+    v0 = bf16_bits_to_f64(v[0])
+    for t in (0, 1, 63, 64, wq // 2, wq - 1):
+        # the self keys 0..t enter as one more segment of t + 1 valid rows
+        kt = cfg.keep_tokens
+        ks = np.zeros((1, cfg.n_kv_heads, kt, cfg.head_dim)); vs = np.zeros_like(ks)
+        ks[0, :, :t + 1] = k_rot0[w:w + t + 1].transpose(1, 0, 2)
+        vs[0, :, :t + 1] = v0[w:w + t + 1].transpose(1, 0, 2)
+        seg_len = np.array([kt] * cfg.keep_chunks + [t + 1])
+        ro, rl = oracle.global_attention_concat(q_rot0[w + t:w + t + 1], np.concatenate([kc_ref, ks]),
+                                                np.concatenate([vc_ref, vs]), seg_len=seg_len)
+        assert_close(dev_bf16_to_f64(layer.global_o[0, t]), ro[0], O_ATOL, O_RTOL, f"global_o[t={t}]")
+        assert_close(layer.global_lse[0, :, t].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"global_lse[t={t}]")
+
+
+def test_full_prefill_stress_config():
+    """64 chunks x 8704 rows in one launch: prefill + scores only (the stress config's step)."""
+    cfg = CFG3
+    _say(f"prefill {cfg.name}: generating inputs")
+    q, k, v = prefill_inputs(cfg, threads=16)
+    layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
+                              cfg.n_kv_heads, cfg.head_dim, cfg.obs_window, cfg.rope_base, 0, 0)
+    layer.chunk_prefill(bits_to_dev(q), bits_to_dev(k), bits_to_dev(v), True)
+    torch.cuda.synchronize()
+    _say("  GPU pass done")
+    _finite_and_bounded(cfg, layer)
+    _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, 63], score_chunks=[0, 31, 63])
+
+
+def test_full_decode_and_gather_sampled():
+    cfg = CFG4
+    _say(f"decode {cfg.name}")
+    g = torch.Generator(device="cuda").manual_seed(4)
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf = torch.bfloat16
+    # gather source [B, S, rows, H_kv, D] and sorted random index subsets
+    R = cfg.src_rows
+    ks = torch.empty((B, S, R, Hkv, D), dtype=bf, device="cuda")
+    for b in range(B):
+        ks[b] = (torch.randn(ks.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    vs = ks.flip(0).contiguous()
+    idx = torch.rand((B, S, Hkv, R), generator=g, device="cuda").argsort(dim=-1)[..., :kt]
+    idx = idx.sort(dim=-1).values.to(torch.int32).contiguous()
+    kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vc = torch.empty_like(kc)
+    pc.pc_gather_kv(ks, vs, None, idx, B, S, R, S, Hkv, kt, D, kc, vc)
+    torch.cuda.synchronize()
+    for (b, s_) in ((0, 0), (7, 13), (15, 31)):
+        ti = idx[b, s_].cpu().numpy()[None]
+        rk, rv = oracle.gather_kv(dev_to_bits(ks[b, s_])[None], dev_to_bits(vs[b, s_])[None], np.zeros(1, dtype=np.int64), ti)
+        assert np.array_equal(dev_to_bits(kc[b, s_]), rk[0]) and np.array_equal(dev_to_bits(vc[b, s_]), rv[0])
+    del ks, vs
+    torch.cuda.empty_cache()
+    # decode over the gathered cache: sampled (sequence, KV group) pairs against one softmax
+    q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda")).to(bf)     # logits with std ~ 1
+    out = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(B, 1, S, kt, Hq, Hkv, D, 0))
+    pc.pc_parallel_attn(q, kc, vc, None, None, None, B, 1, S, kt, Hq, Hkv, D, -1, 1.0e4, 0.0, out, lse, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    G = Hq // Hkv
+    for (b, gk) in ((0, 0), (5, 3), (15, 7)):
+        kf = dev_bf16_to_f64(kc[b, :, gk])[:, None]          # [S, 1, kt, D]
+        vf = dev_bf16_to_f64(vc[b, :, gk])[:, None]
+        qf = dev_bf16_to_f64(q[b, :, gk * G:(gk + 1) * G])    # [1, G, D]
+        ro, rl = oracle.global_attention_concat(qf, kf, vf)
+        assert_close(dev_bf16_to_f64(out[b, :, gk * G:(gk + 1) * G]), ro, O_ATOL, O_RTOL, f"decode out[b={b},g={gk}]")
+        assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"decode lse[b={b},g={gk}]")
