@@ -150,6 +150,7 @@ struct FlashSmem {
   static constexpr int K_ELEMS = PC_FA_BN * D;
   static constexpr int V_ELEMS = D * PC_FA_BN;
   static constexpr int BYTES = (KBUF * K_ELEMS + VBUF * V_ELEMS) * 2;
+  static constexpr int STAGE_BYTES = PC_FA_THREADS * 16;   // one 16-byte slot per lane behind the tiles
 };
 template <int D>
 __device__ __forceinline__ int pc_k_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
@@ -243,6 +244,22 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     }
   }
 
+  // Park Q^T in the accumulation-register file (MFMA reads its B operand from there directly):
+  // the architectural registers are needed for O^T, S^T and P^T.  The only way to name that file
+  // from C++ is a load, so each lane bounces its values through 16 private bytes of LDS.
+  {
+    uint16_t* stage = smem + SM::BYTES / 2 + 8 * tid;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        *(bf16x8*)stage = bq[nb][ks];
+        bf16x8 parked;
+        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=a"(parked) : "v"((uint32_t)(uintptr_t)stage) : "memory");
+        bq[nb][ks] = parked;
+      }
+  }
+
   // ---- cooperative tile loads, straight from global memory into LDS.  Wavefront w issues
   //      instruction i for the 1 KiB block b = 4 i + w of the tile; lane l fills granule
   //      64 b + l of the tile and therefore fetches the source granule the swizzle puts there.
@@ -307,7 +324,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // A step is 32 keys.  Step j reads K rows / V^T columns 32 (j & 1) .. + 31 of tile j >> 1.
   // S^T of step j lives in s_buf[j & 1], its probabilities P^T (bf16) in p_buf[j & 1].
   floatx16 s_buf[2][2];                            // [step parity][row block]
-  bf16x8 p_buf[2][2][2];                           // [step parity][row block][16-key k-step]
+  u32x4 p_buf[2][2][2];                            // [step parity][row block][16-key k-step], bf16 pairs
 
   // Per-lane element offsets of the MFMA A operands inside a tile.  The swizzle is an XOR on the
   // granule bits only, so one base per operand kind suffices: offset(c) = base ^ (8 c) with the
@@ -317,13 +334,142 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 
   // MFMA A operands, read from LDS one region ahead of their use
   bf16x8 ka[KS], va[2][DB];                        // K rows of a step; V^T [16-key k-step][d block]
-  auto qk_read = [&](int j) __attribute__((always_inline)) {
-    const uint16_t* kp = k_lds(j >> 1) + 32 * D * (j & 1);    // swizzle of row r + 32 = that of r
+  float neg_ref[2] = {0.f, 0.f};                   // -m_run, or 0 while a row has seen no key
+  using no_mask = std::integral_constant<bool, false>;
+  using with_mask = std::integral_constant<bool, true>;
+  using yes = std::integral_constant<bool, true>;
+  using no = std::integral_constant<bool, false>;
+
+  // One step of the software pipeline, j = the step whose softmax runs now.  A region is NM
+  // slices of [one MFMA, at most one LDS operand read, a few vector-ALU instructions], and the
+  // compiler may not move instructions across a slice boundary, so the three pipes are fed
+  // evenly by construction instead of by the scheduler's heuristics:
+  //   region 1:  MFMA  O^T += V^T(j-1) P^T(j-1)     LDS  K(j+1) operands
+  //              VALU  row maxima of S^T(j), reference update, first part of P^T(j)
+  //   (rare)     rescale O after the reference of some row moved
+  //   region 2:  MFMA  S^T(j+1) = K(j+1) Q^T        LDS  V^T(j) operands
+  //              VALU  rest of P^T(j) = exp2(S^T(j) - m)
+  // Register r of a row block at lane half hf is key 32 j + 16 (r / 8) + 8 hf + (r % 8).
+  // Lazy rescale: the reference m_run of a row only moves when the step maximum exceeds it by
+  // more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l keep their scale.  The P V
+  // products of step j - 1 (old reference) are all issued in region 1, so O is rescaled after it.
+  // has_pv / has_qk are compile-time: the first step has no previous P V, the last no next K Q^T.
+  // Steps that lie wholly above a wavefront's rows on the diagonal are not skipped: their
+  // logits are masked to -inf, so they add exact zeros (straight-line code keeps the register
+  // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
+  constexpr int NM = 2 * KS;                       // MFMAs per region (= 4 DB)
+  constexpr int MAX_SL = NM / 4;                   // slices of region 1 that take the row maxima
+  constexpr int E1 = 12;                           // probabilities (of 32 per lane) computed in region 1
+  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, int j, floatx16(&s_cur)[2],
+                  floatx16(&s_next)[2], u32x4(&p_cur)[2][2],
+                  const u32x4(&p_prev)[2][2]) __attribute__((always_inline)) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    constexpr bool PV = decltype(has_pv)::value, QK = decltype(has_qk)::value;
+    const uint16_t* kp = k_lds((j + 1) >> 1) + 32 * D * ((j + 1) & 1);   // swizzle of row r + 32 = that of r
+    const uint16_t* vp = v_lds(j >> 1);                                   // swizzle of row d + 32 = that of d
+    float t[2] = {0.f, 0.f}, alpha[2] = {1.f, 1.f}, pe = 0.f;
+    bool grow_any = false;
+    // probability e (0..31: row block e / 16, register e % 16) of this step
+    auto prob = [&](int e) __attribute__((always_inline)) {
+      const int nb = e / 16, r = e % 16;
+      const float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[nb][r], c_log2, neg_ref[nb]));
+      l_run[nb] += pr;
+      // Opaque uses pin the instructions to the slice they were written in: without them the
+      // compiler sinks this (side-effect-free) arithmetic past the slice boundaries.
+      asm volatile("" : "+v"(l_run[nb]));
+      if (r % 2 == 0) {
+        pe = pr;
+      } else {
+        uint32_t w = pack_bf16x2(pe, pr);
+        asm volatile("" : "+v"(w));
+        p_cur[nb][r / 8][(r % 8) / 2] = w;
+      }
+    };
+    // ---------------- region 1
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      if (PV) {
+        const int ts = i / (2 * DB), db = (i / 2) % DB, nb = i % 2;
+        o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            va[ts][db], *(const bf16x8*)&p_prev[nb][ts], o_acc[nb][db], 0, 0, 0);
+      }
+      if (QK && i % 2 == 0) ka[i / 2] = *(const bf16x8*)(kp + (k_base ^ (16 * (i / 2))));
+      if (MASK && i == 0) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = 32 * j + 16 * (r / 8) + 8 * hf + (r % 8);
+            if (key > max_key[nb]) s_cur[nb][r] = -INFINITY;
+          }
+      }
+      if (i < MAX_SL) {
+        // the 8 links of each row block's maximum chain, 8 / MAX_SL per slice
+#pragma unroll
+        for (int q = i * (8 / MAX_SL); q < (i + 1) * (8 / MAX_SL); ++q)
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            if (q == 0) t[nb] = fmaxf(fmaxf(s_cur[nb][0], s_cur[nb][1]), s_cur[nb][2]);
+            else if (q < 7) t[nb] = fmaxf(fmaxf(t[nb], s_cur[nb][2 * q + 1]), s_cur[nb][2 * q + 2]);
+            else t[nb] = fmaxf(t[nb], s_cur[nb][15]);
+          }
+        asm volatile("" : "+v"(t[0]), "+v"(t[1]));
+      }
+      if (i == MAX_SL) {
+        bool grow[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const float tm = pc_xhalf_max(t[nb]) * c_log2;
+          grow[nb] = tm > m_run[nb] + 8.0f;
+          alpha[nb] = grow[nb] ? __builtin_amdgcn_exp2f(m_run[nb] - tm) : 1.0f;   // exp2(-inf) = 0 on the first key
+          m_run[nb] = grow[nb] ? tm : m_run[nb];
+          l_run[nb] *= alpha[nb];
+          neg_ref[nb] = (m_run[nb] == -INFINITY) ? 0.f : -m_run[nb];
+        }
+        grow_any = __any(grow[0] || grow[1]);
+        asm volatile("" : "+v"(l_run[0]), "+v"(l_run[1]), "+v"(neg_ref[0]), "+v"(neg_ref[1]));
+      }
+#pragma unroll
+      for (int e = 0; e < E1; ++e)
+        if (MAX_SL + 1 + e * (NM - MAX_SL - 1) / E1 == i) prob(e);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (grow_any) {
+      // O sits in the accumulation registers; walk it one 16-register block at a time so this
+      // rare path needs only a handful of temporaries
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o_acc[nb][db][r] *= alpha[nb];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---------------- region 2
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+      if (QK) {
+        const int ks = i / 2, nb = i % 2;
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s_next[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], ks == 0 ? zero : s_next[nb], 0, 0, 0);
+      }
+      if (i % 2 == 0) {
+        const int ts = (i / 2) / DB, db = (i / 2) % DB;
+        va[ts][db] = *(const bf16x8*)(vp + 32 * db * PC_FA_BN + (v_base ^ (32 * (j & 1) + 16 * ts)));
+      }
+#pragma unroll
+      for (int e = E1; e < 32; ++e)
+        if ((e - E1) * NM / (32 - E1) == i) prob(e);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // first S^T of a workgroup: operands of step 0, then the product
+  auto first_qk = [&](floatx16(&s)[2]) __attribute__((always_inline)) {
+    const uint16_t* kp = k_lds(0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) ka[ks] = *(const bf16x8*)(kp + (k_base ^ (16 * ks)));
-  };
-  // S^T(j) = K(j) Q^T for both row blocks; the K operand is read once and used twice
-  auto qk_mma = [&](floatx16(&s)[2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -334,121 +480,16 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       for (int nb = 0; nb < 2; ++nb)
         s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], s[nb], 0, 0, 0);
   };
-  auto pv_read = [&](int j) __attribute__((always_inline)) {
-    const uint16_t* vp = v_lds(j >> 1);                       // swizzle of row d + 32 = that of d
-#pragma unroll
-    for (int ts = 0; ts < 2; ++ts)
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-        va[ts][db] = *(const bf16x8*)(vp + 32 * db * PC_FA_BN + (v_base ^ (32 * (j & 1) + 16 * ts)));
-  };
-  // O^T += V^T(j) P^T(j); the V^T operand is read once and used for both row blocks
-  auto pv_mma = [&](const bf16x8(&p)[2][2]) __attribute__((always_inline)) {
+  // trailing O^T += V^T(j) P^T(j) of the last step
+  auto last_pv = [&](const u32x4(&p)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
-          o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ts][db], p[nb][ts], o_acc[nb][db], 0, 0, 0);
+          o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ts][db], *(const bf16x8*)&p[nb][ts], o_acc[nb][db], 0, 0, 0);
   };
-  // Softmax of step j, in two parts.  Register r of a row block at lane half hf is key
-  // 32 j + 16 (r / 8) + 8 hf + (r % 8).
-  // Part A: mask, row maximum of the step (in log2 units); returns whether any row needs a
-  // new reference.  Lazy rescale: the reference m_run only moves when a row's step maximum
-  // exceeds it by more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l keep their scale.
-  float tmax[2];
-  auto softmax_max = [&](auto mask_tag, int j, floatx16(&s)[2]) __attribute__((always_inline)) {
-    constexpr bool MASK = decltype(mask_tag)::value;
-    const int key0 = 32 * j;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      if (MASK) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + 16 * (r / 8) + 8 * hf + (r % 8);
-          if (key > max_key[nb]) s[nb][r] = -INFINITY;
-        }
-      }
-      float t = s[nb][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) t = fmaxf(t, s[nb][r]);
-      tmax[nb] = t;
-    }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) tmax[nb] = pc_xhalf_max(tmax[nb]) * c_log2;
-  };
-  auto rescale_if_needed = [&]() __attribute__((always_inline)) {
-    if (__any(tmax[0] > m_run[0] + 8.0f || tmax[1] > m_run[1] + 8.0f)) {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const float m_new = fmaxf(m_run[nb], tmax[nb]);
-        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-        m_run[nb] = m_new;
-        l_run[nb] *= alpha;
-        // O sits in the accumulation registers; walk it one 16-register block at a time so
-        // this rare path needs only a handful of temporaries
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o_acc[nb][db][r] *= alpha;
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-    }
-  };
-  // Part B: p = exp2(s - m_run) rounded to bf16 (the B operand of the second product), row sums
-  auto softmax_exp = [&](floatx16(&s)[2], bf16x8(&p)[2][2]) __attribute__((always_inline)) {
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      // rows with no visible key yet keep m = -inf; use 0 as the reference to avoid inf - inf
-      const float neg_ref = (m_run[nb] == -INFINITY) ? 0.f : -m_run[nb];
-      float psum = 0.f;
-#pragma unroll
-      for (int ts = 0; ts < 2; ++ts) {
-        u32x4 pk;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[nb][8 * ts + 2 * e], c_log2, neg_ref));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[nb][8 * ts + 2 * e + 1], c_log2, neg_ref));
-          psum += p0 + p1;
-          pk[e] = pack_bf16x2(p0, p1);
-        }
-        p[nb][ts] = *(bf16x8*)&pk;
-      }
-      l_run[nb] += psum;
-    }
-  };
-  using no_mask = std::integral_constant<bool, false>;
-  using with_mask = std::integral_constant<bool, true>;
-
-  // One step of the software pipeline, j = the step whose softmax runs now.  On entry `va`
-  // holds the V^T operands of step j - 1 (read during the previous step).
-  //   region 1:  LDS   K(j+1) operands   MFMA  O^T += V^T(j-1) P^T(j-1)   ||  VALU  row maxima of S^T(j)
-  //   (rare)     move the reference, rescale O and l
-  //   region 2:  LDS   V^T(j) operands   MFMA  S^T(j+1) = K(j+1) Q^T      ||  VALU  P^T(j) = exp2(S^T(j) - m)
-  // The streams of a region are independent, so they overlap inside the wavefront, and every
-  // operand read has a whole region to arrive.
-  // has_pv / has_qk are compile-time: the first step has no previous P V, the last no next K Q^T.
-  // Steps that lie wholly above a wavefront's rows on the diagonal are not skipped: their
-  // logits are masked to -inf, so they add exact zeros (straight-line code keeps the register
-  // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
-  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, int j, floatx16(&s_cur)[2],
-                  floatx16(&s_next)[2], bf16x8(&p_cur)[2][2],
-                  const bf16x8(&p_prev)[2][2]) __attribute__((always_inline)) {
-    if (decltype(has_qk)::value) qk_read(j + 1);
-    if (decltype(has_pv)::value) pv_mma(p_prev);
-    softmax_max(mask_tag, j, s_cur);
-    __builtin_amdgcn_sched_barrier(0);
-    rescale_if_needed();
-    __builtin_amdgcn_sched_barrier(0);
-    pv_read(j);
-    if (decltype(has_qk)::value) qk_mma(s_next);
-    softmax_exp(s_cur, p_cur);
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  using yes = std::integral_constant<bool, true>;
-  using no = std::integral_constant<bool, false>;
 
   if (T > 0) {
     // ---- prologue: tiles 0 and 1 must have landed before the first step; tiles 2, 3 stay in flight
@@ -462,8 +503,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     if (T > 3) load_v(3);
     if (T > 3) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
     __syncthreads();
-    qk_read(0);
-    qk_mma(s_buf[0]);
+    first_qk(s_buf[0]);
     step(with_mask{}, no{}, yes{}, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
 
     // One period = two steps.  Period p runs steps 2p+1 and 2p+2: it reads K tile p + 1 and the
@@ -492,7 +532,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     PC_WAIT_VMCNT(0);
     __syncthreads();
     step(with_mask{}, yes{}, no{}, 2 * T - 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
-    pv_mma(p_buf[1]);
+    last_pv(p_buf[1]);
   }
 
   // ---- epilogue: lane halves hold disjoint key subsets of the same query
@@ -536,7 +576,7 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   using SM = FlashSmem<D>;
   auto kern = flash_fwd_kernel<D, ROPE_Q, PARTIAL>;
   PC_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 SM::BYTES));
+                                 SM::BYTES + SM::STAGE_BYTES));
   const int G = a.n_q_heads / a.n_kv_heads;
   const int n_qt = (a.n_rows + PC_FA_BM - 1) / PC_FA_BM;
   const long long per_group = (long long)G * n_qt * a.n_parts_grid;
@@ -545,7 +585,7 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   PcProfScope prof(PC_KERNEL_FLASH, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES + SM::STAGE_BYTES, st, a);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }
