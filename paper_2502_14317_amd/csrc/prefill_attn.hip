@@ -280,32 +280,32 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     const int d = gi / 8, cv = (gi % 8) ^ pc_v_swz(d);
     v_goff = (uint32_t)(d * a.vt_d_stride * 2 + 16 * cv);
   }
+  // Loads go through buffer descriptors: the address is descriptor base + scalar offset +
+  // per-lane offset (no 64-bit vector arithmetic per load), and bytes past the descriptor's
+  // limit read as zero, so the rows of a last, partial K tile beyond the part's keys need no
+  // clamping (their logits are masked later).
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)kbase, 0, (int)(((long long)(a.n_keys - 1) * a.k_row_stride + D) * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)vtbase, 0, (int)((long long)D * a.vt_d_stride * 2), 0x00020000);
+  // instruction i (0 .. T_LD-1) of this wavefront for K tile t / V^T tile t
+  auto load_k_i = [&](int t, int i) __attribute__((always_inline)) {
+    const int soff = (int)(((long long)t * PC_FA_BN + i * K_ROWS_PER_LD) * a.k_row_stride * 2);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16,
+                                             (int)k_goff, soff, 0, 0);
+  };
+  auto load_v_i = [&](int t, int i) __attribute__((always_inline)) {
+    const int soff = (int)(((long long)i * V_ROWS_PER_LD * a.vt_d_stride + t * PC_FA_BN) * 2);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(v_lds(t) + 512 * (4 * i + wave_s)), 16,
+                                             (int)v_goff, soff, 0, 0);
+  };
   auto load_k = [&](int t) __attribute__((always_inline)) {
-    if ((t + 1) * PC_FA_BN <= a.n_keys) {
 #pragma unroll
-      for (int i = 0; i < T_LD; ++i) {
-        const char* blk = (const char*)(kbase + ((long long)t * PC_FA_BN + i * K_ROWS_PER_LD) * a.k_row_stride);
-        __builtin_amdgcn_global_load_lds((gptr_t)(blk + k_goff),
-                                         (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
-      }
-    } else {   // last, partial tile: rows past the end are clamped to the last row (masked later)
-#pragma unroll
-      for (int i = 0; i < T_LD; ++i) {
-        const int gi = 64 * (4 * i + wave_s) + lane;
-        const int r = gi / (D / 8), c = (gi % (D / 8)) ^ pc_k_swz<D>(r);
-        const int key = min(t * PC_FA_BN + r, a.n_keys - 1);
-        const uint16_t* src = kbase + (long long)key * a.k_row_stride + 8 * c;
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
-      }
-    }
+    for (int i = 0; i < T_LD; ++i) load_k_i(t, i);
   };
   auto load_v = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < T_LD; ++i) {
-      const char* blk = (const char*)(vtbase + (long long)i * V_ROWS_PER_LD * a.vt_d_stride + t * PC_FA_BN);
-      __builtin_amdgcn_global_load_lds((gptr_t)(blk + v_goff),
-                                       (lptr_t)(v_lds(t) + 512 * (4 * i + wave_s)), 16, 0, 0);
-    }
+    for (int i = 0; i < T_LD; ++i) load_v_i(t, i);
   };
   // s_waitcnt vmcnt(N): N newest loads of this wavefront may still be in flight
 #define PC_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
@@ -359,32 +359,44 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
   constexpr int NM = 2 * KS;                       // MFMAs per region (= 4 DB)
   constexpr int MAX_SL = NM / 4;                   // slices of region 1 that take the row maxima
-  constexpr int E1 = 12;                           // probabilities (of 32 per lane) computed in region 1
-  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, int j, floatx16(&s_cur)[2],
+  constexpr int G1 = 13;                           // probability groups (of 34 per step) placed in region 1
+  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, auto has_ld, int j, int t_ld, floatx16(&s_cur)[2],
                   floatx16(&s_next)[2], u32x4(&p_cur)[2][2],
                   const u32x4(&p_prev)[2][2]) __attribute__((always_inline)) {
     constexpr bool MASK = decltype(mask_tag)::value;
-    constexpr bool PV = decltype(has_pv)::value, QK = decltype(has_qk)::value;
+    constexpr bool PV = decltype(has_pv)::value, QK = decltype(has_qk)::value, LD = decltype(has_ld)::value;
     const uint16_t* kp = k_lds((j + 1) >> 1) + 32 * D * ((j + 1) & 1);   // swizzle of row r + 32 = that of r
     const uint16_t* vp = v_lds(j >> 1);                                   // swizzle of row d + 32 = that of d
-    float t[2] = {0.f, 0.f}, alpha[2] = {1.f, 1.f}, pe = 0.f;
+    float t[2] = {0.f, 0.f}, alpha[2] = {1.f, 1.f};
     bool grow_any = false;
     // probability e (0..31: row block e / 16, register e % 16) of this step
-    auto prob = [&](int e) __attribute__((always_inline)) {
-      const int nb = e / 16, r = e % 16;
-      const float pr = __builtin_amdgcn_exp2f(fmaf(s_cur[nb][r], c_log2, neg_ref[nb]));
-      l_run[nb] += pr;
-      // Opaque uses pin the instructions to the slice they were written in: without them the
-      // compiler sinks this (side-effect-free) arithmetic past the slice boundaries.
-      asm volatile("" : "+v"(l_run[nb]));
-      if (r % 2 == 0) {
-        pe = pr;
-      } else {
-        uint32_t w = pack_bf16x2(pe, pr);
-        asm volatile("" : "+v"(w));
-        p_cur[nb][r / 8][(r % 8) / 2] = w;
+    // The probabilities of a step go through three stages, one stage per group: group g takes
+    // the argument of element g, the exp2 of element g - 1 and the sum / bf16 pack of element
+    // g - 2, so no instruction waits on the one issued just before it.  Element e is register
+    // e % 16 of row block e / 16.  Opaque uses pin each group to the slice it is written in:
+    // without them the compiler sinks this (side-effect-free) arithmetic past slice boundaries.
+    float arg[32], pr[32];
+    auto prob_group = [&](int g) __attribute__((always_inline)) {
+      if (g >= 2 && g - 2 < 32) {
+        const int e = g - 2, nb = e / 16, r = e % 16;
+        l_run[nb] += pr[e];
+        asm volatile("" : "+v"(l_run[nb]));
+        if (r % 2 == 1) {
+          uint32_t w = pack_bf16x2(pr[e - 1], pr[e]);
+          asm volatile("" : "+v"(w));
+          p_cur[nb][r / 8][(r % 8) / 2] = w;
+        }
+      }
+      if (g >= 1 && g - 1 < 32) {
+        pr[g - 1] = __builtin_amdgcn_exp2f(arg[g - 1]);
+        asm volatile("" : "+v"(pr[g - 1]));
+      }
+      if (g < 32) {
+        arg[g] = fmaf(s_cur[g / 16][g % 16], c_log2, neg_ref[g / 16]);
+        asm volatile("" : "+v"(arg[g]));
       }
     };
+    constexpr int NG = 34;                         // groups per step
     // ---------------- region 1
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
@@ -393,7 +405,12 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
         o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
             va[ts][db], *(const bf16x8*)&p_prev[nb][ts], o_acc[nb][db], 0, 0, 0);
       }
-      if (QK && i % 2 == 0) ka[i / 2] = *(const bf16x8*)(kp + (k_base ^ (16 * (i / 2))));
+      if (QK && i < KS) ka[i] = *(const bf16x8*)(kp + (k_base ^ (16 * i)));
+      if (LD && i >= NM - 2 * T_LD) {               // one tile-load instruction per slice
+        const int li = i - (NM - 2 * T_LD);
+        if (li < T_LD) load_k_i(t_ld, li);
+        else load_v_i(t_ld, li - T_LD);
+      }
       if (MASK && i == 0) {
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
@@ -430,8 +447,8 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
         asm volatile("" : "+v"(l_run[0]), "+v"(l_run[1]), "+v"(neg_ref[0]), "+v"(neg_ref[1]));
       }
 #pragma unroll
-      for (int e = 0; e < E1; ++e)
-        if (MAX_SL + 1 + e * (NM - MAX_SL - 1) / E1 == i) prob(e);
+      for (int g = 0; g < G1; ++g)
+        if (MAX_SL + 1 + g * (NM - MAX_SL - 1) / G1 == i) prob_group(g);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (grow_any) {
@@ -455,13 +472,13 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         s_next[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], ks == 0 ? zero : s_next[nb], 0, 0, 0);
       }
-      if (i % 2 == 0) {
-        const int ts = (i / 2) / DB, db = (i / 2) % DB;
+      if (i < KS) {
+        const int ts = i / DB, db = i % DB;
         va[ts][db] = *(const bf16x8*)(vp + 32 * db * PC_FA_BN + (v_base ^ (32 * (j & 1) + 16 * ts)));
       }
 #pragma unroll
-      for (int e = E1; e < 32; ++e)
-        if ((e - E1) * NM / (32 - E1) == i) prob(e);
+      for (int g = G1; g < NG; ++g)
+        if ((g - G1) * NM / (NG - G1) == i) prob_group(g);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -504,25 +521,26 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     if (T > 3) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
     __syncthreads();
     first_qk(s_buf[0]);
-    step(with_mask{}, no{}, yes{}, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
+    step(with_mask{}, no{}, yes{}, no{}, 0, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
 
     // One period = two steps.  Period p runs steps 2p+1 and 2p+2: it reads K tile p + 1 and the
     // V^T tiles p and p + 1 (the latter only its first half, for the next period's first step).
-    // Right after its barrier it issues the loads of K(p + 4) and V(p + 4) into the buffers that
-    // held K(p) and V(p - 1), both last read before that barrier.  Tiles are first read three
-    // periods after their loads were issued, so before a barrier a wavefront only waits for the
-    // loads it issued two periods earlier (the two newest batches may stay in flight).
+    // After its barrier it issues the loads of K(p + 4) and V(p + 4), one instruction per slice
+    // of its first step, into the buffers that held K(p) and V(p - 1), both last read before
+    // that barrier.  Tiles are first read three periods after their loads were issued, so before
+    // a barrier a wavefront only waits for the loads it issued two periods earlier (the two
+    // newest batches may stay in flight).  Past the last tile the loads repeat tile T - 1 into
+    // buffers nobody reads again, which keeps the loop free of branches.
     auto period = [&](auto mask_tag, int p) __attribute__((always_inline)) {
       // Opaque no-ops on the address seeds: they stop the compiler from hoisting a dozen
       // loop-invariant per-lane addresses out of the loop into registers the loop cannot spare;
       // recomputing them costs a few vector-ALU instructions per period.
       asm volatile("" : "+v"(k_base), "+v"(v_base));
-      if (p + 3 < T) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
+      if (T >= 4) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
       __syncthreads();
-      if (p + 4 < T) load_k(p + 4);
-      if (p + 4 < T) load_v(p + 4);
-      step(mask_tag, yes{}, yes{}, 2 * p + 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
-      step(mask_tag, yes{}, yes{}, 2 * p + 2, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
+      const int t_ld = min(p + 4, T - 1);
+      step(mask_tag, yes{}, yes{}, yes{}, 2 * p + 1, t_ld, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
+      step(mask_tag, yes{}, yes{}, no{}, 2 * p + 2, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
     };
     const int n_plain = min(T - 1, max(0, (J0 - 1) / 2));   // periods whose steps need no mask
     int p = 0;
@@ -531,7 +549,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     // ---- last period: step 2T-1 and the trailing P V
     PC_WAIT_VMCNT(0);
     __syncthreads();
-    step(with_mask{}, yes{}, no{}, 2 * T - 1, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
+    step(with_mask{}, yes{}, no{}, no{}, 2 * T - 1, 0, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
     last_pv(p_buf[1]);
   }
 
@@ -584,6 +602,10 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   const long long blocks = (groups + 7) / 8 * per_group * 8;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
+  // tile loads address one (sequence, part, head) region with 32-bit byte offsets
+  if ((long long)a.n_keys * a.k_row_stride * 2 >= 0x7fffffffLL ||
+      (long long)D * a.vt_d_stride * 2 >= 0x7fffffffLL)
+    return PC_ERR_SHAPE;
   PcProfScope prof(PC_KERNEL_FLASH, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES + SM::STAGE_BYTES, st, a);
   PC_LAUNCH_CHECK();
