@@ -26,10 +26,11 @@
 #include <math.h>
 #include <type_traits>
 
-#define PC_FA_WAVES 4
+#define PC_FA_NB 1                   // 32-row blocks per wavefront
+#define PC_FA_WAVES 4                // wavefronts per workgroup (one per SIMD); two workgroups share a CU
 #define PC_FA_THREADS (PC_FA_WAVES * PC_WAVE)
-#define PC_FA_BM (PC_FA_WAVES * 64)
-#define PC_FA_BN 64
+#define PC_FA_BM (PC_FA_WAVES * 32 * PC_FA_NB)   // query rows per workgroup
+#define PC_FA_BN 64                  // keys per tile
 #define PC_LOG2E 1.4426950408889634f
 #define PC_LN2 0.6931471805599453f
 
@@ -145,12 +146,12 @@ int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void
 // With these, the 16 lanes served together by a 16-byte LDS read hit 16 distinct bank groups.
 template <int D>
 struct FlashSmem {
-  static constexpr int KBUF = 4;                   // K tile t lives in buffer t % 4
-  static constexpr int VBUF = 5;                   // V^T tile t in buffer t % 5 (read one period early)
+  static constexpr int KBUF = 2;                   // K tile t lives in buffer t % 2
+  static constexpr int VBUF = 3;                   // V^T tile t in buffer t % 3 (read one period early)
   static constexpr int K_ELEMS = PC_FA_BN * D;
   static constexpr int V_ELEMS = D * PC_FA_BN;
   static constexpr int BYTES = (KBUF * K_ELEMS + VBUF * V_ELEMS) * 2;
-  static constexpr int STAGE_BYTES = PC_FA_THREADS * 16;   // one 16-byte slot per lane behind the tiles
+  static constexpr int STAGE_BYTES = 0;   // the Q staging slots alias tile memory
 };
 template <int D>
 __device__ __forceinline__ int pc_k_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
@@ -162,7 +163,7 @@ __device__ __forceinline__ int pc_key_of_row(int m) {
 }
 
 template <int D, bool ROPE_Q, bool PARTIAL>
-__global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a) {
+__global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs a) {
   using SM = FlashSmem<D>;
   constexpr int KS = D / 16;        // k-steps of the first product (over head_dim)
   constexpr int DB = D / 32;        // 32-row blocks of O^T (over head_dim)
@@ -191,8 +192,9 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   const int tid = threadIdx.x, lane = tid % PC_WAVE, wave = tid / PC_WAVE;
   const int hf = lane / 32, n = lane % 32;
   const int row0_wg = qt * PC_FA_BM;
-  const int row0 = row0_wg + 64 * wave;           // first query row of this wavefront
-  int my_row[2], max_key[2];
+  constexpr int NB = PC_FA_NB;
+  const int row0 = row0_wg + 32 * NB * wave;      // first query row of this wavefront
+  int my_row[NB], max_key[NB];
 
   // ---- keys of this workgroup: [0, key_end) of the part
   const int n_valid = a.part_len ? min(max(a.part_len[seq * a.n_parts_grid + part], 0), a.n_keys)
@@ -208,10 +210,10 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   const uint16_t* vtbase = (const uint16_t*)a.v_t + seq * a.vt_seq_stride +
                            part * a.vt_part_stride + g * a.vt_head_stride;
 
-  // ---- Q^T as B operand, two 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7
-  bf16x8 bq[2][KS];
+  // ---- Q^T as B operand, NB 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7
+  bf16x8 bq[NB][KS];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < NB; ++nb) {
     my_row[nb] = row0 + 32 * nb + n;
     max_key[nb] = min(my_row[nb] + a.causal_offset, n_valid - 1);
     const int ld_row = min(my_row[nb], a.n_rows - 1);
@@ -248,9 +250,9 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // the architectural registers are needed for O^T, S^T and P^T.  The only way to name that file
   // from C++ is a load, so each lane bounces its values through 16 private bytes of LDS.
   {
-    uint16_t* stage = smem + SM::BYTES / 2 + 8 * tid;
+    uint16_t* stage = smem + 8 * tid;               // tile memory, not yet in use
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         *(bf16x8*)stage = bq[nb][ks];
@@ -258,20 +260,22 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
         asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=a"(parked) : "v"((uint32_t)(uintptr_t)stage) : "memory");
         bq[nb][ks] = parked;
       }
+    __syncthreads();                                // every lane has its values back before tiles arrive
   }
 
   // ---- cooperative tile loads, straight from global memory into LDS.  Wavefront w issues
-  //      instruction i for the 1 KiB block b = 4 i + w of the tile; lane l fills granule
+  //      instruction i for the 1 KiB block b = WAVES i + w of the tile; lane l fills granule
   //      64 b + l of the tile and therefore fetches the source granule the swizzle puts there.
-  constexpr int T_LD = D / 32;                     // load instructions per thread per tile
+  constexpr int WAVES = PC_FA_WAVES;
+  constexpr int T_LD = D / 8 / WAVES;              // load instructions per wavefront per tile
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
   // Per-lane byte offset of the source granule relative to the block's first row: the same for
   // every load instruction i (the swizzle of row r + 16 i equals that of r) and every tile, so a
   // tile load is a scalar base plus one constant vector offset.
-  constexpr int K_ROWS_PER_LD = 4 * 512 / D;       // tile rows covered by one instruction of all 4 waves
-  constexpr int V_ROWS_PER_LD = 4 * 512 / PC_FA_BN;
+  constexpr int K_ROWS_PER_LD = WAVES * 512 / D;   // tile rows covered by one instruction of all wavefronts
+  constexpr int V_ROWS_PER_LD = WAVES * 512 / PC_FA_BN;
   uint32_t k_goff, v_goff;
   {
     const int gi = 64 * wave_s + lane;
@@ -291,12 +295,12 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // instruction i (0 .. T_LD-1) of this wavefront for K tile t / V^T tile t
   auto load_k_i = [&](int t, int i) __attribute__((always_inline)) {
     const int soff = (int)(((long long)t * PC_FA_BN + i * K_ROWS_PER_LD) * a.k_row_stride * 2);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)(k_lds(t) + 512 * (4 * i + wave_s)), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)(k_lds(t) + 512 * (WAVES * i + wave_s)), 16,
                                              (int)k_goff, soff, 0, 0);
   };
   auto load_v_i = [&](int t, int i) __attribute__((always_inline)) {
     const int soff = (int)(((long long)i * V_ROWS_PER_LD * a.vt_d_stride + t * PC_FA_BN) * 2);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(v_lds(t) + 512 * (4 * i + wave_s)), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(v_lds(t) + 512 * (WAVES * i + wave_s)), 16,
                                              (int)v_goff, soff, 0, 0);
   };
   auto load_k = [&](int t) __attribute__((always_inline)) {
@@ -310,21 +314,23 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // s_waitcnt vmcnt(N): N newest loads of this wavefront may still be in flight
 #define PC_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
 
-  floatx16 o_acc[2][DB];
+  floatx16 o_acc[NB][DB];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
+  for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[nb][db][r] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_run[NB], l_run[NB], neg_ref[NB];        // reference, row sum, -reference (0 while a row has seen no key)
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; neg_ref[nb] = 0.f; }
   const float c_log2 = a.scale * PC_LOG2E;
   const int krow = pc_key_of_row(n);               // LDS row this lane feeds into MFMA row n
 
   // A step is 32 keys.  Step j reads K rows / V^T columns 32 (j & 1) .. + 31 of tile j >> 1.
   // S^T of step j lives in s_buf[j & 1], its probabilities P^T (bf16) in p_buf[j & 1].
-  floatx16 s_buf[2][2];                            // [step parity][row block]
-  u32x4 p_buf[2][2][2];                            // [step parity][row block][16-key k-step], bf16 pairs
+  floatx16 s_buf[2][NB];                           // [step parity][row block]
+  u32x4 p_buf[2][NB][2];                            // [step parity][row block][16-key k-step], bf16 pairs
 
   // Per-lane element offsets of the MFMA A operands inside a tile.  The swizzle is an XOR on the
   // granule bits only, so one base per operand kind suffices: offset(c) = base ^ (8 c) with the
@@ -334,7 +340,6 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 
   // MFMA A operands, read from LDS one region ahead of their use
   bf16x8 ka[KS], va[2][DB];                        // K rows of a step; V^T [16-key k-step][d block]
-  float neg_ref[2] = {0.f, 0.f};                   // -m_run, or 0 while a row has seen no key
   using no_mask = std::integral_constant<bool, false>;
   using with_mask = std::integral_constant<bool, true>;
   using yes = std::integral_constant<bool, true>;
@@ -357,17 +362,21 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
   // Steps that lie wholly above a wavefront's rows on the diagonal are not skipped: their
   // logits are masked to -inf, so they add exact zeros (straight-line code keeps the register
   // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
-  constexpr int NM = 2 * KS;                       // MFMAs per region (= 4 DB)
+  constexpr int NM = NB * KS;                      // MFMAs per region (= 2 NB DB)
   constexpr int MAX_SL = NM / 4;                   // slices of region 1 that take the row maxima
-  constexpr int G1 = 13;                           // probability groups (of 34 per step) placed in region 1
-  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, auto has_ld, int j, int t_ld, floatx16(&s_cur)[2],
-                  floatx16(&s_next)[2], u32x4(&p_cur)[2][2],
-                  const u32x4(&p_prev)[2][2]) __attribute__((always_inline)) {
+  constexpr int NG = 16 * NB + 2;                  // probability groups per step
+  // groups placed in region 1: the share of its free slices among all slices that take groups
+  constexpr int G1 = NG * (NM - MAX_SL - 1) / (2 * NM - MAX_SL - 1);
+  auto step = [&](auto mask_tag, auto has_pv, auto has_qk, auto has_ld, int j, int t_ld, floatx16(&s_cur)[NB],
+                  floatx16(&s_next)[NB], u32x4(&p_cur)[NB][2],
+                  const u32x4(&p_prev)[NB][2]) __attribute__((always_inline)) {
     constexpr bool MASK = decltype(mask_tag)::value;
     constexpr bool PV = decltype(has_pv)::value, QK = decltype(has_qk)::value, LD = decltype(has_ld)::value;
     const uint16_t* kp = k_lds((j + 1) >> 1) + 32 * D * ((j + 1) & 1);   // swizzle of row r + 32 = that of r
     const uint16_t* vp = v_lds(j >> 1);                                   // swizzle of row d + 32 = that of d
-    float t[2] = {0.f, 0.f}, alpha[2] = {1.f, 1.f};
+    float t[NB], alpha[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) { t[nb] = 0.f; alpha[nb] = 1.f; }
     bool grow_any = false;
     // probability e (0..31: row block e / 16, register e % 16) of this step
     // The probabilities of a step go through three stages, one stage per group: group g takes
@@ -375,9 +384,9 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     // g - 2, so no instruction waits on the one issued just before it.  Element e is register
     // e % 16 of row block e / 16.  Opaque uses pin each group to the slice it is written in:
     // without them the compiler sinks this (side-effect-free) arithmetic past slice boundaries.
-    float arg[32], pr[32];
+    float arg[16 * NB], pr[16 * NB];
     auto prob_group = [&](int g) __attribute__((always_inline)) {
-      if (g >= 2 && g - 2 < 32) {
+      if (g >= 2 && g - 2 < 16 * NB) {
         const int e = g - 2, nb = e / 16, r = e % 16;
         l_run[nb] += pr[e];
         asm volatile("" : "+v"(l_run[nb]));
@@ -387,21 +396,20 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
           p_cur[nb][r / 8][(r % 8) / 2] = w;
         }
       }
-      if (g >= 1 && g - 1 < 32) {
+      if (g >= 1 && g - 1 < 16 * NB) {
         pr[g - 1] = __builtin_amdgcn_exp2f(arg[g - 1]);
         asm volatile("" : "+v"(pr[g - 1]));
       }
-      if (g < 32) {
+      if (g < 16 * NB) {
         arg[g] = fmaf(s_cur[g / 16][g % 16], c_log2, neg_ref[g / 16]);
         asm volatile("" : "+v"(arg[g]));
       }
     };
-    constexpr int NG = 34;                         // groups per step
     // ---------------- region 1
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
       if (PV) {
-        const int ts = i / (2 * DB), db = (i / 2) % DB, nb = i % 2;
+        const int ts = i / (NB * DB), db = (i / NB) % DB, nb = i % NB;
         o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
             va[ts][db], *(const bf16x8*)&p_prev[nb][ts], o_acc[nb][db], 0, 0, 0);
       }
@@ -413,7 +421,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       }
       if (MASK && i == 0) {
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = 32 * j + 16 * (r / 8) + 8 * hf + (r % 8);
@@ -425,26 +433,29 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 #pragma unroll
         for (int q = i * (8 / MAX_SL); q < (i + 1) * (8 / MAX_SL); ++q)
 #pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
+          for (int nb = 0; nb < NB; ++nb) {
             if (q == 0) t[nb] = fmaxf(fmaxf(s_cur[nb][0], s_cur[nb][1]), s_cur[nb][2]);
             else if (q < 7) t[nb] = fmaxf(fmaxf(t[nb], s_cur[nb][2 * q + 1]), s_cur[nb][2 * q + 2]);
             else t[nb] = fmaxf(t[nb], s_cur[nb][15]);
           }
-        asm volatile("" : "+v"(t[0]), "+v"(t[1]));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(t[nb]));
       }
       if (i == MAX_SL) {
-        bool grow[2];
+        bool grow = false;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
+        for (int nb = 0; nb < NB; ++nb) {
           const float tm = pc_xhalf_max(t[nb]) * c_log2;
-          grow[nb] = tm > m_run[nb] + 8.0f;
-          alpha[nb] = grow[nb] ? __builtin_amdgcn_exp2f(m_run[nb] - tm) : 1.0f;   // exp2(-inf) = 0 on the first key
-          m_run[nb] = grow[nb] ? tm : m_run[nb];
+          const bool gr = tm > m_run[nb] + 8.0f;
+          grow |= gr;
+          alpha[nb] = gr ? __builtin_amdgcn_exp2f(m_run[nb] - tm) : 1.0f;   // exp2(-inf) = 0 on the first key
+          m_run[nb] = gr ? tm : m_run[nb];
           l_run[nb] *= alpha[nb];
           neg_ref[nb] = (m_run[nb] == -INFINITY) ? 0.f : -m_run[nb];
         }
-        grow_any = __any(grow[0] || grow[1]);
-        asm volatile("" : "+v"(l_run[0]), "+v"(l_run[1]), "+v"(neg_ref[0]), "+v"(neg_ref[1]));
+        grow_any = __any(grow);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(l_run[nb]), "+v"(neg_ref[nb]));
       }
 #pragma unroll
       for (int g = 0; g < G1; ++g)
@@ -455,7 +466,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       // O sits in the accumulation registers; walk it one 16-register block at a time so this
       // rare path needs only a handful of temporaries
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -468,7 +479,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
       if (QK) {
-        const int ks = i / 2, nb = i % 2;
+        const int ks = i / NB, nb = i % NB;
         const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         s_next[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], ks == 0 ? zero : s_next[nb], 0, 0, 0);
       }
@@ -483,28 +494,28 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     }
   };
   // first S^T of a workgroup: operands of step 0, then the product
-  auto first_qk = [&](floatx16(&s)[2]) __attribute__((always_inline)) {
+  auto first_qk = [&](floatx16(&s)[NB]) __attribute__((always_inline)) {
     const uint16_t* kp = k_lds(0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) ka[ks] = *(const bf16x8*)(kp + (k_base ^ (16 * ks)));
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
         s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], s[nb], 0, 0, 0);
   };
   // trailing O^T += V^T(j) P^T(j) of the last step
-  auto last_pv = [&](const u32x4(&p)[2][2]) __attribute__((always_inline)) {
+  auto last_pv = [&](const u32x4(&p)[NB][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
           o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ts][db], *(const bf16x8*)&p[nb][ts], o_acc[nb][db], 0, 0, 0);
   };
 
@@ -512,13 +523,9 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
     // ---- prologue: tiles 0 and 1 must have landed before the first step; tiles 2, 3 stay in flight
     load_k(0);
     load_v(0);
-    if (T > 1) load_k(1);
-    if (T > 1) load_v(1);
-    if (T > 2) load_k(2);
-    if (T > 2) load_v(2);
-    if (T > 3) load_k(3);
-    if (T > 3) load_v(3);
-    if (T > 3) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
+    load_k(min(1, T - 1));
+    load_v(min(1, T - 1));
+    PC_WAIT_VMCNT(0);
     __syncthreads();
     first_qk(s_buf[0]);
     step(with_mask{}, no{}, yes{}, no{}, 0, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
@@ -536,9 +543,9 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
       // loop-invariant per-lane addresses out of the loop into registers the loop cannot spare;
       // recomputing them costs a few vector-ALU instructions per period.
       asm volatile("" : "+v"(k_base), "+v"(v_base));
-      if (T >= 4) { PC_WAIT_VMCNT(4 * T_LD); } else { PC_WAIT_VMCNT(0); }
+      PC_WAIT_VMCNT(0);
       __syncthreads();
-      const int t_ld = min(p + 4, T - 1);
+      const int t_ld = min(p + 2, T - 1);
       step(mask_tag, yes{}, yes{}, yes{}, 2 * p + 1, t_ld, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
       step(mask_tag, yes{}, yes{}, no{}, 2 * p + 2, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
     };
@@ -555,7 +562,7 @@ __global__ __launch_bounds__(PC_FA_THREADS) void flash_fwd_kernel(PcFlashArgs a)
 
   // ---- epilogue: lane halves hold disjoint key subsets of the same query
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
+  for (int nb = 0; nb < NB; ++nb) {
     const float l = pc_xhalf_sum(l_run[nb]);
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
     const float lse = l > 0.f ? m_run[nb] * PC_LN2 + logf(l) : -INFINITY;
