@@ -210,7 +210,10 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   const uint16_t* vtbase = (const uint16_t*)a.v_t + seq * a.vt_seq_stride +
                            part * a.vt_part_stride + g * a.vt_head_stride;
 
-  // ---- Q^T as B operand, NB 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7
+  // ---- Q^T as B operand, NB 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7.
+  //      The softmax scale and log2(e) are folded into Q before its rounding to bf16, so the
+  //      first product yields logits in log2 units and the exponent needs no multiply.
+  const float c_log2 = a.scale * PC_LOG2E;
   bf16x8 bq[NB][KS];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -231,8 +234,8 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
           const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
           const float x1l = bf16_lo_to_f32(x1[e]), x1h = bf16_hi_to_f32(x1[e]);
           const float x2l = bf16_lo_to_f32(x2[e]), x2h = bf16_hi_to_f32(x2[e]);
-          ra[e] = pack_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y);
-          rbv[e] = pack_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y);
+          ra[e] = pack_bf16x2((x1l * c0.x - x2l * c0.y) * c_log2, (x1h * c1.x - x2h * c1.y) * c_log2);
+          rbv[e] = pack_bf16x2((x2l * c0.x + x1l * c0.y) * c_log2, (x2h * c1.x + x1h * c1.y) * c_log2);
         }
         bq[nb][ks] = *(bf16x8*)&ra;
         bq[nb][ks + KS / 2] = *(bf16x8*)&rbv;
@@ -241,7 +244,10 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const u32x4 x = *(const u32x4*)(qrow + 16 * ks + 8 * hf);
-        bq[nb][ks] = *(bf16x8*)&x;
+        u32x4 y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = pack_bf16x2(bf16_lo_to_f32(x[e]) * c_log2, bf16_hi_to_f32(x[e]) * c_log2);
+        bq[nb][ks] = *(bf16x8*)&y;
       }
     }
   }
@@ -321,10 +327,17 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[nb][db][r] = 0.f;
-  float m_run[NB], l_run[NB], neg_ref[NB];        // reference, row sum, -reference (0 while a row has seen no key)
+  // Softmax state per row: reference m_run (log2 units), row sum l_run, and -m_run replicated
+  // over an accumulator tile: it is the C operand of the first MFMA of every S^T, so S^T comes
+  // out of the matrix pipe already relative to the reference.
+  float m_run[NB], l_run[NB];
+  floatx16 negm[NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; neg_ref[nb] = 0.f; }
-  const float c_log2 = a.scale * PC_LOG2E;
+  for (int nb = 0; nb < NB; ++nb) {
+    m_run[nb] = 0.f; l_run[nb] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[nb][r] = 0.f;
+  }
   const int krow = pc_key_of_row(n);               // LDS row this lane feeds into MFMA row n
 
   // A step is 32 keys.  Step j reads K rows / V^T columns 32 (j & 1) .. + 31 of tile j >> 1.
@@ -364,7 +377,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
   constexpr int NM = NB * KS;                      // MFMAs per region (= 2 NB DB)
   constexpr int MAX_SL = NM / 4;                   // slices of region 1 that take the row maxima
-  constexpr int NG = 16 * NB + 2;                  // probability groups per step
+  constexpr int NG = 16 * NB + 1;                  // probability groups per step
   // groups placed in region 1: the share of its free slices among all slices that take groups
   constexpr int G1 = NG * (NM - MAX_SL - 1) / (2 * NM - MAX_SL - 1);
   auto step = [&](auto mask_tag, auto has_pv, auto has_qk, auto has_ld, int j, int t_ld, floatx16(&s_cur)[NB],
@@ -379,15 +392,15 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     for (int nb = 0; nb < NB; ++nb) { t[nb] = 0.f; alpha[nb] = 1.f; }
     bool grow_any = false;
     // probability e (0..31: row block e / 16, register e % 16) of this step
-    // The probabilities of a step go through three stages, one stage per group: group g takes
-    // the argument of element g, the exp2 of element g - 1 and the sum / bf16 pack of element
-    // g - 2, so no instruction waits on the one issued just before it.  Element e is register
-    // e % 16 of row block e / 16.  Opaque uses pin each group to the slice it is written in:
-    // without them the compiler sinks this (side-effect-free) arithmetic past slice boundaries.
-    float arg[16 * NB], pr[16 * NB];
+    // The probabilities of a step go through two stages, one stage per group: group g takes
+    // the exp2 of element g and the sum / bf16 pack of element g - 1, so no instruction waits on
+    // the one issued just before it.  Element e is register e % 16 of row block e / 16.  Opaque
+    // uses pin each group to the slice it is written in: without them the compiler sinks this
+    // (side-effect-free) arithmetic past slice boundaries.
+    float pr[16 * NB];
     auto prob_group = [&](int g) __attribute__((always_inline)) {
-      if (g >= 2 && g - 2 < 16 * NB) {
-        const int e = g - 2, nb = e / 16, r = e % 16;
+      if (g >= 1 && g - 1 < 16 * NB) {
+        const int e = g - 1, nb = e / 16, r = e % 16;
         l_run[nb] += pr[e];
         asm volatile("" : "+v"(l_run[nb]));
         if (r % 2 == 1) {
@@ -396,13 +409,9 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
           p_cur[nb][r / 8][(r % 8) / 2] = w;
         }
       }
-      if (g >= 1 && g - 1 < 16 * NB) {
-        pr[g - 1] = __builtin_amdgcn_exp2f(arg[g - 1]);
-        asm volatile("" : "+v"(pr[g - 1]));
-      }
       if (g < 16 * NB) {
-        arg[g] = fmaf(s_cur[g / 16][g % 16], c_log2, neg_ref[g / 16]);
-        asm volatile("" : "+v"(arg[g]));
+        pr[g] = __builtin_amdgcn_exp2f(s_cur[g / 16][g % 16]);
+        asm volatile("" : "+v"(pr[g]));
       }
     };
     // ---------------- region 1
@@ -442,20 +451,27 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
         for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(t[nb]));
       }
       if (i == MAX_SL) {
-        bool grow = false;
+        // Does any row's maximum leave the window of its reference?  S^T is already relative
+        // to the reference, so the test is a compare with a constant; everything else is rare.
+        bool grow = !PV;                            // the first step sets the reference exactly
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          const float tm = pc_xhalf_max(t[nb]) * c_log2;
-          const bool gr = tm > m_run[nb] + 8.0f;
-          grow |= gr;
-          alpha[nb] = gr ? __builtin_amdgcn_exp2f(m_run[nb] - tm) : 1.0f;   // exp2(-inf) = 0 on the first key
-          m_run[nb] = gr ? tm : m_run[nb];
-          l_run[nb] *= alpha[nb];
-          neg_ref[nb] = (m_run[nb] == -INFINITY) ? 0.f : -m_run[nb];
-        }
+        for (int nb = 0; nb < NB; ++nb) grow |= t[nb] > 8.0f;
         grow_any = __any(grow);
+        if (grow_any) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(l_run[nb]), "+v"(neg_ref[nb]));
+          for (int nb = 0; nb < NB; ++nb) {
+            const float tm = pc_xhalf_max(t[nb]);   // both lane halves hold keys of the same row
+            const bool gr = PV ? tm > 8.0f : tm != -INFINITY;
+            const float delta = gr ? tm : 0.f;
+            alpha[nb] = PV ? __builtin_amdgcn_exp2f(-delta) : 1.0f;   // nothing accumulated before the first step
+            m_run[nb] += delta;
+            l_run[nb] *= alpha[nb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { negm[nb][r] = -m_run[nb]; s_cur[nb][r] -= delta; }
+          }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+v"(l_run[nb]));
       }
 #pragma unroll
       for (int g = 0; g < G1; ++g)
@@ -480,8 +496,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     for (int i = 0; i < NM; ++i) {
       if (QK) {
         const int ks = i / NB, nb = i % NB;
-        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s_next[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], ks == 0 ? zero : s_next[nb], 0, 0, 0);
+        s_next[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], bq[nb][ks], ks == 0 ? negm[nb] : s_next[nb], 0, 0, 0);
       }
       if (i < KS) {
         const int ts = i / DB, db = i % DB;
