@@ -252,23 +252,6 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     }
   }
 
-  // Park Q^T in the accumulation-register file (MFMA reads its B operand from there directly):
-  // the architectural registers are needed for O^T, S^T and P^T.  The only way to name that file
-  // from C++ is a load, so each lane bounces its values through 16 private bytes of LDS.
-  {
-    uint16_t* stage = smem + 8 * tid;               // tile memory, not yet in use
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        *(bf16x8*)stage = bq[nb][ks];
-        bf16x8 parked;
-        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=a"(parked) : "v"((uint32_t)(uintptr_t)stage) : "memory");
-        bq[nb][ks] = parked;
-      }
-    __syncthreads();                                // every lane has its values back before tiles arrive
-  }
-
   // ---- cooperative tile loads, straight from global memory into LDS.  Wavefront w issues
   //      instruction i for the 1 KiB block b = WAVES i + w of the tile; lane l fills granule
   //      64 b + l of the tile and therefore fetches the source granule the swizzle puts there.
