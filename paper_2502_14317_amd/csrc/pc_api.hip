@@ -90,7 +90,7 @@ static float eff_scale(float scale, int head_dim) {
 }
 
 struct PrefillWs {
-  size_t table, v_t, k_rope, ml, total;
+  size_t table, v_img, k_img, k_rope, ml, total;
   int Lp;
 };
 
@@ -100,7 +100,9 @@ static PrefillWs prefill_ws_layout(const pc_shape* s) {
   w.Lp = (int)((L + 63) / 64 * 64);
   size_t off = 0;
   w.table = off; off = pc_align_up(off + L * (s->head_dim / 2) * sizeof(float2), kAlign);
-  w.v_t = off;   off = pc_align_up(off + (size_t)s->n_chunks * s->n_kv_heads * s->head_dim * w.Lp * 2, kAlign);
+  const size_t img_bytes = (size_t)s->n_chunks * s->n_kv_heads * s->head_dim * w.Lp * 2;   // tile images
+  w.v_img = off; off = pc_align_up(off + img_bytes, kAlign);
+  w.k_img = off; off = pc_align_up(off + img_bytes, kAlign);
   w.k_rope = off; off = pc_align_up(off + (size_t)s->n_chunks * L * s->n_kv_heads * s->head_dim * 2, kAlign);
   w.ml = off;    off = pc_align_up(off + pc_scores_ml_bytes(s), kAlign);
   w.total = off;
@@ -140,22 +142,21 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
   float2* table = (float2*)(base + w.table);
-  void* v_t = base + w.v_t;
+  void* v_img = base + w.v_img;
+  void* k_img = base + w.k_img;
   void* kr = k_rope ? k_rope : (void*)(base + w.k_rope);
   const int L = s->chunk_len + s->query_len, D = s->head_dim;
 
   rc = pc_launch_rope_table(table, L, D, s->rope_base, st);
   if (rc != PC_OK) return rc;
-  rc = pc_launch_kv_prepass(k, v, table, kr, v_t, s->n_chunks, L, w.Lp, s->n_kv_heads, D, st);
+  rc = pc_launch_kv_prepass(k, v, table, kr, k_img, v_img, s->n_chunks, L, w.Lp, s->n_kv_heads, D, st);
   if (rc != PC_OK) return rc;
 
   PcFlashArgs a = {};
-  a.q = q; a.k = kr; a.v_t = v_t; a.table = table; a.o = o; a.lse = lse;
+  a.q = q; a.k_img = k_img; a.v_img = v_img; a.table = table; a.o = o; a.lse = lse;
   a.part_o = nullptr; a.part_lse = nullptr; a.part_len = nullptr;
-  a.k_seq_stride = (long long)L * s->n_kv_heads * D; a.k_part_stride = 0;
-  a.k_head_stride = D; a.k_row_stride = (long long)s->n_kv_heads * D;
-  a.vt_seq_stride = (long long)s->n_kv_heads * D * w.Lp; a.vt_part_stride = 0;
-  a.vt_head_stride = (long long)D * w.Lp; a.vt_d_stride = w.Lp;
+  a.img_seq_stride = (long long)s->n_kv_heads * (w.Lp / 64); a.img_part_stride = 0;
+  a.img_head_stride = w.Lp / 64;
   a.n_seq = s->n_chunks; a.n_rows = L; a.n_keys = L;
   a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads; a.head_dim = D;
   a.n_parts_grid = 1; a.n_parts_total = 1; a.part0 = 0;
@@ -225,7 +226,7 @@ extern "C" int pc_gather_kv(const void* k_src, const void* v_src, const int32_t*
 
 // ---------------------------------------------------------------------------- parallel attention
 struct ParWs {
-  size_t q_rot, part_o, part_lse, vt_seg, vt_self, total;
+  size_t q_rot, part_o, part_lse, v_seg, k_seg, v_self, k_self, total;
   int n_parts, ktp, nqp;
   bool small;
 };
@@ -248,12 +249,14 @@ static ParWs par_ws_layout(int batch, int n_q, int n_seg, int k_t, int n_q_heads
   w.q_rot = off;    off = pc_align_up(off + rows * D * 2, kAlign);
   w.part_o = off;   off = pc_align_up(off + rows * (size_t)w.n_parts * D * sizeof(float), kAlign);
   w.part_lse = off; off = pc_align_up(off + rows * (size_t)w.n_parts * sizeof(float), kAlign);
-  w.vt_seg = off;
-  w.vt_self = off;
-  if (!w.small) {
-    off = pc_align_up(off + (size_t)batch * n_seg * n_kv_heads * D * w.ktp * 2, kAlign);
-    w.vt_self = off;
-    if (has_self) off = pc_align_up(off + (size_t)batch * n_kv_heads * D * w.nqp * 2, kAlign);
+  w.v_seg = w.k_seg = w.v_self = w.k_self = off;
+  if (!w.small) {   // tile images of the segments and of the self segment (K and V^T)
+    const size_t seg_bytes = (size_t)batch * n_seg * n_kv_heads * D * w.ktp * 2;
+    const size_t self_bytes = has_self ? (size_t)batch * n_kv_heads * D * w.nqp * 2 : 0;
+    w.v_seg = off;  off = pc_align_up(off + seg_bytes, kAlign);
+    w.k_seg = off;  off = pc_align_up(off + seg_bytes, kAlign);
+    w.v_self = off; off = pc_align_up(off + self_bytes, kAlign);
+    w.k_self = off; off = pc_align_up(off + self_bytes, kAlign);
   }
   w.total = off;
   return w;
@@ -324,31 +327,25 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
   a.n_seq = batch; a.n_rows = n_q; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
   a.head_dim = D; a.n_parts_total = w.n_parts; a.q_pos0 = 0; a.scale = scale;
   if (n_seg > 0) {
-    void* vt = base + w.vt_seg;
-    rc = pc_launch_kv_prepass(nullptr, vc, nullptr, nullptr, vt, batch * n_seg * n_kv_heads, k_t,
-                              w.ktp, 1, D, st);
+    // compacted K is already rotated: copy it into tile images next to those of V^T
+    rc = pc_launch_kv_prepass(kc, vc, nullptr, nullptr, base + w.k_seg, base + w.v_seg,
+                              batch * n_seg * n_kv_heads, k_t, w.ktp, 1, D, st);
     if (rc != PC_OK) return rc;
-    a.k = kc; a.v_t = vt; a.part_len = seg_len;
-    a.k_seq_stride = (long long)n_seg * n_kv_heads * k_t * D;
-    a.k_part_stride = (long long)n_kv_heads * k_t * D;
-    a.k_head_stride = (long long)k_t * D; a.k_row_stride = D;
-    a.vt_seq_stride = (long long)n_seg * n_kv_heads * D * w.ktp;
-    a.vt_part_stride = (long long)n_kv_heads * D * w.ktp;
-    a.vt_head_stride = (long long)D * w.ktp; a.vt_d_stride = w.ktp;
+    a.k_img = base + w.k_seg; a.v_img = base + w.v_seg; a.part_len = seg_len;
+    a.img_seq_stride = (long long)n_seg * n_kv_heads * (w.ktp / 64);
+    a.img_part_stride = (long long)n_kv_heads * (w.ktp / 64);
+    a.img_head_stride = w.ktp / 64;
     a.n_keys = k_t; a.n_parts_grid = n_seg; a.part0 = 0; a.causal_offset = PC_NO_CAUSAL;
     rc = pc_launch_flash(a, st);
     if (rc != PC_OK) return rc;
   }
   if (has_self) {
-    void* vt = base + w.vt_self;
-    rc = pc_launch_kv_prepass(nullptr, v_self, nullptr, nullptr, vt, batch, n_q, w.nqp, n_kv_heads,
-                              D, st);
+    rc = pc_launch_kv_prepass(k_self, v_self, nullptr, nullptr, base + w.k_self, base + w.v_self,
+                              batch, n_q, w.nqp, n_kv_heads, D, st);
     if (rc != PC_OK) return rc;
-    a.k = k_self; a.v_t = vt; a.part_len = nullptr;
-    a.k_seq_stride = (long long)n_q * n_kv_heads * D; a.k_part_stride = 0;
-    a.k_head_stride = D; a.k_row_stride = (long long)n_kv_heads * D;
-    a.vt_seq_stride = (long long)n_kv_heads * D * w.nqp; a.vt_part_stride = 0;
-    a.vt_head_stride = (long long)D * w.nqp; a.vt_d_stride = w.nqp;
+    a.k_img = base + w.k_self; a.v_img = base + w.v_self; a.part_len = nullptr;
+    a.img_seq_stride = (long long)n_kv_heads * (w.nqp / 64); a.img_part_stride = 0;
+    a.img_head_stride = w.nqp / 64;
     a.n_keys = n_q; a.n_parts_grid = 1; a.part0 = n_seg; a.causal_offset = 0;
     rc = pc_launch_flash(a, st);
     if (rc != PC_OK) return rc;

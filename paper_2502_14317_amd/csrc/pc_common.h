@@ -92,25 +92,25 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
 
 int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st);
 
-// K/V pre-pass: rotate K (skipped when k == nullptr), transpose V into [n_seq, H_kv, D, Lp].
+// K/V pre-pass: K (rotated when a table is given; skipped when k == nullptr) -> k_rope (row-major,
+// optional) and K tile images (optional); V -> V^T tile images.  Images: [n_seq][n_kv_heads][Lp / 64][64 * D].
 int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void* k_rope,
-                         void* v_t, int n_seq, int L, int Lp, int n_kv_heads, int head_dim,
-                         hipStream_t st);
+                         void* k_img, void* v_img, int n_seq, int L, int Lp, int n_kv_heads,
+                         int head_dim, hipStream_t st);
 
-// Flash-style tile kernel.  A workgroup handles (sequence, query head, 256-row Q tile, part);
+// Flash-style tile kernel.  A workgroup handles (sequence, query head, 128-row Q tile, part);
 // a "part" is an independent key set (a compressed segment) with its own softmax.
 struct PcFlashArgs {
   const void* q;            // [n_seq, n_rows, H_q, D] bf16
-  const void* k;            // rotated keys: k + seq*k_seq_stride + part*k_part_stride + g*k_head_stride + row*k_row_stride
-  const void* v_t;          // transposed values: v_t + seq*.. + part*.. + g*vt_head_stride + d*vt_d_stride + key
+  const void* k_img;        // K tile images (rotated keys), image index = seq * img_seq_stride +
+  const void* v_img;        //   part * img_part_stride + head * img_head_stride + tile; V^T likewise
   const float2* table;      // rope table (rotate q at q_pos0 + row) or nullptr (q already rotated)
   void* o;                  // [n_seq, n_rows, H_q, D] bf16 (final output mode)
   float* lse;               // [n_seq, H_q, n_rows] or nullptr
   float* part_o;            // partial mode: [n_seq, n_parts_total, n_rows, H_q, D] fp32, else nullptr
   float* part_lse;          // [n_seq, n_parts_total, n_rows, H_q]
   const int32_t* part_len;  // [n_seq, n_parts_grid] valid keys per part or nullptr (= n_keys)
-  long long k_seq_stride, k_part_stride, k_head_stride, k_row_stride;      // elements
-  long long vt_seq_stride, vt_part_stride, vt_head_stride, vt_d_stride;    // elements
+  long long img_seq_stride, img_part_stride, img_head_stride;              // in tile images
   int n_seq, n_rows, n_keys, n_q_heads, n_kv_heads, head_dim;
   int n_parts_grid, n_parts_total, part0;
   int causal_offset;        // key j visible to row r iff j <= r + causal_offset; >= 2^29: no mask

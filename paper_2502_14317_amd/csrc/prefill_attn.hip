@@ -56,45 +56,68 @@ int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hip
 }
 
 // ------------------------------------------------------------------------------------------
+// Tile images.  flash_fwd_kernel copies whole 64-key tiles of K and V^T into LDS with contiguous
+// 1 KiB loads, so this pre-pass writes both in the exact byte order the MFMA operand reads want,
+// 16-byte granules (8 bf16) stored granule-column by granule-column:
+//   K image   [16 * D / 128 .. i.e. D/8 columns][64 keys]:   granule (c, r) = K[key r][8c .. 8c+7]
+//   V^T image [8 columns][D rows]:                           granule (c, d) = V[keys 8c .. 8c+7][d]
+// The 16 lanes an LDS read serves together then touch 256 consecutive bytes (no bank conflict,
+// no swizzle), and every operand address is one per-lane base plus an immediate offset.
+// Images of one (sequence, KV head) are consecutive: [n_seq][n_kv_heads][Lp / 64][64 * D].
+// Keys past the end of a sequence are zero in both images.
 // One workgroup per (sequence, KV head, 64-row tile).
 template <int D>
 __global__ __launch_bounds__(256) void kv_prepass_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const float2* __restrict__ table, uint16_t* __restrict__ k_rope, uint16_t* __restrict__ v_t,
-    int L, int Lp, int n_kv_heads) {
+    const float2* __restrict__ table, uint16_t* __restrict__ k_rope, uint16_t* __restrict__ k_img,
+    uint16_t* __restrict__ v_img, int L, int Lp, int n_kv_heads) {
   constexpr int HALF = D / 2;
   constexpr int VSTRIDE = D + 2;                  // bf16 elements, odd number of dwords
   __shared__ uint16_t v_lds[64 * VSTRIDE];
   const int seq = blockIdx.x, g = blockIdx.y, tile = blockIdx.z;
   const int row0 = tile * 64;
   const long long seq_base = (long long)seq * L;
+  const long long img = (((long long)seq * n_kv_heads + g) * (Lp / 64) + tile) * (64 * D);
 
-  // ---- K: rotate pairs (i, i + D/2); a thread handles 8 consecutive i of one row
+  // ---- K: rotate pairs (i, i + D/2) when a table is given; a thread handles 8 consecutive i of one row
   constexpr int K_ITEMS = 64 * (HALF / 8);
   for (int it = threadIdx.x; k != nullptr && it < K_ITEMS; it += 256) {
     const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
     const int row = row0 + r;
+    uint4 oa = make_uint4(0, 0, 0, 0), ob = make_uint4(0, 0, 0, 0);
     if (row < L) {
       const long long off = ((seq_base + row) * n_kv_heads + g) * D;
       const uint4 a = *(const uint4*)(k + off + i0);
       const uint4 b = *(const uint4*)(k + off + HALF + i0);
-      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-      uint32_t ra[4], rb[4];
-      const float2* cs = table + (long long)row * HALF + i0;
+      if (table != nullptr) {
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+        uint32_t ra[4], rb[4];
+        const float2* cs = table + (long long)row * HALF + i0;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
-        const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
-        const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
-        ra[e] = pack_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y);
-        rb[e] = pack_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y);
+        for (int e = 0; e < 4; ++e) {
+          const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+          const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
+          const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
+          ra[e] = pack_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y);
+          rb[e] = pack_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y);
+        }
+        oa = make_uint4(ra[0], ra[1], ra[2], ra[3]);
+        ob = make_uint4(rb[0], rb[1], rb[2], rb[3]);
+      } else {
+        oa = a; ob = b;
       }
-      *(uint4*)(k_rope + off + i0) = make_uint4(ra[0], ra[1], ra[2], ra[3]);
-      *(uint4*)(k_rope + off + HALF + i0) = make_uint4(rb[0], rb[1], rb[2], rb[3]);
+      if (k_rope != nullptr) {
+        *(uint4*)(k_rope + off + i0) = oa;
+        *(uint4*)(k_rope + off + HALF + i0) = ob;
+      }
+    }
+    if (k_img != nullptr) {
+      *(uint4*)(k_img + img + ((i0 / 8) * 64 + r) * 8) = oa;
+      *(uint4*)(k_img + img + (((HALF + i0) / 8) * 64 + r) * 8) = ob;
     }
   }
 
-  // ---- V: 64 x D tile -> LDS -> D x 64 tile of V^T (zero beyond row L)
+  // ---- V: 64 x D tile -> LDS -> V^T image (zero beyond row L)
   constexpr int V_ITEMS = 64 * (D / 8);
   for (int it = threadIdx.x; it < V_ITEMS; it += 256) {
     const int r = it / (D / 8), c8 = (it % (D / 8)) * 8;
@@ -105,45 +128,38 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
     dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
   }
   __syncthreads();
-  constexpr int T_ITEMS = D * 8;                  // (d, group of 8 keys)
+  constexpr int T_ITEMS = 8 * D;                  // (granule column = group of 8 keys, d)
   for (int it = threadIdx.x; it < T_ITEMS; it += 256) {
-    const int d = it / 8, r8 = (it % 8) * 8;
+    const int c = it / D, d = it % D;
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint32_t lo = v_lds[(r8 + 2 * e) * VSTRIDE + d];
-      const uint32_t hi = v_lds[(r8 + 2 * e + 1) * VSTRIDE + d];
+      const uint32_t lo = v_lds[(8 * c + 2 * e) * VSTRIDE + d];
+      const uint32_t hi = v_lds[(8 * c + 2 * e + 1) * VSTRIDE + d];
       w[e] = lo | (hi << 16);
     }
-    const long long off = (((long long)seq * n_kv_heads + g) * D + d) * Lp + row0 + r8;
-    *(uint4*)(v_t + off) = make_uint4(w[0], w[1], w[2], w[3]);
+    *(uint4*)(v_img + img + (c * D + d) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
 int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void* k_rope,
-                         void* v_t, int n_seq, int L, int Lp, int n_kv_heads, int head_dim,
-                         hipStream_t st) {
+                         void* k_img, void* v_img, int n_seq, int L, int Lp, int n_kv_heads,
+                         int head_dim, hipStream_t st) {
   dim3 grid(n_seq, n_kv_heads, Lp / 64), block(256);
   PcProfScope prof(PC_KERNEL_KV_PREPASS, st);
   if (head_dim == 128)
     hipLaunchKernelGGL(kv_prepass_kernel<128>, grid, block, 0, st, (const uint16_t*)k,
-                       (const uint16_t*)v, table, (uint16_t*)k_rope, (uint16_t*)v_t, L, Lp,
-                       n_kv_heads);
+                       (const uint16_t*)v, table, (uint16_t*)k_rope, (uint16_t*)k_img,
+                       (uint16_t*)v_img, L, Lp, n_kv_heads);
   else
     hipLaunchKernelGGL(kv_prepass_kernel<64>, grid, block, 0, st, (const uint16_t*)k,
-                       (const uint16_t*)v, table, (uint16_t*)k_rope, (uint16_t*)v_t, L, Lp,
-                       n_kv_heads);
+                       (const uint16_t*)v, table, (uint16_t*)k_rope, (uint16_t*)k_img,
+                       (uint16_t*)v_img, L, Lp, n_kv_heads);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }
 
 // ------------------------------------------------------------------------------------------
-// LDS tiles are filled by direct global->LDS loads (a wavefront instruction writes 64 x 16 B
-// contiguously), so rows cannot be padded.  Bank conflicts are avoided by an XOR swizzle of the
-// 16-byte granules inside a row instead: granule c of row r is stored in slot c ^ f(r).
-//   K tile   [64 keys][D]:   f(r) = r & 15 (D = 128, 256-byte rows), (r >> 1) & 7 (D = 64)
-//   V^T tile [D][64 keys]:   f(d) = (d >> 1) & 7 (128-byte rows)
-// With these, the 16 lanes served together by a 16-byte LDS read hit 16 distinct bank groups.
 template <int D>
 struct FlashSmem {
   static constexpr int KBUF = 2;                   // K tile t lives in buffer t % 2
@@ -151,11 +167,7 @@ struct FlashSmem {
   static constexpr int K_ELEMS = PC_FA_BN * D;
   static constexpr int V_ELEMS = D * PC_FA_BN;
   static constexpr int BYTES = (KBUF * K_ELEMS + VBUF * V_ELEMS) * 2;
-  static constexpr int STAGE_BYTES = 0;   // the Q staging slots alias tile memory
 };
-template <int D>
-__device__ __forceinline__ int pc_k_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-__device__ __forceinline__ int pc_v_swz(int d) { return (d >> 1) & 7; }
 
 // row index of the first MFMA's A operand -> key within a 32-key block (swap bits 2 and 3)
 __device__ __forceinline__ int pc_key_of_row(int m) {
@@ -205,10 +217,10 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   // steps of 32 keys: steps [0, J0) are visible to every row of the workgroup (no mask)
   const int J0 = (min(row0_wg + a.causal_offset, n_valid - 1) + 1) / 32;
 
-  const uint16_t* kbase = (const uint16_t*)a.k + seq * a.k_seq_stride + part * a.k_part_stride +
-                          g * a.k_head_stride;
-  const uint16_t* vtbase = (const uint16_t*)a.v_t + seq * a.vt_seq_stride +
-                           part * a.vt_part_stride + g * a.vt_head_stride;
+  // tile images of this (sequence, part, KV head): consecutive 64-key tiles of 64 * D elements
+  const long long img0 = (seq * a.img_seq_stride + part * a.img_part_stride + g * a.img_head_stride) * (64LL * D);
+  const uint16_t* kbase = (const uint16_t*)a.k_img + img0;
+  const uint16_t* vbase = (const uint16_t*)a.v_img + img0;
 
   // ---- Q^T as B operand, NB 32-row blocks: lane holds query n of each, d = 16*ks + 8*hf .. +7.
   //      The softmax scale and log2(e) are folded into Q before its rounding to bf16, so the
@@ -252,45 +264,26 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     }
   }
 
-  // ---- cooperative tile loads, straight from global memory into LDS.  Wavefront w issues
-  //      instruction i for the 1 KiB block b = WAVES i + w of the tile; lane l fills granule
-  //      64 b + l of the tile and therefore fetches the source granule the swizzle puts there.
+  // ---- cooperative tile loads, straight from global memory into LDS: a tile image is copied
+  //      as it is, wavefront w issuing instruction i for its 1 KiB block WAVES i + w.  Loads go
+  //      through buffer descriptors (descriptor base + scalar offset + one constant per-lane
+  //      offset, no 64-bit vector arithmetic per load).
   constexpr int WAVES = PC_FA_WAVES;
   constexpr int T_LD = D / 8 / WAVES;              // load instructions per wavefront per tile
+  constexpr int IMG_BYTES = 64 * D * 2;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
-  // Per-lane byte offset of the source granule relative to the block's first row: the same for
-  // every load instruction i (the swizzle of row r + 16 i equals that of r) and every tile, so a
-  // tile load is a scalar base plus one constant vector offset.
-  constexpr int K_ROWS_PER_LD = WAVES * 512 / D;   // tile rows covered by one instruction of all wavefronts
-  constexpr int V_ROWS_PER_LD = WAVES * 512 / PC_FA_BN;
-  uint32_t k_goff, v_goff;
-  {
-    const int gi = 64 * wave_s + lane;
-    const int r = gi / (D / 8), c = (gi % (D / 8)) ^ pc_k_swz<D>(r);
-    k_goff = (uint32_t)(r * a.k_row_stride * 2 + 16 * c);
-    const int d = gi / 8, cv = (gi % 8) ^ pc_v_swz(d);
-    v_goff = (uint32_t)(d * a.vt_d_stride * 2 + 16 * cv);
-  }
-  // Loads go through buffer descriptors: the address is descriptor base + scalar offset +
-  // per-lane offset (no 64-bit vector arithmetic per load), and bytes past the descriptor's
-  // limit read as zero, so the rows of a last, partial K tile beyond the part's keys need no
-  // clamping (their logits are masked later).
-  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)kbase, 0, (int)(((long long)(a.n_keys - 1) * a.k_row_stride + D) * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)vtbase, 0, (int)((long long)D * a.vt_d_stride * 2), 0x00020000);
-  // instruction i (0 .. T_LD-1) of this wavefront for K tile t / V^T tile t
+  const int n_img = (a.n_keys + 63) / 64;
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kbase, 0, n_img * IMG_BYTES, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vbase, 0, n_img * IMG_BYTES, 0x00020000);
+  const int ld_goff = 1024 * wave_s + 16 * lane;
   auto load_k_i = [&](int t, int i) __attribute__((always_inline)) {
-    const int soff = (int)(((long long)t * PC_FA_BN + i * K_ROWS_PER_LD) * a.k_row_stride * 2);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)(k_lds(t) + 512 * (WAVES * i + wave_s)), 16,
-                                             (int)k_goff, soff, 0, 0);
+                                             ld_goff, t * IMG_BYTES + 1024 * WAVES * i, 0, 0);
   };
   auto load_v_i = [&](int t, int i) __attribute__((always_inline)) {
-    const int soff = (int)(((long long)i * V_ROWS_PER_LD * a.vt_d_stride + t * PC_FA_BN) * 2);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(v_lds(t) + 512 * (WAVES * i + wave_s)), 16,
-                                             (int)v_goff, soff, 0, 0);
+                                             ld_goff, t * IMG_BYTES + 1024 * WAVES * i, 0, 0);
   };
   auto load_k = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
@@ -328,11 +321,11 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   floatx16 s_buf[2][NB];                           // [step parity][row block]
   u32x4 p_buf[2][NB][2];                            // [step parity][row block][16-key k-step], bf16 pairs
 
-  // Per-lane element offsets of the MFMA A operands inside a tile.  The swizzle is an XOR on the
-  // granule bits only, so one base per operand kind suffices: offset(c) = base ^ (8 c) with the
-  // lane's own swizzle and half-select folded into the base.
-  int k_base = krow * D + 8 * (hf ^ pc_k_swz<D>(krow));
-  int v_base = n * PC_FA_BN + 8 * (hf ^ pc_v_swz(n));
+  // Per-lane element offsets of the MFMA A operands inside a tile image: K granule
+  // (2 ks + hf, 32 (j & 1) + krow), V^T granule (4 (j & 1) + 2 ts + hf, 32 db + n).  Everything
+  // but the lane's own part is a compile-time offset of the LDS read.
+  int k_base = (hf * 64 + krow) * 8;
+  int v_base = (hf * D + n) * 8;
 
   // MFMA A operands, read from LDS one region ahead of their use
   bf16x8 ka[KS], va[2][DB];                        // K rows of a step; V^T [16-key k-step][d block]
@@ -368,8 +361,8 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
                   const u32x4(&p_prev)[NB][2]) __attribute__((always_inline)) {
     constexpr bool MASK = decltype(mask_tag)::value;
     constexpr bool PV = decltype(has_pv)::value, QK = decltype(has_qk)::value, LD = decltype(has_ld)::value;
-    const uint16_t* kp = k_lds((j + 1) >> 1) + 32 * D * ((j + 1) & 1);   // swizzle of row r + 32 = that of r
-    const uint16_t* vp = v_lds(j >> 1);                                   // swizzle of row d + 32 = that of d
+    const uint16_t* kp = k_lds((j + 1) >> 1) + 32 * 8 * ((j + 1) & 1) + k_base;   // this lane's granule of column hf
+    const uint16_t* vp = v_lds(j >> 1) + 4 * (j & 1) * D * 8 + v_base;
     float t[NB], alpha[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) { t[nb] = 0.f; alpha[nb] = 1.f; }
@@ -405,7 +398,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
         o_acc[nb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
             va[ts][db], *(const bf16x8*)&p_prev[nb][ts], o_acc[nb][db], 0, 0, 0);
       }
-      if (QK && i < KS) ka[i] = *(const bf16x8*)(kp + (k_base ^ (16 * i)));
+      if (QK && i < KS) ka[i] = *(const bf16x8*)(kp + 2 * i * 64 * 8);
       if (LD && i >= NM - 2 * T_LD) {               // one tile-load instruction per slice
         const int li = i - (NM - 2 * T_LD);
         if (li < T_LD) load_k_i(t_ld, li);
@@ -483,7 +476,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
       }
       if (i < KS) {
         const int ts = i / DB, db = i % DB;
-        va[ts][db] = *(const bf16x8*)(vp + 32 * db * PC_FA_BN + (v_base ^ (32 * (j & 1) + 16 * ts)));
+        va[ts][db] = *(const bf16x8*)(vp + 2 * ts * D * 8 + 32 * db * 8);
       }
 #pragma unroll
       for (int g = G1; g < NG; ++g)
@@ -493,9 +486,9 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   };
   // first S^T of a workgroup: operands of step 0, then the product
   auto first_qk = [&](floatx16(&s)[NB]) __attribute__((always_inline)) {
-    const uint16_t* kp = k_lds(0);
+    const uint16_t* kp = k_lds(0) + k_base;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) ka[ks] = *(const bf16x8*)(kp + (k_base ^ (16 * ks)));
+    for (int ks = 0; ks < KS; ++ks) ka[ks] = *(const bf16x8*)(kp + 2 * ks * 64 * 8);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -599,7 +592,7 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   using SM = FlashSmem<D>;
   auto kern = flash_fwd_kernel<D, ROPE_Q, PARTIAL>;
   PC_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 SM::BYTES + SM::STAGE_BYTES));
+                                 SM::BYTES));
   const int G = a.n_q_heads / a.n_kv_heads;
   const int n_qt = (a.n_rows + PC_FA_BM - 1) / PC_FA_BM;
   const long long per_group = (long long)G * n_qt * a.n_parts_grid;
@@ -608,11 +601,9 @@ static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   // tile loads address one (sequence, part, head) region with 32-bit byte offsets
-  if ((long long)a.n_keys * a.k_row_stride * 2 >= 0x7fffffffLL ||
-      (long long)D * a.vt_d_stride * 2 >= 0x7fffffffLL)
-    return PC_ERR_SHAPE;
+  if (((long long)a.n_keys + 63) / 64 * 64 * D * 2 >= 0x7fffffffLL) return PC_ERR_SHAPE;
   PcProfScope prof(PC_KERNEL_FLASH, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES + SM::STAGE_BYTES, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(PC_FA_THREADS), SM::BYTES, st, a);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }
