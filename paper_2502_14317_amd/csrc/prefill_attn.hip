@@ -2,9 +2,8 @@
 //
 // Three kernels:
 //   rope_table_kernel   cos/sin of position * theta_i, computed in fp64, stored fp32
-//   kv_prepass_kernel   K -> rotated K (bf16, the KV cache later steps gather from);
-//                       V -> V^T [seq, H_kv, D, Lp] so that the P.V product finds its
-//                       contraction index (keys) contiguous, as the MFMA operand layout needs
+//   kv_prepass_kernel   K -> rotated K (bf16, the KV cache later steps gather from) and K tile
+//                       images; V -> V^T tile images (the layouts the tile kernel copies to LDS)
 //   flash_fwd_kernel    online-softmax attention on 32x32x16 bf16 MFMA
 //
 // flash_fwd_kernel computes S^T = K Q^T and O^T = V^T P^T.  In the MFMA result layout a lane
@@ -13,13 +12,15 @@
 // rescale factor of O is a per-lane scalar, and P^T in registers is already the B operand
 // of the second product (after rounding to bf16).  K rows are fed to the first MFMA in a
 // permuted order (bits 2 and 3 of the row index swapped) so that the 8 probabilities a lane
-// holds for one k-step belong to 8 consecutive keys, i.e. one 16-byte LDS read of V^T.
+// holds for one k-step belong to 8 consecutive keys, i.e. one 16-byte granule of V^T.
 //
-// Workgroup: 8 wavefronts x 32 query rows = 256 rows of one (sequence, query head); key tiles
-// of 64 staged in LDS (K: [64][D], V^T: [D][64], padded rows, double buffered).  Two
-// wavefronts share a SIMD, so one wavefront's softmax (vector ALU, exp) overlaps the other's
-// MFMA.  Causal structure: a Q tile only visits key tiles up to its diagonal, the mask is
-// applied on diagonal tiles only, and row blocks are paired (i, 7 - i) per SIMD for balance.
+// Workgroup: 4 wavefronts x 32 query rows = 128 rows of one (sequence, query head), one
+// wavefront per SIMD, at most 256 registers and 80 KiB of LDS, so that two workgroups share a
+// CU: the second wavefront of every SIMD belongs to an independent workgroup and fills the
+// issue slots the first one leaves (a single wavefront cannot keep the matrix pipe busy: its
+// own vector-ALU, LDS and barrier time is exposed).  Key tiles of 64 are copied into LDS by
+// direct global->LDS loads (K double-, V^T triple-buffered).  Causal structure: a Q tile only
+// visits key tiles up to its diagonal and the mask is applied on diagonal tiles only.
 // Workgroups are ordered so that one XCD works on one (sequence, KV head) at a time (its K/V
 // stay in that XCD's L2) and takes the long (late) Q tiles first.
 #include "pc_common.h"

@@ -35,9 +35,11 @@ struct PcScoreArgs {
   float scale_log2;
 };
 
-__device__ __forceinline__ void split_bf16(float x, uint32_t& hi, uint32_t& lo) {
-  hi = f32_to_bf16_bits(x);
-  lo = f32_to_bf16_bits(x - __uint_as_float(hi << 16));
+// (x0, x1) -> packed bf16 pair of the values and packed bf16 pair of the rounding remainders
+// (both roundings to nearest-even, in hardware; inputs are finite by contract)
+__device__ __forceinline__ void split_bf16x2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  hi = pack_bf16x2(x0, x1);
+  lo = pack_bf16x2(x0 - bf16_lo_to_f32(hi), x1 - bf16_hi_to_f32(hi));
 }
 
 template <int D, int PASS>
@@ -96,13 +98,8 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
           const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
           const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
           const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
-          uint32_t ha, la, hb, lb;
-          split_bf16(x1l * c0.x - x2l * c0.y, ha, la);
-          split_bf16(x1h * c1.x - x2h * c1.y, hb, lb);
-          h1[e] = ha | (hb << 16); l1[e] = la | (lb << 16);
-          split_bf16(x2l * c0.x + x1l * c0.y, ha, la);
-          split_bf16(x2h * c1.x + x1h * c1.y, hb, lb);
-          h2[e] = ha | (hb << 16); l2[e] = la | (lb << 16);
+          split_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y, h1[e], l1[e]);
+          split_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y, h2[e], l2[e]);
         }
         uint4 t;
         t = make_uint4(h1[0], h1[1], h1[2], h1[3]); qhi[ks] = *(bf16x8*)&t;
@@ -148,13 +145,8 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
           const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
           const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
           const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
-          uint32_t ha, la, hb, lb;
-          split_bf16(x1l * c0.x - x2l * c0.y, ha, la);
-          split_bf16(x1h * c1.x - x2h * c1.y, hb, lb);
-          h1[e] = ha | (hb << 16); l1[e] = la | (lb << 16);
-          split_bf16(x2l * c0.x + x1l * c0.y, ha, la);
-          split_bf16(x2h * c1.x + x1h * c1.y, hb, lb);
-          h2[e] = ha | (hb << 16); l2[e] = la | (lb << 16);
+          split_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y, h1[e], l1[e]);
+          split_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y, h2[e], l2[e]);
         }
         *(uint4*)(k_hi + r * KSTRIDE + i0) = make_uint4(h1[0], h1[1], h1[2], h1[3]);
         *(uint4*)(k_lo + r * KSTRIDE + i0) = make_uint4(l1[0], l1[1], l1[2], l1[3]);
@@ -197,8 +189,8 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
           if (m_new > -INFINITY) {
             float sum = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sum += exp2f(sv[r] - m_new);
-            l_run = l_run * exp2f(m_run - m_new) + sum;
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(sv[r] - m_new);
+            l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + sum;
             m_run = m_new;
           }
         } else {
@@ -206,7 +198,7 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
           float sum = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = exp2f(s[r] * a.scale_log2 - lse_r[r]);
+            const float p = __builtin_amdgcn_exp2f(s[r] * a.scale_log2 - lse_r[r]);
             sum += (key <= qrow_r[r]) ? p : 0.f;
           }
           tok_acc[t][kb] += sum;
@@ -245,17 +237,18 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
   }
 }
 
-// chunk_score[c] = sum of tok_score[c, :, :], summed in a fixed order.
-__global__ __launch_bounds__(256) void chunk_score_kernel(const float* __restrict__ tok_score,
-                                                          float* __restrict__ chunk_score,
-                                                          long long per_chunk) {
-  __shared__ float red[256];
+// chunk_score[c] = sum of tok_score[c, :, :], summed in a fixed order (thread-strided partial
+// sums, then a tree over the workgroup), so the result does not depend on timing.
+__global__ __launch_bounds__(1024) void chunk_score_kernel(const float* __restrict__ tok_score,
+                                                           float* __restrict__ chunk_score,
+                                                           long long per_chunk) {
+  __shared__ float red[1024];
   const float* src = tok_score + (long long)blockIdx.x * per_chunk;
   float x = 0.f;
-  for (long long i = threadIdx.x; i < per_chunk; i += 256) x += src[i];
+  for (long long i = threadIdx.x; i < per_chunk; i += 1024) x += src[i];
   red[threadIdx.x] = x;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
+  for (int s = 512; s > 0; s >>= 1) {
     if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
@@ -294,7 +287,7 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const floa
   PC_LAUNCH_CHECK();
   if (chunk_score) {
     PcProfScope prof(PC_KERNEL_CHUNK_SCORE, st);
-    hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(256), 0, st, tok_score,
+    hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(1024), 0, st, tok_score,
                        chunk_score, (long long)s->n_kv_heads * s->chunk_len);
     PC_LAUNCH_CHECK();
   }
