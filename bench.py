@@ -28,9 +28,9 @@ PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
 # counters read for a plain 1 GiB copy (2048 B per FETCH_SIZE count, 1024 B per WRITE_SIZE count);
 # commands and raw counts: profiles/pmc_hbm_traffic.md.  Keyed by (kernel, workload).
 MEASURED_TRAFFIC = {
-    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.4264e6 * 2048 + 1.0651e6 * 1024,
-    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.0980e6 * 2048 + 1.66e4 * 1024,
-    ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1151e6 * 2048 + 4.1943e6 * 1024,
+    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.6028e6 * 2048 + 1.0667e6 * 1024,
+    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.0981e6 * 2048 + 1.66e4 * 1024,
+    ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1150e6 * 2048 + 4.1943e6 * 1024,
 }
 
 
