@@ -40,6 +40,41 @@ def flash_flops(cfg):
     return 4.0 * cfg.head_dim * (L * (L + 1) / 2.0) * cfg.n_q_heads * cfg.n_chunks
 
 
+def bench_ceilings(pc, torch):
+    """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
+    constant and on random operands (the shader clock depends on the data: the part is
+    power-limited), and a plain device copy."""
+    n_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.empty((n_cus * 512,), dtype=torch.float32, device="cuda")
+    out = {}
+    for name, rnd in (("mfma_constant_operands", 0), ("mfma_random_operands", 1)):
+        best = 0.0
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = pc.pc_mfma_ceiling(rnd, n_cus, 100000, scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best = max(best, flops / (e0.elapsed_time(e1) * 1e-3))
+        out[name] = {"achieved": best / 1e12, "unit": "TFLOP/s", "frac_of_peak": best / PEAK_BF16_FLOPS}
+    a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")    # 1 GiB
+    b = torch.empty_like(a)
+    best = 0.0
+    for rep in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        if rep:
+            best = max(best, 2.0 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3))
+    out["device_copy"] = {"achieved": best / 1e9, "unit": "GB/s", "frac_of_peak": best / PEAK_HBM_BYTES}
+    del a, b, scratch
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(cfg, q, k, v, n_rows_sample=768, n_grows_sample=128):
     """Time the oracle (as it stands) on a bounded sample and scale to the whole step.
 
@@ -265,7 +300,8 @@ def main():
         del qd, kd, vd
         torch.cuda.empty_cache()
         result["secondary"] = bench_secondary(pc, torch, max(args.steps, 5), args.warmup)
-        print(f"[bench] secondary done", file=sys.stderr, flush=True)
+        result["ceilings"] = bench_ceilings(pc, torch)
+        print(f"[bench] secondary done; ceilings {result['ceilings']}", file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v)
     print(json.dumps(result), flush=True)

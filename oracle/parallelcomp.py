@@ -14,6 +14,8 @@ and follows the paper's order of steps:
   query_scores          Eq. 5-6: cumulative query->key attention, summed over voting rows
   select_chunks         Eq. 3-4 mechanics: fixed number of best chunks (see readings below)
   select_tokens         Eq. 7: retained token set per head per chunk
+  select_tokens_calibrated  Eq. 8 then Eq. 7: evict the tokens of one position class whose score
+                        exceeds lambda (R_H), keep the best of the rest
   gather_kv             Eq. 7: compressed KV cache K_r = K_x[.], V_r = V_x[.]
   global_attention_*    Eq. 9-11: the query attends over [K^1 .. K^C, K^q]
 
@@ -32,6 +34,12 @@ Readings of the paper taken here (the paper is silent or ambiguous on each):
     larger is better.  This replaces Eq. 3's self-information, which needs a language-model
     head and trained weights: selection against the paper's own criterion is PARITY UNPINNED.
   * In global attention keys keep their chunk-local rotation and query row t sits at w + t.
+  * Attention calibration (Eq. 8): the text evicts R_H although the equation indexes the
+    retained cache with it (as Eq. 7 does with R_L); R_H = tokens of ONE position class (a
+    contiguous index range [lo, hi): the appendix's first 100 / last 100 / the rest) whose
+    cumulative score is strictly above lambda; lambda is never given (a parameter).  Combined
+    with compression, R_H is evicted first and the top-k of the remaining tokens is kept, so a
+    head keeps min(k, w - |R_H|) tokens.  A NaN score is not above lambda.
 
 Pins (tests/test_oracle_pins.py): brute-force softmax in pure Python loops; closed forms
 (K = 0, V = 1, position 0, norm preservation, shift invariance); a library attention routine
@@ -137,20 +145,46 @@ def select_tokens(tok_score, k_t):
     return out.reshape(tok_score.shape[:-1] + (k_t,))
 
 
+def select_tokens_calibrated(tok_score, k_t, lam, class_lo, class_hi):
+    """Eq. 8 followed by Eq. 7 per row of tok_score [..., w].
+
+    R_H = {j in [class_lo, class_hi) : score_j > lam} is evicted; of the remaining tokens the
+    k_t best are kept (ties to the lower id), ascending.  Returns (idx [..., k_t] int32 padded
+    with -1, cnt [...] int32 = number kept = min(k_t, w - |R_H|)).
+    """
+    tok_score = np.asarray(tok_score, dtype=np.float64)
+    w = tok_score.shape[-1]
+    flat = tok_score.reshape(-1, w)
+    idx = np.full((flat.shape[0], k_t), -1, dtype=np.int32)
+    cnt = np.zeros(flat.shape[0], dtype=np.int32)
+    for i in range(flat.shape[0]):
+        evicted = np.zeros(w, dtype=bool)
+        for j in range(max(class_lo, 0), min(class_hi, w)):
+            if flat[i, j] > lam:
+                evicted[j] = True
+        rest = np.nonzero(~evicted)[0]
+        keep = rest[_top_k_lower_index_wins(flat[i, rest], min(k_t, rest.shape[0]))]
+        cnt[i] = keep.shape[0]
+        idx[i, :cnt[i]] = np.sort(keep)
+    return idx.reshape(tok_score.shape[:-1] + (k_t,)), cnt.reshape(tok_score.shape[:-1])
+
+
 # --------------------------------------------------------------------------- Eq. 7
 def gather_kv(k_src, v_src, chunk_idx, tok_idx):
     """Compressed cache: dst[s, g, t, :] = src[chunk_idx[s], tok_idx[s, g, t], g, :].
 
     k_src, v_src [C, rows, H_kv, D] (any dtype: this is a pure copy);
-    chunk_idx [n_sel]; tok_idx [n_sel, H_kv, k_t].  Returns [n_sel, H_kv, k_t, D] each.
+    chunk_idx [n_sel]; tok_idx [n_sel, H_kv, k_t], a negative id gives a zero row.
+    Returns [n_sel, H_kv, k_t, D] each.
     """
     n_sel, Hkv, kt = tok_idx.shape
-    kd = np.empty((n_sel, Hkv, kt) + k_src.shape[3:], dtype=k_src.dtype)
-    vd = np.empty_like(kd)
+    kd = np.zeros((n_sel, Hkv, kt) + k_src.shape[3:], dtype=k_src.dtype)
+    vd = np.zeros_like(kd)
     for s in range(n_sel):
         for g in range(Hkv):
-            kd[s, g] = k_src[chunk_idx[s], tok_idx[s, g], g]
-            vd[s, g] = v_src[chunk_idx[s], tok_idx[s, g], g]
+            ok = tok_idx[s, g] >= 0
+            kd[s, g, ok] = k_src[chunk_idx[s], tok_idx[s, g, ok], g]
+            vd[s, g, ok] = v_src[chunk_idx[s], tok_idx[s, g, ok], g]
     return kd, vd
 
 
@@ -170,23 +204,22 @@ def global_attention_concat(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
 
     q_rot [n_q, H_q, D] rotated query rows; kc, vc [S, H_kv, k_t, D] compressed segments
     (keys rotated); optional causal self segment k_self, v_self [n_q, H_kv, D]: query row t
-    sees self keys 0..t.  seg_len [S]: valid rows per segment (default all k_t).
-    Returns o [n_q, H_q, D], lse [n_q, H_q].
+    sees self keys 0..t.  seg_len [S] or [S, H_kv]: valid rows per segment (and KV head);
+    default all k_t.  Returns o [n_q, H_q, D], lse [n_q, H_q].
     """
     nq, Hq, D = q_rot.shape
     S, Hkv, kt, _ = kc.shape
     G = Hq // Hkv
     if scale is None:
         scale = 1.0 / np.sqrt(np.float64(D))
-    seg_len = np.full(S, kt, dtype=np.int64) if seg_len is None else np.asarray(seg_len)
+    seg_len = _seg_len_per_head(seg_len, S, Hkv, kt)
     o = np.zeros((nq, Hq, D))
     lse = np.zeros((nq, Hq))
-    n_ctx = int(seg_len.sum())
     for h in range(Hq):
         g = h // G
-        K = [kc[s, g, :seg_len[s]] for s in range(S)]
-        V = [vc[s, g, :seg_len[s]] for s in range(S)]
-        visible = np.ones((nq, n_ctx), dtype=bool)
+        K = [kc[s, g, :seg_len[s, g]] for s in range(S)]
+        V = [vc[s, g, :seg_len[s, g]] for s in range(S)]
+        visible = np.ones((nq, int(seg_len[:, g].sum())), dtype=bool)
         if k_self is not None:
             K.append(k_self[:, g])
             V.append(v_self[:, g])
@@ -197,6 +230,14 @@ def global_attention_concat(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
         P, lse[:, h] = _masked_softmax_rows((q_rot[:, h] @ K.T) * scale, visible)
         o[:, h] = P @ V
     return o, lse
+
+
+def _seg_len_per_head(seg_len, S, Hkv, kt):
+    """seg_len None / [S] / [S, H_kv] -> int64 [S, H_kv]."""
+    if seg_len is None:
+        return np.full((S, Hkv), kt, dtype=np.int64)
+    seg_len = np.asarray(seg_len, dtype=np.int64)
+    return np.repeat(seg_len[:, None], Hkv, axis=1) if seg_len.ndim == 1 else seg_len
 
 
 def lse_merge(o_parts, lse_parts):
@@ -219,7 +260,7 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
     G = Hq // Hkv
     if scale is None:
         scale = 1.0 / np.sqrt(np.float64(D))
-    seg_len = np.full(S, kt, dtype=np.int64) if seg_len is None else np.asarray(seg_len)
+    seg_len = _seg_len_per_head(seg_len, S, Hkv, kt)
     n_parts = S + (1 if k_self is not None else 0)
     o_p = np.zeros((n_parts, nq, Hq, D))
     l_p = np.full((n_parts, nq, Hq), -np.inf)
@@ -227,8 +268,8 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
     for h in range(Hq):
         g = h // G
         for s in range(S):
-            if seg_len[s] > 0:
-                Ks, Vs = kc[s, g, :seg_len[s]], vc[s, g, :seg_len[s]]
+            if seg_len[s, g] > 0:
+                Ks, Vs = kc[s, g, :seg_len[s, g]], vc[s, g, :seg_len[s, g]]
                 P, l_p[s, :, h] = _masked_softmax_rows((q_rot[:, h] @ Ks.T) * scale)
                 o_p[s, :, h] = P @ Vs
         if k_self is not None:
@@ -239,12 +280,14 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
 
 # --------------------------------------------------------------------------- the whole layer
 def parallelcomp_layer(q, k, v, chunk_len, obs_window, keep_chunks, keep_tokens, rope_base,
-                       scale=None, attn_rows=None):
+                       scale=None, attn_rows=None, calibration=None):
     """One layer of the method on C chunk sequences, in the paper's order of steps.
 
     q [C, L, H_q, D], k, v [C, L, H_kv, D] in float64, before RoPE; every chunk's last
     L - chunk_len rows are the query rows.  attn_rows: rows of every chunk for which the local
-    attention output is computed (default all).  Returns a dict with every intermediate result.
+    attention output is computed (default all).  calibration = (lambda, class_lo, class_hi)
+    switches the token selection to Eq. 8 + Eq. 7 (select_tokens_calibrated).  Returns a dict
+    with every intermediate result.
     """
     C, L, Hq, D = q.shape
     Hkv = k.shape[2]
@@ -268,10 +311,15 @@ def parallelcomp_layer(q, k, v, chunk_len, obs_window, keep_chunks, keep_tokens,
     if keep_chunks <= 0:
         return out
     chunk_idx = select_chunks(out["chunk_score"], keep_chunks)
-    tok_idx = select_tokens(out["tok_score"][chunk_idx], keep_tokens)
+    if calibration is None:
+        tok_idx, tok_cnt = select_tokens(out["tok_score"][chunk_idx], keep_tokens), None
+    else:
+        tok_idx, tok_cnt = select_tokens_calibrated(out["tok_score"][chunk_idx], keep_tokens,
+                                                    *calibration)
     kc, vc = gather_kv(out["k_rope"], v, chunk_idx, tok_idx)
     k_self, v_self = out["k_rope"][0, w:], v[0, w:]
-    og, lg = global_attention_merged(q_rot_query, kc, vc, k_self, v_self, scale=scale)
-    out.update({"chunk_idx": chunk_idx, "tok_idx": tok_idx, "kc": kc, "vc": vc,
+    og, lg = global_attention_merged(q_rot_query, kc, vc, k_self, v_self, seg_len=tok_cnt,
+                                     scale=scale)
+    out.update({"chunk_idx": chunk_idx, "tok_idx": tok_idx, "tok_cnt": tok_cnt, "kc": kc, "vc": vc,
                 "global_o": og, "global_lse": lg, "q_rot_query": q_rot_query})
     return out

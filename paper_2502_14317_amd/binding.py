@@ -21,7 +21,7 @@ SYMBOLS = [
     "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
     "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
-    "pc_profile_get", "pc_kernel_name",
+    "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling",
 ]
 
 
@@ -81,6 +81,8 @@ def lib():
     L.pc_profile_get.argtypes = [c_int, POINTER(c_int), POINTER(c_float)]
     L.pc_kernel_name.argtypes = [c_int]
     L.pc_kernel_name.restype = c_char_p
+    L.pc_mfma_ceiling.argtypes = [c_int, c_int, c_int, P, c_size_t, POINTER(ctypes.c_double), P]
+    L.pc_mfma_ceiling.restype = c_int
     _lib = L
     return L
 
@@ -176,6 +178,15 @@ def pc_profile_begin():
 
 def pc_profile_end():
     _check(lib().pc_profile_end(), "pc_profile_end")
+
+
+def pc_mfma_ceiling(random_operands, n_cus, iters, scratch):
+    """Enqueue the MFMA-only ceiling kernel; returns the flops of the launch (time it outside)."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().pc_mfma_ceiling(int(bool(random_operands)), n_cus, iters, _ptr(scratch),
+                                 scratch.numel() * scratch.element_size(), ctypes.byref(flops),
+                                 _stream()), "pc_mfma_ceiling")
+    return flops.value
 
 
 def pc_profile_records():

@@ -1,0 +1,59 @@
+// Measurement aid: what the matrix pipe of this machine sustains, to put the attention kernel's
+// roofline fraction in context.  A loop of nothing but independent 32x32x16 bf16 MFMAs, two
+// wavefronts per SIMD on every CU, on constant or on random operands (the shader clock, and with
+// it the throughput, depends on how many bits toggle: the part is power-limited).
+#include "pc_common.h"
+
+__device__ __forceinline__ uint32_t pc_mix(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+  return x;
+}
+
+template <int RND>
+__global__ __launch_bounds__(512) void mfma_ceiling_kernel(float* out, int iters) {
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    u32x4 x, y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (RND) {   // bf16 pairs with random sign and mantissa, magnitude in [0.5, 2)
+        const uint32_t h1 = pc_mix(threadIdx.x * 131u + j * 17u + e + blockIdx.x * 7919u), h2 = pc_mix(h1 + 12345u);
+        x[e] = (h1 & 0x807f807fu) | 0x3f003f00u | ((h1 >> 3) & 0x00800080u);
+        y[e] = (h2 & 0x807f807fu) | 0x3f003f00u | ((h2 >> 3) & 0x00800080u);
+      } else {
+        x[e] = 0x3f803f80u; y[e] = 0x3f803f80u;   // 1.0
+      }
+    }
+    a[j] = *(bf16x8*)&x; b[j] = *(bf16x8*)&y;
+  }
+  floatx16 acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m)
+      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m & 3], b[(m + (m >> 2)) & 3], acc[m], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[j][r];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+extern "C" int pc_mfma_ceiling(int random_operands, int n_cus, int iters, float* scratch,
+                               size_t scratch_bytes, double* flops, void* stream) {
+  if (!scratch || !flops) return PC_ERR_NULL;
+  if (n_cus < 1 || n_cus > 4096 || iters < 1 || iters > (1 << 22)) return PC_ERR_SHAPE;
+  if (scratch_bytes < (size_t)n_cus * 512 * sizeof(float)) return PC_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  if (random_operands) hipLaunchKernelGGL(mfma_ceiling_kernel<1>, dim3(n_cus), dim3(512), 0, st, scratch, iters);
+  else hipLaunchKernelGGL(mfma_ceiling_kernel<0>, dim3(n_cus), dim3(512), 0, st, scratch, iters);
+  PC_LAUNCH_CHECK();
+  *flops = (double)n_cus * 8.0 /* wavefronts */ * 8.0 * iters * 32768.0;
+  return PC_OK;
+}

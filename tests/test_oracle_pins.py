@@ -374,6 +374,99 @@ def test_planted_relevance_selects_known_chunks_and_tokens():
     assert out["chunk_score"][1] > out["chunk_score"][3] > out["chunk_score"][[0, 2, 4]].max()
 
 
+# ------------------------------------------------------------------ Eq. 8 (attention calibration)
+def test_calibrated_selection_vs_brute_force_and_special_cases():
+    """Eq. 8 + Eq. 7: tokens of one position class with score above lambda are evicted, the
+    best k of the rest are kept.  Brute force in plain loops; lambda = +inf or an empty class
+    reduces to Eq. 7; lambda = -inf evicts the whole class."""
+    r = _rng(31)
+    w, k = 37, 9
+    score = r.standard_normal((3, 2, w))
+    score[0, 0, 5] = score[0, 0, 6] = score[0, 0, 30] = 0.25        # ties inside and outside the class
+    score[1, 1, 3] = np.nan                                          # a NaN is not above lambda
+    lam, lo, hi = 0.1, 2, 21
+    idx, cnt = oracle.select_tokens_calibrated(score, k, lam, lo, hi)
+    for a in range(3):
+        for g in range(2):
+            cand = []
+            for j in range(w):
+                x = score[a, g, j]
+                if lo <= j < hi and x > lam:
+                    continue
+                cand.append((-(x if x == x else -math.inf), j))     # NaN ranks below everything
+            cand.sort()
+            want = sorted(j for _, j in cand[:k])
+            assert cnt[a, g] == len(want) == min(k, len(cand))
+            assert list(idx[a, g, :cnt[a, g]]) == want and all(idx[a, g, cnt[a, g]:] == -1)
+    plain = oracle.select_tokens(score, k)
+    for args in ((math.inf, lo, hi), (lam, 7, 7), (lam, w, w + 5)):
+        idx2, cnt2 = oracle.select_tokens_calibrated(score, k, *args)
+        np.testing.assert_array_equal(idx2, plain)
+        assert (cnt2 == k).all()
+    idx3, cnt3 = oracle.select_tokens_calibrated(score, 30, -math.inf, 10, 20)
+    assert (cnt3 == 27).all() and (idx3[..., 27:] == -1).all()
+    assert not np.isin(idx3[..., :27], np.arange(10, 20)).any()
+    keep = np.r_[0:10, 20:w]
+    np.testing.assert_array_equal(idx3[..., :27], np.broadcast_to(keep, (3, 2, 27)))   # k >= rest: all of it
+
+
+def test_calibration_evicts_the_planted_sink_token():
+    """Config 0 plants an attention sink (key 0 of every chunk has 4x the norm).  With
+    unit-variance entries it collects the largest cumulative score of the first-100 class in most
+    heads; a threshold between the largest and the second largest class score evicts exactly
+    that token (R_s of the appendix), and the rest of the kept set is the plain top-k of the
+    other tokens."""
+    cfg = CFG0U
+    qb, kb, vb = prefill_inputs(cfg)
+    c = 1
+    pos = np.arange(cfg.seq_len)
+    q_rot = oracle.rope(bf16_bits_to_f64(qb[c]), pos, cfg.rope_base)
+    k_rot = oracle.rope(bf16_bits_to_f64(kb[c]), pos, cfg.rope_base)
+    tok, _ = oracle.query_scores(q_rot, k_rot, cfg.chunk_len, cfg.obs_window, cfg.n_kv_heads)
+    n_sink_top = 0
+    for g in range(cfg.n_kv_heads):
+        cls = tok[g, :100]
+        order = np.argsort(-cls)
+        lam = 0.5 * (cls[order[0]] + cls[order[1]])
+        idx, cnt = oracle.select_tokens_calibrated(tok[g], cfg.keep_tokens, lam, 0, 100)
+        assert cnt == cfg.keep_tokens and order[0] not in idx
+        rest = np.delete(np.arange(cfg.chunk_len), order[0])
+        want = np.sort(rest[np.argsort(-tok[g, rest], kind="stable")[:cfg.keep_tokens]])
+        np.testing.assert_array_equal(idx, want)
+        n_sink_top += int(order[0] == 0)
+    assert n_sink_top >= cfg.n_kv_heads // 2
+
+
+def test_global_attention_with_per_head_lengths_ignores_padding():
+    """Per-head segment lengths (what calibration produces): rows past a head's length carry no
+    weight whatever they hold, the printed one-softmax form agrees with the merged form, and a
+    head whose lengths equal those of a plain [S] vector gives the same numbers."""
+    r = _rng(33)
+    nq, Hq, Hkv, D, S, kt = 3, 4, 2, 8, 3, 6
+    q = r.standard_normal((nq, Hq, D)); kc = r.standard_normal((S, Hkv, kt, D)); vc = r.standard_normal((S, Hkv, kt, D))
+    ks = r.standard_normal((nq, Hkv, D)); vs = r.standard_normal((nq, Hkv, D))
+    sl = np.array([[6, 2], [0, 5], [3, 3]])
+    o1, l1 = oracle.global_attention_concat(q, kc, vc, ks, vs, seg_len=sl)
+    o2, l2 = oracle.global_attention_merged(q, kc, vc, ks, vs, seg_len=sl)
+    np.testing.assert_allclose(o1, o2, atol=1e-12); np.testing.assert_allclose(l1, l2, atol=1e-12)
+    kc2, vc2 = kc.copy(), vc.copy()
+    for s_ in range(S):
+        for g in range(Hkv):
+            kc2[s_, g, sl[s_, g]:] = 1e3; vc2[s_, g, sl[s_, g]:] = -7.0
+    o3, l3 = oracle.global_attention_merged(q, kc2, vc2, ks, vs, seg_len=sl)
+    np.testing.assert_array_equal(o2, o3); np.testing.assert_array_equal(l2, l3)
+    o4, l4 = oracle.global_attention_concat(q, kc, vc, ks, vs, seg_len=sl[:, 0])
+    np.testing.assert_allclose(o1[:, :2], o4[:, :2], atol=1e-13)     # heads of KV head 0
+
+
+def test_gather_of_padded_ids_gives_zero_rows():
+    r = _rng(34)
+    src = r.standard_normal((2, 5, 1, 4)); val = r.standard_normal((2, 5, 1, 4))
+    kd, vd = oracle.gather_kv(src, val, np.array([1]), np.array([[[0, 3, -1]]], dtype=np.int32))
+    np.testing.assert_array_equal(kd[0, 0], [src[1, 0, 0], src[1, 3, 0], np.zeros(4)])
+    np.testing.assert_array_equal(vd[0, 0, 2], np.zeros(4))
+
+
 def test_workload_plant_makes_relevant_chunks_win():
     """The unit-variance tiny config: the planted chunk must be the top chunk of the oracle."""
     cfg = CFG0U
