@@ -40,6 +40,35 @@ def flash_flops(cfg):
     return 4.0 * cfg.head_dim * (L * (L + 1) / 2.0) * cfg.n_q_heads * cfg.n_chunks
 
 
+def bench_calibration(pc, torch, cfg, layer, qd, vd, steps):
+    """Attention calibration (Eq. 8 before Eq. 7) on the scores of the timed workload: the
+    first-100-token class with a threshold at the 99.9th percentile of its scores.  Reports the
+    selection kernel with and without the predicate and the eviction + global-attention tail of
+    the layer with per-head lengths."""
+    lam = float(torch.quantile(layer.tok_score[:, :, :100].flatten().float(), 0.999))
+    def timed(fn):
+        fn(); torch.cuda.synchronize()
+        pc.pc_profile_begin()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        pc.pc_profile_end()
+        acc = {}
+        for name, ms in pc.pc_profile_records():
+            acc[name] = acc.get(name, 0.0) + ms / steps
+        return acc
+    plain = timed(lambda: layer.evict_and_attend(qd, vd))
+    layer.calibration = (lam, 0, 100)
+    cal = timed(lambda: layer.evict_and_attend(qd, vd))
+    kept = layer.tok_cnt.float().mean().item()
+    layer.calibration = None
+    return {"class": [0, 100], "lambda": lam, "mean_tokens_kept_per_head": kept,
+            "select_tokens_kernel_ms": {"eq7": round(plain.get("select_tokens_kernel", 0.0), 4),
+                                        "eq8_then_eq7": round(cal.get("select_tokens_kernel", 0.0), 4)},
+            "evict_and_attend_ms": {"eq7": round(sum(plain.values()), 4),
+                                    "eq8_then_eq7": round(sum(cal.values()), 4)}}
+
+
 def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
@@ -292,6 +321,8 @@ def main():
                      "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(("flash_fwd_kernel", cfg.name))},
         "kernel_ms_per_step": breakdown,
     }
+    if not prefill_only:
+        result["calibration"] = bench_calibration(pc, torch, cfg, layer, qd, vd, max(args.steps, 5))
     print(f"[bench] {cfg.name}: {ms_per_step:.3f} ms/step, flash {flash_avg * 1e3:.3f} ms "
           f"({result['roofline']['frac'] * 100:.1f}% of bf16 MFMA peak)", file=sys.stderr, flush=True)
     del layer

@@ -107,6 +107,21 @@ int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int3
                           int32_t n_kv_heads, int32_t chunk_len, int32_t k,
                           int32_t* out_idx, void* stream);
 
+/* ---- Eq. 8 then Eq. 7 (attention calibration + compression) ---------------------------------
+ * As pc_select_tokens_topk, after evicting R_H: the tokens j of ONE position class
+ * class_lo <= j < class_hi (the appendix's first 100 / last 100 / the rest) whose score is
+ * strictly above lambda (a NaN score is not).  Of the remaining tokens the k best are kept, so
+ * head (s, g) keeps out_cnt[s, g] = min(k, chunk_len - |R_H|) tokens:
+ *   out_idx [n_sel, H_kv, k] int32 ascending, entries past out_cnt[s, g] are -1 (pc_gather_kv
+ *   turns them into zero rows; pass out_cnt to pc_parallel_attn as per-head seg_len)
+ *   out_cnt [n_sel, H_kv] int32.
+ * 0 <= class_lo <= class_hi <= chunk_len (an empty class gives Eq. 7), lambda not NaN
+ * (+inf evicts nothing); otherwise as pc_select_tokens_topk.  No workspace. */
+int pc_select_tokens_calibrated(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,
+                                int32_t n_kv_heads, int32_t chunk_len, int32_t k, float lambda,
+                                int32_t class_lo, int32_t class_hi, int32_t* out_idx,
+                                int32_t* out_cnt, void* stream);
+
 /* ---- Eq. 7 (compressed KV cache) -----------------------------------------------------------
  * dst[b, s, g, t, :] = src[b, chunk_idx[b, s], tok_idx[b, s, g, t], g, :]  for K and V.
  *   k_src, v_src [batch, n_chunks, rows_per_chunk, H_kv, D] bf16 (a pure 16-bit copy)
@@ -127,14 +142,15 @@ int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
  *   q [B, n_q, H_q, D] bf16; if q_pos0 >= 0 it is rotated here at positions q_pos0 + t,
  *     if q_pos0 < 0 it is taken as already rotated.
  *   kc, vc [B, S, H_kv, k_t, D] bf16, keys already rotated (chunk-local positions kept)
- *   seg_len [B, S] int32 valid rows per segment, NULL => k_t
+ *   seg_len int32 valid rows per segment, NULL => k_t: [B, S] if seg_len_per_head = 0,
+ *     [B, S, H_kv] (one length per KV head, as Eq. 8 leaves them) if seg_len_per_head = 1
  *   k_self, v_self [B, n_q, H_kv, D] bf16 rotated keys / values of the query rows, both NULL
  *     for no self segment (decode)
  *   out [B, n_q, H_q, D] bf16;  lse_out [B, H_q, n_q] fp32, nullable.
  * n_q * (H_q / H_kv) <= 16 runs the HBM-bound split-KV kernel; larger n_q the MFMA tile kernel.
  * Workspace: pc_parallel_attn_workspace_bytes(...). */
 int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
-                     const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                     int32_t seg_len_per_head, const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
                      int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
                      int32_t head_dim, int32_t q_pos0, float rope_base, float softmax_scale,
                      void* out, float* lse_out, void* ws, size_t ws_bytes, void* stream);

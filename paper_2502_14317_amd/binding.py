@@ -19,7 +19,7 @@ PC_OK = 0
 SYMBOLS = [
     "pc_chunk_prefill_attn", "pc_chunk_prefill_workspace_bytes", "pc_chunk_query_scores",
     "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
-    "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
+    "pc_select_tokens_calibrated", "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling",
 ]
@@ -68,7 +68,9 @@ def lib():
     L.pc_select_tokens_topk.restype = c_int
     L.pc_gather_kv.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P]
     L.pc_gather_kv.restype = c_int
-    L.pc_parallel_attn.argtypes = [P] * 6 + [c_int32] * 8 + [c_float, c_float, P, P, P, c_size_t, P]
+    L.pc_parallel_attn.argtypes = [P] * 4 + [c_int32, P, P] + [c_int32] * 8 + [c_float, c_float, P, P, P, c_size_t, P]
+    L.pc_select_tokens_calibrated.argtypes = [P, P] + [c_int32] * 4 + [c_float, c_int32, c_int32, P, P, P]
+    L.pc_select_tokens_calibrated.restype = c_int
     L.pc_parallel_attn.restype = c_int
     L.pc_parallel_attn_workspace_bytes.argtypes = [c_int32] * 8
     L.pc_parallel_attn_workspace_bytes.restype = c_size_t
@@ -156,6 +158,14 @@ def pc_select_tokens_topk(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k,
            "pc_select_tokens_topk")
 
 
+def pc_select_tokens_calibrated(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, lam,
+                                class_lo, class_hi, out_idx, out_cnt):
+    _check(lib().pc_select_tokens_calibrated(_ptr(tok_score), _ptr(chunk_idx), n_sel, n_kv_heads,
+                                             chunk_len, k, lam, class_lo, class_hi, _ptr(out_idx),
+                                             _ptr(out_cnt), _stream()),
+           "pc_select_tokens_calibrated")
+
+
 def pc_gather_kv(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
                  n_kv_heads, k, head_dim, k_dst, v_dst):
     _check(lib().pc_gather_kv(_ptr(k_src), _ptr(v_src), _ptr(chunk_idx), _ptr(tok_idx), batch,
@@ -164,9 +174,11 @@ def pc_gather_kv(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chu
 
 
 def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t, n_q_heads,
-                     n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out, lse_out, ws):
+                     n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out, lse_out, ws,
+                     seg_len_per_head=0):
     p, n = _ws(ws)
-    _check(lib().pc_parallel_attn(_ptr(q), _ptr(kc), _ptr(vc), _ptr(seg_len), _ptr(k_self),
+    _check(lib().pc_parallel_attn(_ptr(q), _ptr(kc), _ptr(vc), _ptr(seg_len),
+                                  int(seg_len_per_head), _ptr(k_self),
                                   _ptr(v_self), batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
                                   head_dim, q_pos0, rope_base, softmax_scale, _ptr(out),
                                   _ptr(lse_out), p, n, _stream()), "pc_parallel_attn")

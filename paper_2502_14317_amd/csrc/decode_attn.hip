@@ -29,7 +29,8 @@ struct PcDecodeArgs {
   const uint16_t* q;      // rotated queries [B, n_q, H_q, D]
   const uint16_t* kc;     // [B, S, H_kv, k_t, D]
   const uint16_t* vc;
-  const int32_t* seg_len; // [B, S] or nullptr
+  const int32_t* seg_len; // [B, S] ([B, S, H_kv] if seg_len_per_head) or nullptr
+  int seg_len_per_head;
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
   int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
@@ -60,7 +61,8 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
   const int b = bid;
 
-  const int len = a.seg_len ? min(max(a.seg_len[b * a.n_seg + s], 0), a.k_t) : a.k_t;
+  const int len_idx = a.seg_len_per_head ? (b * a.n_seg + s) * a.n_kv_heads + g : b * a.n_seg + s;
+  const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
   const long long seg_base = ((((long long)b * a.n_seg + s) * a.n_kv_heads + g) * a.k_t) * D;
   const uint16_t* kseg = a.kc + seg_base;
   const uint16_t* vseg = a.vc + seg_base;
@@ -358,12 +360,12 @@ int pc_decode_keys_per_wg(int k_t) {
 }
 
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
-                     int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                     int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
                      int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
                      hipStream_t st) {
   PcDecodeArgs a;
   a.q = (const uint16_t*)q_rot; a.kc = (const uint16_t*)kc; a.vc = (const uint16_t*)vc;
-  a.seg_len = seg_len; a.part_o = part_o; a.part_lse = part_lse;
+  a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
   a.keys_per_wg = pc_decode_keys_per_wg(k_t);
   a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;

@@ -206,8 +206,23 @@ extern "C" int pc_select_tokens_topk(const float* tok_score, const int32_t* chun
     return PC_ERR_SHAPE;
   if ((long long)n_sel * n_kv_heads > 0x7fffffffLL) return PC_ERR_SHAPE;
   if (n_sel == 0) return PC_OK;
-  return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, out_idx,
-                                 (hipStream_t)stream);
+  return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, 0.f, 0, 0,
+                                 out_idx, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int pc_select_tokens_calibrated(const float* tok_score, const int32_t* chunk_idx,
+                                           int32_t n_sel, int32_t n_kv_heads, int32_t chunk_len,
+                                           int32_t k, float lambda, int32_t class_lo,
+                                           int32_t class_hi, int32_t* out_idx, int32_t* out_cnt,
+                                           void* stream) {
+  if (!tok_score || !out_idx || !out_cnt) return PC_ERR_NULL;
+  if (n_sel < 0 || n_kv_heads < 1 || chunk_len < 1 || chunk_len > 32768 || k < 1 || k > chunk_len)
+    return PC_ERR_SHAPE;
+  if ((long long)n_sel * n_kv_heads > 0x7fffffffLL) return PC_ERR_SHAPE;
+  if (class_lo < 0 || class_hi < class_lo || class_hi > chunk_len || lambda != lambda) return PC_ERR_SHAPE;
+  if (n_sel == 0) return PC_OK;
+  return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, lambda,
+                                 class_lo, class_hi, out_idx, out_cnt, (hipStream_t)stream);
 }
 
 extern "C" int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
@@ -279,7 +294,7 @@ extern "C" size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, i
 }
 
 extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
-                                const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                                int32_t seg_len_per_head, const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
                                 int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
                                 int32_t head_dim, int32_t q_pos0, float rope_base,
                                 float softmax_scale, void* out, float* lse_out, void* ws,
@@ -288,6 +303,7 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
   if (rc != PC_OK) return rc;
   if (!q || !out) return PC_ERR_NULL;
   if (n_seg > 0 && (!kc || !vc)) return PC_ERR_NULL;
+  if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
   if ((k_self == nullptr) != (v_self == nullptr)) return PC_ERR_NULL;
   const int has_self = k_self != nullptr;
   if (n_seg == 0 && !has_self) return PC_ERR_SHAPE;
@@ -312,7 +328,7 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
 
   if (w.small) {
     if (n_seg > 0) {
-      rc = pc_launch_decode(q_rot, kc, vc, seg_len, batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
+      rc = pc_launch_decode(q_rot, kc, vc, seg_len, seg_len_per_head, batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
                             D, scale, part_o, part_lse, w.n_parts, st);
       if (rc != PC_OK) return rc;
     }
@@ -332,6 +348,7 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
                               batch * n_seg * n_kv_heads, k_t, w.ktp, 1, D, st);
     if (rc != PC_OK) return rc;
     a.k_img = base + w.k_seg; a.v_img = base + w.v_seg; a.part_len = seg_len;
+    a.part_len_per_head = seg_len_per_head;
     a.img_seq_stride = (long long)n_seg * n_kv_heads * (w.ktp / 64);
     a.img_part_stride = (long long)n_kv_heads * (w.ktp / 64);
     a.img_head_stride = w.ktp / 64;
@@ -344,6 +361,7 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
                               batch, n_q, w.nqp, n_kv_heads, D, st);
     if (rc != PC_OK) return rc;
     a.k_img = base + w.k_self; a.v_img = base + w.v_self; a.part_len = nullptr;
+    a.part_len_per_head = 0;
     a.img_seq_stride = (long long)n_kv_heads * (w.nqp / 64); a.img_part_stride = 0;
     a.img_head_stride = w.nqp / 64;
     a.n_keys = n_q; a.n_parts_grid = 1; a.part0 = n_seg; a.causal_offset = 0;

@@ -86,9 +86,10 @@ int pc_launch_gather(const void* k_src, const void* v_src, const int32_t* chunk_
                      hipStream_t st);
 int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, float* out_score,
                             hipStream_t st);
+// cls_lo >= cls_hi: plain top-k (Eq. 7); else Eq. 8 first.  out_cnt may be nullptr.
 int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
-                            int n_kv_heads, int chunk_len, int k, int32_t* out_idx,
-                            hipStream_t st);
+                            int n_kv_heads, int chunk_len, int k, float lambda, int cls_lo,
+                            int cls_hi, int32_t* out_idx, int32_t* out_cnt, hipStream_t st);
 
 int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st);
 
@@ -109,7 +110,8 @@ struct PcFlashArgs {
   float* lse;               // [n_seq, H_q, n_rows] or nullptr
   float* part_o;            // partial mode: [n_seq, n_parts_total, n_rows, H_q, D] fp32, else nullptr
   float* part_lse;          // [n_seq, n_parts_total, n_rows, H_q]
-  const int32_t* part_len;  // [n_seq, n_parts_grid] valid keys per part or nullptr (= n_keys)
+  const int32_t* part_len;  // [n_seq, n_parts_grid] (x [n_kv_heads] if part_len_per_head) valid keys per part, or nullptr (= n_keys)
+  int part_len_per_head;
   long long img_seq_stride, img_part_stride, img_head_stride;              // in tile images
   int n_seq, n_rows, n_keys, n_q_heads, n_kv_heads, head_dim;
   int n_parts_grid, n_parts_total, part0;
@@ -128,7 +130,7 @@ int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int 
                      int pos0, float base, hipStream_t st);
 int pc_decode_keys_per_wg(int k_t);
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
-                     int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                     int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
                      int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
                      hipStream_t st);
 int pc_launch_merge(const float* part_o, const float* part_lse, const void* q_rot,

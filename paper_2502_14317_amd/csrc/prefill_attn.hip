@@ -210,8 +210,9 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   int my_row[NB], max_key[NB];
 
   // ---- keys of this workgroup: [0, key_end) of the part
-  const int n_valid = a.part_len ? min(max(a.part_len[seq * a.n_parts_grid + part], 0), a.n_keys)
-                                 : a.n_keys;
+  const int len_idx = a.part_len_per_head ? (seq * a.n_parts_grid + part) * a.n_kv_heads + g
+                                          : seq * a.n_parts_grid + part;
+  const int n_valid = a.part_len ? min(max(a.part_len[len_idx], 0), a.n_keys) : a.n_keys;
   int key_end = n_valid;
   if (a.causal_offset < PC_NO_CAUSAL) key_end = min(key_end, row0_wg + PC_FA_BM + a.causal_offset);
   const int T = (key_end + PC_FA_BN - 1) / PC_FA_BN;          // 64-key tiles

@@ -44,15 +44,20 @@ int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, 
 //     above T and equal to T, the counts are prefix-summed over wavefronts, and a second sweep
 //     emits index i iff key_i > T, or key_i == T and fewer than need_eq equal keys precede it.
 //     Output is ascending by construction and ties go to the lower index.
+// Attention calibration (Eq. 8) is a predicate on the keys: a token of the position class
+// [cls_lo, cls_hi) whose score is above lambda gets key 0, below every candidate (a NaN score
+// is a candidate with key 1), and k shrinks to the number of candidates when fewer are left;
+// the unused tail of the output is filled with -1 and the kept count is reported.
 #define PC_SEL_THREADS 512
 #define PC_SEL_WAVES (PC_SEL_THREADS / PC_WAVE)
 
 __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
     const float* __restrict__ tok_score, const int32_t* __restrict__ chunk_idx, int n_kv_heads,
-    int n, int k, int32_t* __restrict__ out_idx) {
+    int n, int k, float lambda, int cls_lo, int cls_hi, int32_t* __restrict__ out_idx,
+    int32_t* __restrict__ out_cnt) {
   extern __shared__ uint32_t keys[];   // n
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t sh_bin, sh_need;
+  __shared__ uint32_t sh_bin, sh_need, sh_evicted;
   __shared__ uint32_t wave_gt[PC_SEL_WAVES], wave_eq[PC_SEL_WAVES];
 
   const int s = blockIdx.x / n_kv_heads;
@@ -61,9 +66,24 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
   const float* src = tok_score + ((long long)c * n_kv_heads + g) * n;
   int32_t* dst = out_idx + (long long)blockIdx.x * k;
 
-  for (int i = threadIdx.x; i < n; i += PC_SEL_THREADS) keys[i] = pc_order_key(src[i]);
+  if (threadIdx.x == 0) sh_evicted = 0;
+  __syncthreads();
+  uint32_t my_evicted = 0;
+  for (int i = threadIdx.x; i < n; i += PC_SEL_THREADS) {
+    const float x = src[i];
+    uint32_t key = pc_order_key(x);
+    key = key == 0u ? 1u : key;
+    if (i >= cls_lo && i < cls_hi && x > lambda) { key = 0u; ++my_evicted; }
+    keys[i] = key;
+  }
+  if (my_evicted) atomicAdd(&sh_evicted, my_evicted);
+  __syncthreads();
+  const int k_eff = min(k, n - (int)sh_evicted);
+  for (int i = k_eff + threadIdx.x; i < k; i += PC_SEL_THREADS) dst[i] = -1;
+  if (threadIdx.x == 0 && out_cnt) out_cnt[blockIdx.x] = k_eff;
+  if (k_eff == 0) return;                          // uniform over the workgroup
 
-  uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+  uint32_t prefix = 0, mask = 0, need = (uint32_t)k_eff;
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (threadIdx.x < 256) hist[threadIdx.x] = 0;
     __syncthreads();
@@ -127,8 +147,8 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
 }
 
 int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
-                            int n_kv_heads, int chunk_len, int k, int32_t* out_idx,
-                            hipStream_t st) {
+                            int n_kv_heads, int chunk_len, int k, float lambda, int cls_lo,
+                            int cls_hi, int32_t* out_idx, int32_t* out_cnt, hipStream_t st) {
   const size_t lds = (size_t)chunk_len * sizeof(uint32_t);
   if (lds > 48 * 1024) {
     PC_HIP_TRY(hipFuncSetAttribute((const void*)select_tokens_kernel,
@@ -136,7 +156,8 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
   }
   PcProfScope prof(PC_KERNEL_SELECT_TOKENS, st);
   hipLaunchKernelGGL(select_tokens_kernel, dim3(n_sel * n_kv_heads), dim3(PC_SEL_THREADS), lds, st,
-                     tok_score, chunk_idx, n_kv_heads, chunk_len, k, out_idx);
+                     tok_score, chunk_idx, n_kv_heads, chunk_len, k, lambda, cls_lo, cls_hi,
+                     out_idx, out_cnt);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }

@@ -10,12 +10,13 @@ from . import binding as B
 class ParallelCompLayer:
     def __init__(self, n_chunks, chunk_len, query_len, n_q_heads, n_kv_heads, head_dim,
                  obs_window, rope_base, keep_chunks, keep_tokens, softmax_scale=0.0,
-                 device="cuda"):
+                 device="cuda", calibration=None):
         self.C, self.w, self.wq = n_chunks, chunk_len, query_len
         self.L = chunk_len + query_len
         self.Hq, self.Hkv, self.D = n_q_heads, n_kv_heads, head_dim
         self.kc_n, self.kt_n = keep_chunks, keep_tokens
         self.rope_base, self.scale = rope_base, softmax_scale
+        self.calibration = calibration          # None or (lambda, class_lo, class_hi) of Eq. 8
         self.shape = B.make_shape(n_chunks, chunk_len, query_len, n_q_heads, n_kv_heads, head_dim,
                                   obs_window, rope_base, softmax_scale)
         dev, bf, f32, i32 = device, torch.bfloat16, torch.float32, torch.int32
@@ -30,6 +31,7 @@ class ParallelCompLayer:
             self.chunk_idx = torch.empty((keep_chunks,), dtype=i32, device=dev)
             self.chunk_top = torch.empty((keep_chunks,), dtype=f32, device=dev)
             self.tok_idx = torch.empty((keep_chunks, Hkv, keep_tokens), dtype=i32, device=dev)
+            self.tok_cnt = torch.empty((keep_chunks, Hkv), dtype=i32, device=dev)
             self.kc = torch.empty((1, keep_chunks, Hkv, keep_tokens, D), dtype=bf, device=dev)
             self.vc = torch.empty_like(self.kc)
             self.global_o = torch.empty((1, query_len, Hq, D), dtype=bf, device=dev)
@@ -45,16 +47,25 @@ class ParallelCompLayer:
                                 self.chunk_score if with_scores else None, self.ws)
 
     def evict_and_attend(self, q, v):
-        """Eq. 3-4 mechanics, Eq. 7 and Eq. 9-11 on the results of chunk_prefill."""
+        """Eq. 3-4 mechanics, Eq. 7 (after Eq. 8 when calibration is set) and Eq. 9-11 on the
+        results of chunk_prefill."""
         C, L, w = self.C, self.L, self.w
         B.pc_select_chunks_topk(self.chunk_score, C, self.kc_n, self.chunk_idx, self.chunk_top)
-        B.pc_select_tokens_topk(self.tok_score, self.chunk_idx, self.kc_n, self.Hkv, w, self.kt_n,
-                                self.tok_idx)
+        if self.calibration is None:
+            B.pc_select_tokens_topk(self.tok_score, self.chunk_idx, self.kc_n, self.Hkv, w,
+                                    self.kt_n, self.tok_idx)
+            seg_len, per_head = None, 0
+        else:
+            lam, lo, hi = self.calibration
+            B.pc_select_tokens_calibrated(self.tok_score, self.chunk_idx, self.kc_n, self.Hkv, w,
+                                          self.kt_n, lam, lo, hi, self.tok_idx, self.tok_cnt)
+            seg_len, per_head = self.tok_cnt, 1
         B.pc_gather_kv(self.k_rope, v, self.chunk_idx, self.tok_idx, 1, C, L, self.kc_n, self.Hkv,
                        self.kt_n, self.D, self.kc, self.vc)
-        B.pc_parallel_attn(q[0, w:], self.kc, self.vc, None, self.k_rope[0, w:], v[0, w:], 1,
+        B.pc_parallel_attn(q[0, w:], self.kc, self.vc, seg_len, self.k_rope[0, w:], v[0, w:], 1,
                            self.wq, self.kc_n, self.kt_n, self.Hq, self.Hkv, self.D, w,
-                           self.rope_base, self.scale, self.global_o, self.global_lse, self.ws)
+                           self.rope_base, self.scale, self.global_o, self.global_lse, self.ws,
+                           seg_len_per_head=per_head)
 
     def forward(self, q, k, v):
         self.chunk_prefill(q, k, v, with_scores=True)

@@ -47,6 +47,12 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_select_tokens_topk(None, None, 1, 1, 8, 2, one, None) == -1
     assert L.pc_select_tokens_topk(one, None, 1, 1, 8, 9, one, None) == -2
     assert L.pc_select_tokens_topk(one, None, 1, 1, 40000, 2, one, None) == -2
+    # calibrated token selection (Eq. 8): class bounds and lambda are checked on the host
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 4, one, None, None) == -1
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 5, 4, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 9, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, float('nan'), 0, 4, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 0, 1, 8, 2, 0.5, 0, 4, one, one, None) == 0
     # gather
     assert L.pc_gather_kv(one, one, None, None, 1, 1, 8, 1, 1, 2, 128, one, one, None) == -1
     assert L.pc_gather_kv(one, one, None, one, 1, 1, 8, 1, 1, 2, 96, one, one, None) == -2
@@ -67,11 +73,12 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, one, one, 1 << 30, None) == -1
     # parallel attention
     args = (1, 1, 2, 64, 8, 2, 128, -1, 1e4, 0.0)
-    assert L.pc_parallel_attn(None, one, one, None, None, None, *args, one, None, one, 1 << 30, None) == -1
-    assert L.pc_parallel_attn(one, one, one, None, one, None, *args, one, None, one, 1 << 30, None) == -1
-    assert L.pc_parallel_attn(one, one, one, None, None, None, *args, one, None, one, 8, None) == -3
+    assert L.pc_parallel_attn(None, one, one, None, 0, None, None, *args, one, None, one, 1 << 30, None) == -1
+    assert L.pc_parallel_attn(one, one, one, None, 0, one, None, *args, one, None, one, 1 << 30, None) == -1
+    assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *args, one, None, one, 8, None) == -3
+    assert L.pc_parallel_attn(one, one, one, one, 2, None, None, *args, one, None, one, 1 << 30, None) == -2
     bad_args = (1, 1, 2, 64, 8, 3, 128, -1, 1e4, 0.0)
-    assert L.pc_parallel_attn(one, one, one, None, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
+    assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
 
 
 def test_workspace_sizes_are_positive_and_monotone():
