@@ -145,20 +145,23 @@ def select_tokens(tok_score, k_t):
     return out.reshape(tok_score.shape[:-1] + (k_t,))
 
 
-def select_tokens_calibrated(tok_score, k_t, lam, class_lo, class_hi):
+def select_tokens_calibrated(tok_score, k_t, lam, class_lo, class_hi, valid_len=None):
     """Eq. 8 followed by Eq. 7 per row of tok_score [..., w].
 
     R_H = {j in [class_lo, class_hi) : score_j > lam} is evicted; of the remaining tokens the
-    k_t best are kept (ties to the lower id), ascending.  Returns (idx [..., k_t] int32 padded
-    with -1, cnt [...] int32 = number kept = min(k_t, w - |R_H|)).
+    k_t best are kept (ties to the lower id), ascending.  valid_len [...] (optional): only
+    tokens j < valid_len exist (a chunk shorter than w).  Returns (idx [..., k_t] int32 padded
+    with -1, cnt [...] int32 = number kept = min(k_t, valid_len - |R_H|)).
     """
     tok_score = np.asarray(tok_score, dtype=np.float64)
     w = tok_score.shape[-1]
     flat = tok_score.reshape(-1, w)
+    vlen = np.full(flat.shape[0], w) if valid_len is None else np.asarray(valid_len).reshape(-1)
     idx = np.full((flat.shape[0], k_t), -1, dtype=np.int32)
     cnt = np.zeros(flat.shape[0], dtype=np.int32)
     for i in range(flat.shape[0]):
         evicted = np.zeros(w, dtype=bool)
+        evicted[vlen[i]:] = True
         for j in range(max(class_lo, 0), min(class_hi, w)):
             if flat[i, j] > lam:
                 evicted[j] = True
@@ -280,7 +283,7 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
 
 # --------------------------------------------------------------------------- the whole layer
 def parallelcomp_layer(q, k, v, chunk_len, obs_window, keep_chunks, keep_tokens, rope_base,
-                       scale=None, attn_rows=None, calibration=None):
+                       scale=None, attn_rows=None, calibration=None, chunk_lens=None):
     """One layer of the method on C chunk sequences, in the paper's order of steps.
 
     q [C, L, H_q, D], k, v [C, L, H_kv, D] in float64, before RoPE; every chunk's last
@@ -288,36 +291,47 @@ def parallelcomp_layer(q, k, v, chunk_len, obs_window, keep_chunks, keep_tokens,
     attention output is computed (default all).  calibration = (lambda, class_lo, class_hi)
     switches the token selection to Eq. 8 + Eq. 7 (select_tokens_calibrated).  Returns a dict
     with every intermediate result.
+    chunk_lens [C] (optional): chunk c has only chunk_lens[c] <= chunk_len context rows ("at
+    most w tokens" per chunk, sec. 3.1) and its sequence is rows [0, chunk_lens[c] + w_q) of
+    q[c], k[c], v[c]: the query rows follow the context directly, at positions chunk_lens[c] + t.
+    Rows behind a short sequence are padding: outputs and rotated keys there stay zero, the
+    token scores of the missing tokens are zero and they are never selected (a head of a short
+    chunk may keep fewer than keep_tokens tokens; per-head counts are returned as tok_cnt).
     """
     C, L, Hq, D = q.shape
     Hkv = k.shape[2]
     w = chunk_len
     wq = L - w
-    pos = np.arange(L)
+    lens = np.full(C, w, dtype=np.int64) if chunk_lens is None else np.asarray(chunk_lens, dtype=np.int64)
     rows = np.arange(L) if attn_rows is None else np.asarray(attn_rows)
     out = {"o": np.zeros((C, rows.shape[0], Hq, D)), "lse": np.zeros((C, rows.shape[0], Hq)),
            "k_rope": np.zeros_like(k), "tok_score": np.zeros((C, Hkv, w)),
            "chunk_score": np.zeros(C), "attn_rows": rows}
     q_rot_query = None
     for c in range(C):
-        q_rot = rope(q[c], pos, rope_base)
-        k_rot = rope(k[c], pos, rope_base)
-        out["k_rope"][c] = k_rot
-        out["o"][c], out["lse"][c] = local_attention(q_rot, k_rot, v[c], scale, rows)
-        out["tok_score"][c], out["chunk_score"][c] = query_scores(q_rot, k_rot, w, obs_window,
-                                                                  Hkv, scale)
+        Lc = int(lens[c]) + wq
+        pos = np.arange(Lc)
+        q_rot = rope(q[c, :Lc], pos, rope_base)
+        k_rot = rope(k[c, :Lc], pos, rope_base)
+        out["k_rope"][c, :Lc] = k_rot
+        sel = np.nonzero(rows < Lc)[0]
+        out["o"][c, sel], out["lse"][c, sel] = local_attention(q_rot, k_rot, v[c, :Lc], scale, rows[sel])
+        tok, out["chunk_score"][c] = query_scores(q_rot, k_rot, int(lens[c]), obs_window, Hkv, scale)
+        out["tok_score"][c, :, :lens[c]] = tok
         if c == 0:
-            q_rot_query = q_rot[w:]
+            q_rot_query = q_rot[lens[0]:]
     if keep_chunks <= 0:
         return out
     chunk_idx = select_chunks(out["chunk_score"], keep_chunks)
-    if calibration is None:
+    if calibration is None and chunk_lens is None:
         tok_idx, tok_cnt = select_tokens(out["tok_score"][chunk_idx], keep_tokens), None
     else:
+        lam, lo, hi = (np.inf, 0, 0) if calibration is None else calibration
+        vlen = np.repeat(lens[chunk_idx][:, None], Hkv, axis=1)
         tok_idx, tok_cnt = select_tokens_calibrated(out["tok_score"][chunk_idx], keep_tokens,
-                                                    *calibration)
+                                                    lam, lo, hi, valid_len=vlen)
     kc, vc = gather_kv(out["k_rope"], v, chunk_idx, tok_idx)
-    k_self, v_self = out["k_rope"][0, w:], v[0, w:]
+    k_self, v_self = out["k_rope"][0, lens[0]:lens[0] + wq], v[0, lens[0]:lens[0] + wq]
     og, lg = global_attention_merged(q_rot_query, kc, vc, k_self, v_self, seg_len=tok_cnt,
                                      scale=scale)
     out.update({"chunk_idx": chunk_idx, "tok_idx": tok_idx, "tok_cnt": tok_cnt, "kc": kc, "vc": vc,

@@ -467,6 +467,56 @@ def test_gather_of_padded_ids_gives_zero_rows():
     np.testing.assert_array_equal(vd[0, 0, 2], np.zeros(4))
 
 
+# ------------------------------------------------------------------ ragged chunks, streaming queue (sec. 3.1)
+def test_ragged_chunks_reduce_to_uniform_chunks_of_their_own_length():
+    """A chunk with fewer context rows is the same computation as a uniform layer whose chunk
+    length is that chunk's length; rows behind the short sequence are padding that nothing reads."""
+    r = _rng(41)
+    C, w, wq, Hq, Hkv, D, base = 3, 20, 4, 4, 2, 8, 1e4
+    lens = np.array([20, 13, 7])
+    L = w + wq
+    q = r.standard_normal((C, L, Hq, D)); k = r.standard_normal((C, L, Hkv, D)); v = r.standard_normal((C, L, Hkv, D))
+    out = oracle.parallelcomp_layer(q, k, v, w, 3, 2, 5, base, chunk_lens=lens)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    for c in range(C):
+        q2[c, lens[c] + wq:] = 1e9; k2[c, lens[c] + wq:] = -1e9; v2[c, lens[c] + wq:] = 1e9
+    out2 = oracle.parallelcomp_layer(q2, k2, v2, w, 3, 2, 5, base, chunk_lens=lens)
+    for key in ("o", "lse", "tok_score", "chunk_score", "global_o", "tok_idx", "tok_cnt"):
+        np.testing.assert_array_equal(out[key], out2[key])
+    for c in range(C):
+        Lc = lens[c] + wq
+        one = oracle.parallelcomp_layer(q[c:c + 1, :Lc], k[c:c + 1, :Lc], v[c:c + 1, :Lc], int(lens[c]), 3, 0, 0, base)
+        np.testing.assert_array_equal(out["o"][c, :Lc], one["o"][0])
+        np.testing.assert_array_equal(out["tok_score"][c, :, :lens[c]], one["tok_score"][0])
+        assert not out["tok_score"][c, :, lens[c]:].any() and not out["o"][c, Lc:].any()
+        assert out["chunk_score"][c] == one["chunk_score"][0]
+    # the shortest kept chunk has 7 tokens < 5? no: 7 >= 5, so every head keeps 5; with k = 9 it cannot
+    out9 = oracle.parallelcomp_layer(q, k, v, w, 3, 3, 9, base, chunk_lens=lens)
+    for s_, c in enumerate(out9["chunk_idx"]):
+        assert (out9["tok_cnt"][s_] == min(9, lens[c])).all()
+        assert (out9["tok_idx"][s_][:, :min(9, lens[c])] < lens[c]).all()
+
+
+def test_streaming_priority_queue_equals_offline_top_k():
+    """Chunks arrive in batches; a queue of fixed size keeps the best seen so far (score
+    descending, earlier chunk first on ties).  Whatever the batch size, the final queue is the
+    offline top-k of all chunk scores: the reason the method may free an evicted chunk's KV."""
+    r = _rng(42)
+    for trial in range(20):
+        n, k = int(r.integers(5, 40)), int(r.integers(1, 6))
+        score = np.round(r.standard_normal(n), 1)                 # many exact ties
+        want = list(oracle.select_chunks(score, min(k, n)))
+        for batch in (1, 2, 3, 7, n):
+            queue = []                                            # (score, global chunk id)
+            for c0 in range(0, n, batch):
+                queue += [(score[c], c) for c in range(c0, min(c0 + batch, n))]
+                queue.sort(key=lambda t: (-t[0], t[1]))
+                queue = queue[:k]
+                seen = min(c0 + batch, n)
+                assert [c for _, c in queue] == list(oracle.select_chunks(score[:seen], min(k, seen)))
+            assert [c for _, c in queue] == want
+
+
 def test_workload_plant_makes_relevant_chunks_win():
     """The unit-variance tiny config: the planted chunk must be the top chunk of the oracle."""
     cfg = CFG0U
