@@ -69,6 +69,33 @@ def bench_calibration(pc, torch, cfg, layer, qd, vd, steps):
                                     "eq8_then_eq7": round(sum(cal.values()), 4)}}
 
 
+def bench_streaming(torch, cfg, qd, kd, vd, steps):
+    """The layer with chunks arriving in batches and a resident priority queue of the kept
+    chunks' compacted KV (the memory-bounded mode of sec. 3.1): time per layer and resident bytes."""
+    from paper_2502_14317_amd.layer import StreamingParallelComp
+    out = {}
+    for bc in (4, 8):
+        if bc >= cfg.n_chunks:
+            continue
+        st = StreamingParallelComp(cfg.n_chunks, bc, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
+                                   cfg.n_kv_heads, cfg.head_dim, cfg.obs_window, cfg.rope_base,
+                                   cfg.keep_chunks, cfg.keep_tokens)
+        st.forward(qd, kd, vd)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.forward(qd, kd, vd)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        resident = sum(t.numel() * t.element_size() for t in (st.o, st.lse, st.k_rope, st.tok_score, st.kc, st.vc, st.ws))
+        out[f"batch_{bc}_chunks"] = {"ms_per_layer": round(ms, 3),
+                                     "tokens_per_s_per_layer": cfg.n_chunks * cfg.chunk_len / (ms * 1e-3),
+                                     "library_buffers_bytes": resident}
+        del st
+        torch.cuda.empty_cache()
+    return out
+
+
 def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
@@ -323,6 +350,7 @@ def main():
     }
     if not prefill_only:
         result["calibration"] = bench_calibration(pc, torch, cfg, layer, qd, vd, max(args.steps, 5))
+        result["streaming"] = bench_streaming(torch, cfg, qd, kd, vd, max(args.steps // 2, 3))
     print(f"[bench] {cfg.name}: {ms_per_step:.3f} ms/step, flash {flash_avg * 1e3:.3f} ms "
           f"({result['roofline']['frac'] * 100:.1f}% of bf16 MFMA peak)", file=sys.stderr, flush=True)
     del layer

@@ -67,15 +67,22 @@ typedef struct pc_shape {
  *          steps gather from); when NULL the rotated keys live only in the workspace.
  *   tok_score [C, H_kv, w] fp32 out, nullable; chunk_score [C] fp32 out, nullable (needs
  *          tok_score): exactly what pc_chunk_query_scores writes, from the same launch queue.
+ *   chunk_lens [C] int32 (device), nullable: ragged chunks ("at most w tokens" per chunk,
+ *          sec. 3.1).  Chunk c then holds chunk_lens[c] <= w context rows (clamped to [0, w]) and
+ *          its sequence is rows [0, chunk_lens[c] + w_q) of q[c], k[c], v[c]: the query rows
+ *          follow the context directly, at positions chunk_lens[c] + t.  Rows behind a short
+ *          sequence are padding: o and lse there are not written, tok_score of the missing
+ *          tokens is 0, k_rope there is unspecified.  NULL => every chunk has w rows.
  * Arithmetic: bf16 MFMA products of the bf16-rounded rotated q and k, fp32 softmax and
  * accumulation.  Workspace: pc_chunk_prefill_workspace_bytes(shape). */
 int pc_chunk_prefill_attn(const pc_shape* shape, const void* q, const void* k, const void* v,
-                          void* o, float* lse, void* k_rope, float* tok_score,
+                          const int32_t* chunk_lens, void* o, float* lse, void* k_rope, float* tok_score,
                           float* chunk_score, void* ws, size_t ws_bytes, void* stream);
 size_t pc_chunk_prefill_workspace_bytes(const pc_shape* shape);
 
 /* ---- Eq. 5-6 -------------------------------------------------------------------------------
- * Cumulative attention of the voting rows R = {L - w_obs, ..., L - 1} to every chunk key:
+ * Cumulative attention of the voting rows R = {L - w_obs, ..., L - 1} to every chunk key
+ * (with chunk_lens, as in pc_chunk_prefill_attn: L = chunk_lens[c] + w_q and j < chunk_lens[c]):
  *   tok_score[c, g, j] = sum_{h in group g} sum_{r in R} P[c, h, r, j],  j < w
  *   chunk_score[c]     = sum_g sum_j tok_score[c, g, j]                    (nullable)
  * where P[c, h, r, :] is row r of Eq. 1 (softmax over all causal keys j <= r of the sequence,
@@ -84,7 +91,7 @@ size_t pc_chunk_prefill_workspace_bytes(const pc_shape* shape);
  * with fp32 accumulation, i.e. to about fp32 accuracy, so that selections are stable.
  * Workspace: pc_chunk_query_scores_workspace_bytes(shape). */
 int pc_chunk_query_scores(const pc_shape* shape, const void* q, const void* k,
-                          float* tok_score, float* chunk_score,
+                          const int32_t* chunk_lens, float* tok_score, float* chunk_score,
                           void* ws, size_t ws_bytes, void* stream);
 size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* shape);
 
@@ -115,12 +122,14 @@ int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int3
  *   out_idx [n_sel, H_kv, k] int32 ascending, entries past out_cnt[s, g] are -1 (pc_gather_kv
  *   turns them into zero rows; pass out_cnt to pc_parallel_attn as per-head seg_len)
  *   out_cnt [n_sel, H_kv] int32.
+ * chunk_lens [n_chunks_total] int32 (device, nullable): chunk c holds only chunk_lens[c] tokens
+ * (ragged chunks); the missing ones are never kept, so out_cnt = min(k, chunk_lens[c] - |R_H|).
  * 0 <= class_lo <= class_hi <= chunk_len (an empty class gives Eq. 7), lambda not NaN
  * (+inf evicts nothing); otherwise as pc_select_tokens_topk.  No workspace. */
 int pc_select_tokens_calibrated(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,
                                 int32_t n_kv_heads, int32_t chunk_len, int32_t k, float lambda,
-                                int32_t class_lo, int32_t class_hi, int32_t* out_idx,
-                                int32_t* out_cnt, void* stream);
+                                int32_t class_lo, int32_t class_hi, const int32_t* chunk_lens,
+                                int32_t* out_idx, int32_t* out_cnt, void* stream);
 
 /* ---- Eq. 7 (compressed KV cache) -----------------------------------------------------------
  * dst[b, s, g, t, :] = src[b, chunk_idx[b, s], tok_idx[b, s, g, t], g, :]  for K and V.

@@ -54,11 +54,11 @@ def lib():
             "(the HIP extension is required; there is no CPU fallback)")
     L = ctypes.CDLL(_LIB_PATH)
     P = c_void_p
-    L.pc_chunk_prefill_attn.argtypes = [POINTER(pc_shape), P, P, P, P, P, P, P, P, P, c_size_t, P]
+    L.pc_chunk_prefill_attn.argtypes = [POINTER(pc_shape), P, P, P, P, P, P, P, P, P, P, c_size_t, P]
     L.pc_chunk_prefill_attn.restype = c_int
     L.pc_chunk_prefill_workspace_bytes.argtypes = [POINTER(pc_shape)]
     L.pc_chunk_prefill_workspace_bytes.restype = c_size_t
-    L.pc_chunk_query_scores.argtypes = [POINTER(pc_shape), P, P, P, P, P, c_size_t, P]
+    L.pc_chunk_query_scores.argtypes = [POINTER(pc_shape), P, P, P, P, P, P, c_size_t, P]
     L.pc_chunk_query_scores.restype = c_int
     L.pc_chunk_query_scores_workspace_bytes.argtypes = [POINTER(pc_shape)]
     L.pc_chunk_query_scores_workspace_bytes.restype = c_size_t
@@ -69,7 +69,7 @@ def lib():
     L.pc_gather_kv.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P]
     L.pc_gather_kv.restype = c_int
     L.pc_parallel_attn.argtypes = [P] * 4 + [c_int32, P, P] + [c_int32] * 8 + [c_float, c_float, P, P, P, c_size_t, P]
-    L.pc_select_tokens_calibrated.argtypes = [P, P] + [c_int32] * 4 + [c_float, c_int32, c_int32, P, P, P]
+    L.pc_select_tokens_calibrated.argtypes = [P, P] + [c_int32] * 4 + [c_float, c_int32, c_int32, P, P, P, P]
     L.pc_select_tokens_calibrated.restype = c_int
     L.pc_parallel_attn.restype = c_int
     L.pc_parallel_attn_workspace_bytes.argtypes = [c_int32] * 8
@@ -134,16 +134,18 @@ def pc_parallel_attn_workspace_bytes(batch, n_q, n_seg, k_t, n_q_heads, n_kv_hea
                                                   head_dim, int(has_self))
 
 
-def pc_chunk_prefill_attn(shape, q, k, v, o, lse, k_rope, tok_score, chunk_score, ws):
+def pc_chunk_prefill_attn(shape, q, k, v, o, lse, k_rope, tok_score, chunk_score, ws,
+                          chunk_lens=None):
     p, n = _ws(ws)
-    _check(lib().pc_chunk_prefill_attn(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
-                                       _ptr(lse), _ptr(k_rope), _ptr(tok_score), _ptr(chunk_score),
+    _check(lib().pc_chunk_prefill_attn(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v),
+                                       _ptr(chunk_lens), _ptr(o), _ptr(lse), _ptr(k_rope), _ptr(tok_score), _ptr(chunk_score),
                                        p, n, _stream()), "pc_chunk_prefill_attn")
 
 
-def pc_chunk_query_scores(shape, q, k, tok_score, chunk_score, ws):
+def pc_chunk_query_scores(shape, q, k, tok_score, chunk_score, ws, chunk_lens=None):
     p, n = _ws(ws)
-    _check(lib().pc_chunk_query_scores(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(tok_score),
+    _check(lib().pc_chunk_query_scores(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(chunk_lens),
+                                       _ptr(tok_score),
                                        _ptr(chunk_score), p, n, _stream()), "pc_chunk_query_scores")
 
 
@@ -159,10 +161,11 @@ def pc_select_tokens_topk(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k,
 
 
 def pc_select_tokens_calibrated(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, lam,
-                                class_lo, class_hi, out_idx, out_cnt):
+                                class_lo, class_hi, out_idx, out_cnt, chunk_lens=None):
     _check(lib().pc_select_tokens_calibrated(_ptr(tok_score), _ptr(chunk_idx), n_sel, n_kv_heads,
-                                             chunk_len, k, lam, class_lo, class_hi, _ptr(out_idx),
-                                             _ptr(out_cnt), _stream()),
+                                             chunk_len, k, lam, class_lo, class_hi,
+                                             _ptr(chunk_lens), _ptr(out_idx), _ptr(out_cnt),
+                                             _stream()),
            "pc_select_tokens_calibrated")
 
 

@@ -125,7 +125,7 @@ extern "C" size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* s) {
 }
 
 extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const void* k, const void* v,
-                                     void* o, float* lse, void* k_rope, float* tok_score,
+                                     const int32_t* chunk_lens, void* o, float* lse, void* k_rope, float* tok_score,
                                      float* chunk_score, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(s);
   if (rc != PC_OK) return rc;
@@ -161,19 +161,20 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads; a.head_dim = D;
   a.n_parts_grid = 1; a.n_parts_total = 1; a.part0 = 0;
   a.causal_offset = 0; a.q_pos0 = 0;
+  a.seq_ctx = chunk_lens; a.seq_add = s->query_len;
   a.scale = eff_scale(s->softmax_scale, D);
   rc = pc_launch_flash(a, st);
   if (rc != PC_OK) return rc;
 
   if (tok_score) {
-    rc = pc_launch_scores(s, q, k, table, base + w.ml, tok_score, chunk_score, st);
+    rc = pc_launch_scores(s, q, k, chunk_lens, table, base + w.ml, tok_score, chunk_score, st);
     if (rc != PC_OK) return rc;
   }
   return PC_OK;
 }
 
 extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const void* k,
-                                     float* tok_score, float* chunk_score, void* ws,
+                                     const int32_t* chunk_lens, float* tok_score, float* chunk_score, void* ws,
                                      size_t ws_bytes, void* stream) {
   int rc = check_shape(s);
   if (rc != PC_OK) return rc;
@@ -188,7 +189,7 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
   void* ml = (char*)ws + pc_align_up((size_t)L * (s->head_dim / 2) * sizeof(float2), kAlign);
   rc = pc_launch_rope_table(table, L, s->head_dim, s->rope_base, st);
   if (rc != PC_OK) return rc;
-  return pc_launch_scores(s, q, k, table, ml, tok_score, chunk_score, st);
+  return pc_launch_scores(s, q, k, chunk_lens, table, ml, tok_score, chunk_score, st);
 }
 
 extern "C" int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_t k,
@@ -207,14 +208,14 @@ extern "C" int pc_select_tokens_topk(const float* tok_score, const int32_t* chun
   if ((long long)n_sel * n_kv_heads > 0x7fffffffLL) return PC_ERR_SHAPE;
   if (n_sel == 0) return PC_OK;
   return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, 0.f, 0, 0,
-                                 out_idx, nullptr, (hipStream_t)stream);
+                                 nullptr, out_idx, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int pc_select_tokens_calibrated(const float* tok_score, const int32_t* chunk_idx,
                                            int32_t n_sel, int32_t n_kv_heads, int32_t chunk_len,
                                            int32_t k, float lambda, int32_t class_lo,
-                                           int32_t class_hi, int32_t* out_idx, int32_t* out_cnt,
-                                           void* stream) {
+                                           int32_t class_hi, const int32_t* chunk_lens,
+                                           int32_t* out_idx, int32_t* out_cnt, void* stream) {
   if (!tok_score || !out_idx || !out_cnt) return PC_ERR_NULL;
   if (n_sel < 0 || n_kv_heads < 1 || chunk_len < 1 || chunk_len > 32768 || k < 1 || k > chunk_len)
     return PC_ERR_SHAPE;
@@ -222,7 +223,7 @@ extern "C" int pc_select_tokens_calibrated(const float* tok_score, const int32_t
   if (class_lo < 0 || class_hi < class_lo || class_hi > chunk_len || lambda != lambda) return PC_ERR_SHAPE;
   if (n_sel == 0) return PC_OK;
   return pc_launch_select_tokens(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, lambda,
-                                 class_lo, class_hi, out_idx, out_cnt, (hipStream_t)stream);
+                                 class_lo, class_hi, chunk_lens, out_idx, out_cnt, (hipStream_t)stream);
 }
 
 extern "C" int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,

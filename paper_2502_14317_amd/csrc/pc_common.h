@@ -89,7 +89,8 @@ int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, 
 // cls_lo >= cls_hi: plain top-k (Eq. 7); else Eq. 8 first.  out_cnt may be nullptr.
 int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
                             int n_kv_heads, int chunk_len, int k, float lambda, int cls_lo,
-                            int cls_hi, int32_t* out_idx, int32_t* out_cnt, hipStream_t st);
+                            int cls_hi, const int32_t* chunk_lens, int32_t* out_idx,
+                            int32_t* out_cnt, hipStream_t st);
 
 int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st);
 
@@ -112,6 +113,8 @@ struct PcFlashArgs {
   float* part_lse;          // [n_seq, n_parts_total, n_rows, H_q]
   const int32_t* part_len;  // [n_seq, n_parts_grid] (x [n_kv_heads] if part_len_per_head) valid keys per part, or nullptr (= n_keys)
   int part_len_per_head;
+  const int32_t* seq_ctx;   // [n_seq] context rows per sequence or nullptr: sequence s has
+  int seq_add;              //   min(seq_ctx[s], n_rows - seq_add) + seq_add rows (and keys)
   long long img_seq_stride, img_part_stride, img_head_stride;              // in tile images
   int n_seq, n_rows, n_keys, n_q_heads, n_kv_heads, head_dim;
   int n_parts_grid, n_parts_total, part0;
@@ -123,7 +126,7 @@ struct PcFlashArgs {
 int pc_launch_flash(const PcFlashArgs& a, hipStream_t st);
 
 size_t pc_scores_ml_bytes(const pc_shape* s);
-int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const float2* table,
+int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
                      void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st);
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,

@@ -205,6 +205,9 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   const int tid = threadIdx.x, lane = tid % PC_WAVE, wave = tid / PC_WAVE;
   const int hf = lane / 32, n = lane % 32;
   const int row0_wg = qt * PC_FA_BM;
+  // rows (= keys) of this sequence: a short chunk is [its context rows ; the query rows]
+  const int seq_rows = a.seq_ctx ? min(max(a.seq_ctx[seq], 0), a.n_rows - a.seq_add) + a.seq_add : a.n_rows;
+  if (row0_wg >= seq_rows) return;                 // a Q tile of padding rows (uniform over the workgroup)
   constexpr int NB = PC_FA_NB;
   const int row0 = row0_wg + 32 * NB * wave;      // first query row of this wavefront
   int my_row[NB], max_key[NB];
@@ -212,7 +215,8 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   // ---- keys of this workgroup: [0, key_end) of the part
   const int len_idx = a.part_len_per_head ? (seq * a.n_parts_grid + part) * a.n_kv_heads + g
                                           : seq * a.n_parts_grid + part;
-  const int n_valid = a.part_len ? min(max(a.part_len[len_idx], 0), a.n_keys) : a.n_keys;
+  const int n_valid = a.part_len ? min(max(a.part_len[len_idx], 0), a.n_keys)
+                                 : (a.seq_ctx ? min(a.n_keys, seq_rows) : a.n_keys);
   int key_end = n_valid;
   if (a.causal_offset < PC_NO_CAUSAL) key_end = min(key_end, row0_wg + PC_FA_BM + a.causal_offset);
   const int T = (key_end + PC_FA_BN - 1) / PC_FA_BN;          // 64-key tiles
@@ -233,7 +237,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   for (int nb = 0; nb < NB; ++nb) {
     my_row[nb] = row0 + 32 * nb + n;
     max_key[nb] = min(my_row[nb] + a.causal_offset, n_valid - 1);
-    const int ld_row = min(my_row[nb], a.n_rows - 1);
+    const int ld_row = min(my_row[nb], seq_rows - 1);
     const uint16_t* qrow = (const uint16_t*)a.q + (((long long)seq * a.n_rows + ld_row) * a.n_q_heads + h) * D;
     if (ROPE_Q) {
       const float2* cs = a.table + (long long)(a.q_pos0 + ld_row) * HALF;
@@ -559,7 +563,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     const float l = pc_xhalf_sum(l_run[nb]);
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
     const float lse = l > 0.f ? m_run[nb] * PC_LN2 + logf(l) : -INFINITY;
-    if (my_row[nb] < a.n_rows) {
+    if (my_row[nb] < seq_rows) {
       if (PARTIAL) {
         const long long prow = ((((long long)seq * a.n_parts_total + a.part0 + part) * a.n_rows) + my_row[nb]) * a.n_q_heads + h;
         float* po = a.part_o + prow * D;

@@ -28,6 +28,7 @@
 struct PcScoreArgs {
   const uint16_t* q;       // [C, L, H_q, D] before RoPE
   const uint16_t* k;       // [C, L, H_kv, D] before RoPE
+  const int32_t* chunk_lens; // [C] context rows per chunk or nullptr (= w)
   const float2* table;     // [L, D/2] (cos, sin)
   float2* ml;              // workspace [C, H_kv, n_kb, n_cols] (max in log2 units, sum)
   float* tok_score;        // [C, H_kv, w]
@@ -55,7 +56,9 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
   const int tid = threadIdx.x, lane = tid % PC_WAVE, wave = tid / PC_WAVE;
   const int hf = lane / 32, n = lane % 32;
   const int n_cb = (a.n_cols + 31) / 32;
-  const int first_obs = a.L - a.w_obs;
+  // a short chunk is [len context rows ; the query rows]: its voting rows end at len + w_q
+  const int ctx_len = a.chunk_lens ? min(max(a.chunk_lens[c], 0), a.w) : a.w;
+  const int first_obs = ctx_len + (a.L - a.w) - a.w_obs;
   const long long ml_base = (((long long)c * a.n_kv_heads + g) * a.n_kb) * a.n_cols;
 
   if (PASS == 2) {
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
       float x = 0.f;
 #pragma unroll
       for (int wv = 0; wv < PC_SC_WAVES; ++wv) x += tok_part[wv][tid];
-      a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = x;
+      a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = key < ctx_len ? x : 0.f;
     }
   }
 }
@@ -262,10 +265,10 @@ size_t pc_scores_ml_bytes(const pc_shape* s) {
   return (size_t)s->n_chunks * s->n_kv_heads * n_kb * n_cols * sizeof(float2);
 }
 
-int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const float2* table,
+int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
                      void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st) {
   PcScoreArgs a;
-  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.table = table;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.table = table; a.chunk_lens = chunk_lens;
   a.ml = (float2*)ml_ws; a.tok_score = tok_score;
   a.L = s->chunk_len + s->query_len; a.w = s->chunk_len; a.w_obs = s->obs_window;
   a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads;

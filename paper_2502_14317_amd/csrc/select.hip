@@ -53,8 +53,8 @@ int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, 
 
 __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
     const float* __restrict__ tok_score, const int32_t* __restrict__ chunk_idx, int n_kv_heads,
-    int n, int k, float lambda, int cls_lo, int cls_hi, int32_t* __restrict__ out_idx,
-    int32_t* __restrict__ out_cnt) {
+    int n, int k, float lambda, int cls_lo, int cls_hi, const int32_t* __restrict__ chunk_lens,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_cnt) {
   extern __shared__ uint32_t keys[];   // n
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sh_bin, sh_need, sh_evicted;
@@ -66,6 +66,7 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
   const float* src = tok_score + ((long long)c * n_kv_heads + g) * n;
   int32_t* dst = out_idx + (long long)blockIdx.x * k;
 
+  const int n_valid = chunk_lens ? min(max(chunk_lens[c], 0), n) : n;   // a short chunk has fewer tokens
   if (threadIdx.x == 0) sh_evicted = 0;
   __syncthreads();
   uint32_t my_evicted = 0;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
     const float x = src[i];
     uint32_t key = pc_order_key(x);
     key = key == 0u ? 1u : key;
-    if (i >= cls_lo && i < cls_hi && x > lambda) { key = 0u; ++my_evicted; }
+    if ((i >= cls_lo && i < cls_hi && x > lambda) || i >= n_valid) { key = 0u; ++my_evicted; }
     keys[i] = key;
   }
   if (my_evicted) atomicAdd(&sh_evicted, my_evicted);
@@ -148,7 +149,8 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
 
 int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, int n_sel,
                             int n_kv_heads, int chunk_len, int k, float lambda, int cls_lo,
-                            int cls_hi, int32_t* out_idx, int32_t* out_cnt, hipStream_t st) {
+                            int cls_hi, const int32_t* chunk_lens, int32_t* out_idx,
+                            int32_t* out_cnt, hipStream_t st) {
   const size_t lds = (size_t)chunk_len * sizeof(uint32_t);
   if (lds > 48 * 1024) {
     PC_HIP_TRY(hipFuncSetAttribute((const void*)select_tokens_kernel,
@@ -157,7 +159,7 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
   PcProfScope prof(PC_KERNEL_SELECT_TOKENS, st);
   hipLaunchKernelGGL(select_tokens_kernel, dim3(n_sel * n_kv_heads), dim3(PC_SEL_THREADS), lds, st,
                      tok_score, chunk_idx, n_kv_heads, chunk_len, k, lambda, cls_lo, cls_hi,
-                     out_idx, out_cnt);
+                     chunk_lens, out_idx, out_cnt);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }

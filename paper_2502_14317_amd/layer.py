@@ -17,6 +17,8 @@ class ParallelCompLayer:
         self.kc_n, self.kt_n = keep_chunks, keep_tokens
         self.rope_base, self.scale = rope_base, softmax_scale
         self.calibration = calibration          # None or (lambda, class_lo, class_hi) of Eq. 8
+        self.chunk_lens = None                  # set by chunk_prefill for ragged chunks
+        self.first_len = chunk_len
         self.shape = B.make_shape(n_chunks, chunk_len, query_len, n_q_heads, n_kv_heads, head_dim,
                                   obs_window, rope_base, softmax_scale)
         dev, bf, f32, i32 = device, torch.bfloat16, torch.float32, torch.int32
@@ -40,35 +42,120 @@ class ParallelCompLayer:
                                                             Hq, Hkv, D, True))
         self.ws = B.alloc_workspace(ws, dev)
 
-    def chunk_prefill(self, q, k, v, with_scores=True):
-        """Eq. 1-2 and 5-6 for all chunks: fills o, lse, k_rope, tok_score, chunk_score."""
+    def chunk_prefill(self, q, k, v, with_scores=True, chunk_lens=None, first_len=None):
+        """Eq. 1-2 and 5-6 for all chunks: fills o, lse, k_rope, tok_score, chunk_score.
+        chunk_lens [C] int32 (device): ragged chunks, see pc_chunk_prefill_attn; first_len is
+        chunk_lens[0] as a host integer (where chunk 0's query rows sit; default w)."""
+        self.chunk_lens = chunk_lens
+        self.first_len = self.w if first_len is None else int(first_len)
         B.pc_chunk_prefill_attn(self.shape, q, k, v, self.o, self.lse, self.k_rope,
                                 self.tok_score if with_scores else None,
-                                self.chunk_score if with_scores else None, self.ws)
+                                self.chunk_score if with_scores else None, self.ws,
+                                chunk_lens=chunk_lens)
 
     def evict_and_attend(self, q, v):
         """Eq. 3-4 mechanics, Eq. 7 (after Eq. 8 when calibration is set) and Eq. 9-11 on the
         results of chunk_prefill."""
         C, L, w = self.C, self.L, self.w
         B.pc_select_chunks_topk(self.chunk_score, C, self.kc_n, self.chunk_idx, self.chunk_top)
-        if self.calibration is None:
+        if self.calibration is None and self.chunk_lens is None:
             B.pc_select_tokens_topk(self.tok_score, self.chunk_idx, self.kc_n, self.Hkv, w,
                                     self.kt_n, self.tok_idx)
             seg_len, per_head = None, 0
         else:
-            lam, lo, hi = self.calibration
+            lam, lo, hi = self.calibration if self.calibration is not None else (float("inf"), 0, 0)
             B.pc_select_tokens_calibrated(self.tok_score, self.chunk_idx, self.kc_n, self.Hkv, w,
-                                          self.kt_n, lam, lo, hi, self.tok_idx, self.tok_cnt)
+                                          self.kt_n, lam, lo, hi, self.tok_idx, self.tok_cnt,
+                                          chunk_lens=self.chunk_lens)
             seg_len, per_head = self.tok_cnt, 1
         B.pc_gather_kv(self.k_rope, v, self.chunk_idx, self.tok_idx, 1, C, L, self.kc_n, self.Hkv,
                        self.kt_n, self.D, self.kc, self.vc)
-        B.pc_parallel_attn(q[0, w:], self.kc, self.vc, seg_len, self.k_rope[0, w:], v[0, w:], 1,
-                           self.wq, self.kc_n, self.kt_n, self.Hq, self.Hkv, self.D, w,
+        w0 = self.first_len
+        B.pc_parallel_attn(q[0, w0:w0 + self.wq], self.kc, self.vc, seg_len,
+                           self.k_rope[0, w0:w0 + self.wq], v[0, w0:w0 + self.wq], 1,
+                           self.wq, self.kc_n, self.kt_n, self.Hq, self.Hkv, self.D, w0,
                            self.rope_base, self.scale, self.global_o, self.global_lse, self.ws,
                            seg_len_per_head=per_head)
 
-    def forward(self, q, k, v):
-        self.chunk_prefill(q, k, v, with_scores=True)
+    def forward(self, q, k, v, chunk_lens=None, first_len=None):
+        self.chunk_prefill(q, k, v, with_scores=True, chunk_lens=chunk_lens, first_len=first_len)
         if self.kc_n > 0:
             self.evict_and_attend(q, v)
         return self.global_o if self.kc_n > 0 else self.o
+
+
+class StreamingParallelComp:
+    """The same layer with the chunks arriving in memory-sized batches (sec. 3.1: chunks are
+    encoded a batch at a time and a fixed-size priority queue keeps the best ones).  After each
+    batch the queue holds the top keep_chunks of all chunks seen so far (score descending, earlier
+    chunk first on ties, i.e. the offline top-k of the prefix); only the compacted KV of the chunks
+    in the queue stays resident, an evicted chunk's slot is reused.  The final queue equals the
+    offline selection, whatever the batch size.  Host code here only owns buffers and the
+    chunk-id -> slot table; every computation is a library call."""
+
+    def __init__(self, n_chunks, batch_chunks, chunk_len, query_len, n_q_heads, n_kv_heads,
+                 head_dim, obs_window, rope_base, keep_chunks, keep_tokens, softmax_scale=0.0,
+                 device="cuda"):
+        self.C, self.bc = n_chunks, min(batch_chunks, n_chunks)
+        self.w, self.wq, self.L = chunk_len, query_len, chunk_len + query_len
+        self.Hq, self.Hkv, self.D = n_q_heads, n_kv_heads, head_dim
+        self.obs, self.rope_base, self.scale = obs_window, rope_base, softmax_scale
+        self.kc_n, self.kt_n = min(keep_chunks, n_chunks), keep_tokens
+        bf, f32, i32 = torch.bfloat16, torch.float32, torch.int32
+        bc, L, Hq, Hkv, D = self.bc, self.L, n_q_heads, n_kv_heads, head_dim
+        self.o = torch.empty((bc, L, Hq, D), dtype=bf, device=device)
+        self.lse = torch.empty((bc, Hq, L), dtype=f32, device=device)
+        self.k_rope = torch.empty((bc, L, Hkv, D), dtype=bf, device=device)
+        self.tok_score = torch.empty((bc, Hkv, chunk_len), dtype=f32, device=device)
+        self.chunk_score = torch.empty((n_chunks,), dtype=f32, device=device)     # all chunks seen
+        self.chunk_idx = torch.empty((self.kc_n,), dtype=i32, device=device)
+        self.tok_idx = torch.empty((self.kc_n, Hkv, keep_tokens), dtype=i32, device=device)   # by slot
+        self.kc = torch.empty((1, self.kc_n, Hkv, keep_tokens, D), dtype=bf, device=device)   # by slot
+        self.vc = torch.empty_like(self.kc)
+        self.q_query = torch.empty((query_len, Hq, D), dtype=bf, device=device)
+        self.k_self = torch.empty((query_len, Hkv, D), dtype=bf, device=device)
+        self.v_self = torch.empty_like(self.k_self)
+        self.global_o = torch.empty((1, query_len, Hq, D), dtype=bf, device=device)
+        self.global_lse = torch.empty((1, Hq, query_len), dtype=f32, device=device)
+        shape = B.make_shape(bc, chunk_len, query_len, Hq, Hkv, D, obs_window, rope_base, softmax_scale)
+        ws = max(B.pc_chunk_prefill_workspace_bytes(shape),
+                 B.pc_parallel_attn_workspace_bytes(1, query_len, self.kc_n, keep_tokens, Hq, Hkv, D, True))
+        self.ws = B.alloc_workspace(ws, device)
+        self.slot_of = {}            # global chunk id -> slot of its compacted KV
+        self.one = torch.zeros((1,), dtype=i32, device=device)
+
+    def forward(self, q, k, v):
+        """q [C, L, H_q, D], k, v [C, L, H_kv, D] (any device-resident source; only one batch is
+        touched at a time).  Returns the global attention output of the query rows."""
+        free = list(range(self.kc_n))
+        self.slot_of = {}
+        for c0 in range(0, self.C, self.bc):
+            c1 = min(c0 + self.bc, self.C)
+            nb = c1 - c0
+            shape = B.make_shape(nb, self.w, self.wq, self.Hq, self.Hkv, self.D, self.obs,
+                                 self.rope_base, self.scale)
+            B.pc_chunk_prefill_attn(shape, q[c0:c1], k[c0:c1], v[c0:c1], self.o[:nb], self.lse[:nb],
+                                    self.k_rope[:nb], self.tok_score[:nb], self.chunk_score[c0:c1],
+                                    self.ws)
+            if c0 == 0:              # the query rows of chunk 0 are the self segment (plain copies)
+                self.q_query.copy_(q[0, self.w:]); self.k_self.copy_(self.k_rope[0, self.w:])
+                self.v_self.copy_(v[0, self.w:])
+            keep = min(self.kc_n, c1)
+            B.pc_select_chunks_topk(self.chunk_score, c1, keep, self.chunk_idx, None)
+            queue = self.chunk_idx[:keep].tolist()                     # host: queue membership
+            for c in [c for c in self.slot_of if c not in queue]:
+                free.append(self.slot_of.pop(c))
+            for c in [c for c in queue if c not in self.slot_of]:      # entrants are in this batch
+                slot = free.pop()
+                self.slot_of[c] = slot
+                self.one.fill_(c - c0)
+                B.pc_select_tokens_topk(self.tok_score, self.one, 1, self.Hkv, self.w, self.kt_n,
+                                        self.tok_idx[slot:slot + 1])
+                B.pc_gather_kv(self.k_rope, v[c0:c1], self.one, self.tok_idx[slot:slot + 1], 1, nb,
+                               self.L, 1, self.Hkv, self.kt_n, self.D, self.kc[:, slot:slot + 1],
+                               self.vc[:, slot:slot + 1])
+        n_seg = len(self.slot_of)
+        B.pc_parallel_attn(self.q_query, self.kc, self.vc, None, self.k_self, self.v_self, 1, self.wq,
+                           n_seg, self.kt_n, self.Hq, self.Hkv, self.D, self.w, self.rope_base,
+                           self.scale, self.global_o, self.global_lse, self.ws)
+        return self.global_o

@@ -48,29 +48,29 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_select_tokens_topk(one, None, 1, 1, 8, 9, one, None) == -2
     assert L.pc_select_tokens_topk(one, None, 1, 1, 40000, 2, one, None) == -2
     # calibrated token selection (Eq. 8): class bounds and lambda are checked on the host
-    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 4, one, None, None) == -1
-    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 5, 4, one, one, None) == -2
-    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 9, one, one, None) == -2
-    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, float('nan'), 0, 4, one, one, None) == -2
-    assert L.pc_select_tokens_calibrated(one, None, 0, 1, 8, 2, 0.5, 0, 4, one, one, None) == 0
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 4, None, one, None, None) == -1
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 5, 4, None, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, 0.5, 0, 9, None, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 1, 1, 8, 2, float('nan'), 0, 4, None, one, one, None) == -2
+    assert L.pc_select_tokens_calibrated(one, None, 0, 1, 8, 2, 0.5, 0, 4, None, one, one, None) == 0
     # gather
     assert L.pc_gather_kv(one, one, None, None, 1, 1, 8, 1, 1, 2, 128, one, one, None) == -1
     assert L.pc_gather_kv(one, one, None, one, 1, 1, 8, 1, 1, 2, 96, one, one, None) == -2
     # prefill
     good = pc.make_shape(2, 64, 16, 8, 2, 128, 8, 1e4)
-    assert L.pc_chunk_prefill_attn(None, one, one, one, one, one, None, None, None, one, 1 << 30, None) == -1
-    assert L.pc_chunk_prefill_attn(ctypes.byref(good), None, one, one, one, one, None, None, None, one, 1 << 30, None) == -1
-    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, None, one, 16, None) == -3
-    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, None, None, 0, None) == -3
+    assert L.pc_chunk_prefill_attn(None, one, one, one, None, one, one, None, None, None, one, 1 << 30, None) == -1
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), None, one, one, None, one, one, None, None, None, one, 1 << 30, None) == -1
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, None, one, one, None, None, None, one, 16, None) == -3
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, None, one, one, None, None, None, None, 0, None) == -3
     for field, value in (("head_dim", 96), ("n_q_heads", 7), ("n_chunks", 0), ("rope_base", 0.5)):
         bad = pc.make_shape(2, 64, 16, 8, 2, 128, 8, 1e4)
         setattr(bad, field, value)
-        assert L.pc_chunk_prefill_attn(ctypes.byref(bad), one, one, one, one, one, None, None, None, one, 1 << 30, None) == -2
+        assert L.pc_chunk_prefill_attn(ctypes.byref(bad), one, one, one, None, one, one, None, None, None, one, 1 << 30, None) == -2
         assert pc.pc_chunk_prefill_workspace_bytes(bad) == 0
     bad = pc.make_shape(2, 64, 16, 8, 2, 128, 100, 1e4)     # obs_window too large
-    assert L.pc_chunk_query_scores(ctypes.byref(bad), one, one, one, None, one, 1 << 30, None) == -2
+    assert L.pc_chunk_query_scores(ctypes.byref(bad), one, one, None, one, None, one, 1 << 30, None) == -2
     # chunk_score without tok_score
-    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, one, one, None, None, one, one, 1 << 30, None) == -1
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, None, one, one, None, None, one, one, 1 << 30, None) == -1
     # parallel attention
     args = (1, 1, 2, 64, 8, 2, 128, -1, 1e4, 0.0)
     assert L.pc_parallel_attn(None, one, one, None, 0, None, None, *args, one, None, one, 1 << 30, None) == -1
