@@ -13,6 +13,7 @@ and follows the paper's order of steps:
   local_attention       Eq. 1-2: A = Softmax(Q K^T / sqrt(d)), F = A V, inside one chunk
   query_scores          Eq. 5-6: cumulative query->key attention, summed over voting rows
   select_chunks         Eq. 3-4 mechanics: fixed number of best chunks (see readings below)
+  chunk_self_information  Eq. 3: I_c = -log P(X^q | X^c) from given language-model logits
   select_tokens         Eq. 7: retained token set per head per chunk
   select_tokens_calibrated  Eq. 8 then Eq. 7: evict the tokens of one position class whose score
                         exceeds lambda (R_H), keep the best of the rest
@@ -31,8 +32,11 @@ Readings of the paper taken here (the paper is silent or ambiguous on each):
   * The kept set of Eq. 7 is the top-k by score; ties go to the lower index.
   * GQA: a KV head's score is the sum over the query heads that read it.
   * Chunk criterion: the query's attention mass on the chunk (sum of its token scores),
-    larger is better.  This replaces Eq. 3's self-information, which needs a language-model
-    head and trained weights: selection against the paper's own criterion is PARITY UNPINNED.
+    larger is better.  This replaces Eq. 3's self-information inside the layer, which needs a
+    language-model head and trained weights: selection against the paper's own criterion on
+    real text is PARITY UNPINNED.  chunk_self_information computes Eq. 3 itself from given
+    logits (synthetic ones here); select_chunks(-I, k) is then Eq. 4's "lowest I_c, fixed count"
+    (Eq. 4 as printed compares the index c with a threshold: read as I_c <= epsilon).
   * In global attention keys keep their chunk-local rotation and query row t sits at w + t.
   * Attention calibration (Eq. 8): the text evicts R_H although the equation indexes the
     retained cache with it (as Eq. 7 does with R_L); R_H = tokens of ONE position class (a
@@ -120,6 +124,24 @@ def query_scores(q_rot, k_rot, chunk_len, obs_window, n_kv_heads, scale=None):
     col = P.sum(axis=0)                                          # [H_q, L]
     tok = col.reshape(n_kv_heads, G, L).sum(axis=1)[:, :chunk_len]
     return tok, tok.sum()
+
+
+# --------------------------------------------------------------------------- Eq. 3
+def chunk_self_information(logits, targets):
+    """Self-information of the query tokens given each chunk (Eq. 3).
+
+    logits [C, n_t, V]: row (c, t) holds the language model's logits for query token t after
+    chunk c and the query tokens before t; targets [n_t]: the query's token ids.  By the chain
+    rule  I_c = -log P(X^q | X^c) = sum_t ( log sum_v exp(logits[c, t, v]) - logits[c, t, targets[t]] ).
+    Returns (I [C], nll [C, n_t]) in nats.  Lower I = more relevant chunk (Eq. 4 keeps those).
+    """
+    logits = np.asarray(logits, dtype=np.float64)
+    targets = np.asarray(targets, dtype=np.int64)
+    m = logits.max(axis=2)
+    lse = m + np.log(np.exp(logits - m[..., None]).sum(axis=2))
+    tgt = np.take_along_axis(logits, targets[None, :, None], axis=2)[..., 0]
+    nll = lse - tgt
+    return nll.sum(axis=1), nll
 
 
 # --------------------------------------------------------------------------- selection

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from workloads import (CFG0, CFG0U, CFG1_SMALL, CFG2_SMALL, prefill_inputs, bf16_bits_to_f64,
-                       relevant_chunks, f32_to_bf16_bits, bf16_bits_to_f32)
+                       relevant_chunks, f32_to_bf16_bits, bf16_bits_to_f32, lm_logits_inputs)
 
 
 def _rng(seed):
@@ -515,6 +515,53 @@ def test_streaming_priority_queue_equals_offline_top_k():
                 seen = min(c0 + batch, n)
                 assert [c for _, c in queue] == list(oracle.select_chunks(score[:seen], min(k, seen)))
             assert [c for _, c in queue] == want
+
+
+# ------------------------------------------------------------------ Eq. 3 (chunk self-information)
+def test_self_information_brute_force_and_closed_forms():
+    """I_c = -log P(X^q | X^c) by the chain rule over given logits: plain loops with math.exp /
+    math.log; uniform logits give n_t log V; a constant added to a row changes nothing; raising
+    the target logit by a over uniform logits gives log(V - 1 + e^a) - a per token; the
+    probabilities exp(-nll) of all possible targets of a row sum to one."""
+    r = _rng(51)
+    C, T, V = 3, 4, 7
+    logits = r.standard_normal((C, T, V)) * 3
+    targets = r.integers(0, V, size=T)
+    I, nll = oracle.chunk_self_information(logits, targets)
+    for c in range(C):
+        tot = 0.0
+        for t in range(T):
+            z = sum(math.exp(logits[c, t, v_]) for v_ in range(V))
+            p = math.exp(logits[c, t, targets[t]]) / z
+            assert abs(nll[c, t] + math.log(p)) < 1e-12
+            tot -= math.log(p)
+        assert abs(I[c] - tot) < 1e-11
+    I0, _ = oracle.chunk_self_information(np.full((2, 5, 11), 0.37), np.arange(5))
+    np.testing.assert_allclose(I0, 5 * math.log(11), rtol=1e-14)
+    I1, _ = oracle.chunk_self_information(logits + r.standard_normal((C, T, 1)) * 50, targets)
+    np.testing.assert_allclose(I1, I, rtol=1e-12)
+    a = 2.5
+    x = np.zeros((1, 3, 9)); x[0, np.arange(3), [4, 0, 8]] = a
+    I2, _ = oracle.chunk_self_information(x, [4, 0, 8])
+    np.testing.assert_allclose(I2, 3 * (math.log(8 + math.exp(a)) - a), rtol=1e-14)
+    total = np.zeros((C, T))
+    for v_ in range(V):
+        _, n_v = oracle.chunk_self_information(logits, np.full(T, v_))
+        total += np.exp(-n_v)
+    np.testing.assert_allclose(total, 1.0, rtol=1e-12)
+    big = np.array([[[1000.0, 999.0, -1000.0]]])                   # no overflow
+    np.testing.assert_allclose(oracle.chunk_self_information(big, [1])[0], math.log(1 + math.exp(1.0)), rtol=1e-12)
+
+
+def test_self_information_ranks_planted_chunks_first():
+    """Synthetic logits in which the query is more predictable after chunks 1 and 4: Eq. 4 keeps
+    the chunks of lowest self-information, i.e. the top-k of -I."""
+    lb, targets = lm_logits_inputs(6, 24, 512, relevant=(4, 1))
+    I, _ = oracle.chunk_self_information(bf16_bits_to_f64(lb), targets)
+    assert sorted(oracle.select_chunks(-I, 2)) == [1, 4]
+    assert I[[1, 4]].max() < I[[0, 2, 3, 5]].min()
+    lb2, t2 = lm_logits_inputs(6, 24, 512, relevant=(4, 1))
+    assert np.array_equal(lb, lb2) and np.array_equal(targets, t2)
 
 
 def test_workload_plant_makes_relevant_chunks_win():

@@ -173,3 +173,21 @@ def gather_inputs(cfg: DecodeConfig, threads: int = 8):
         list(ex.map(fill, range(B)))
     chunk_idx = np.arange(S, dtype=np.int32)
     return ks, vs, chunk_idx, idx
+
+
+def lm_logits_inputs(n_chunks: int, n_tokens: int, vocab: int, relevant=(), boost: float = 1.5,
+                     cfg_id: int = 31):
+    """Synthetic language-model logits for the query tokens after every chunk (stand-in for an LM
+    head's output: no trained weights here).  logits [C, n_tokens, vocab] as bf16 bit patterns,
+    N(0, 2^2) entries; targets [n_tokens] int32, the query's own token ids (the same for every
+    chunk).  For the chunks listed in `relevant`, the target token's logit is raised by `boost`
+    at every position: the query is more predictable after a relevant chunk."""
+    rng = _rng(cfg_id, 0)
+    targets = rng.integers(0, vocab, size=n_tokens).astype(np.int32)
+    logits = np.empty((n_chunks, n_tokens, vocab), dtype=np.uint16)
+    for c in range(n_chunks):
+        x = _normal(_rng(cfg_id, 1 + c), (n_tokens, vocab), 2.0)
+        if c in set(int(r) for r in relevant):
+            x[np.arange(n_tokens), targets] += np.float32(boost)
+        logits[c] = f32_to_bf16_bits(x)
+    return logits, targets
