@@ -96,6 +96,35 @@ def bench_streaming(torch, cfg, qd, kd, vd, steps):
     return out
 
 
+def bench_self_info(pc, torch, steps):
+    """Eq. 3 reducer on logits shaped like the 128K workload's: 16 chunks x 512 query tokens x a
+    128256-entry vocabulary in bf16 (2.1 GB), each logit read once: an HBM-bound streaming pass."""
+    C, T, V = 16, 512, 128256
+    g = torch.Generator(device="cuda").manual_seed(3)
+    logits = torch.empty((C, T, V), dtype=torch.bfloat16, device="cuda")
+    for c in range(C):
+        logits[c] = (torch.randn((T, V), generator=g, device="cuda") * 2.0).to(torch.bfloat16)
+    targets = torch.randint(0, V, (T,), generator=g, device="cuda", dtype=torch.int32)
+    nll = torch.empty((C, T), dtype=torch.float32, device="cuda")
+    info = torch.empty((C,), dtype=torch.float32, device="cuda")
+    run = lambda: pc.pc_chunk_self_information(logits, targets, C, T, V, True, nll, info)
+    run(); torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    ms = [m for n, m in pc.pc_profile_records() if n == "self_info_rows_kernel"]
+    avg = sum(ms) / len(ms) * 1e-3
+    nbytes = C * T * V * 2.0
+    del logits
+    torch.cuda.empty_cache()
+    return {"workload": "16 chunks x 512 query tokens x vocab 128256, bf16 logits",
+            "roofline": {"bound": "hbm", "kernel": "self_info_rows_kernel", "achieved": nbytes / avg / 1e9,
+                         "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": nbytes / avg / PEAK_HBM_BYTES,
+                         "kernel_ms": avg * 1e3, "traffic": None}}
+
+
 def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
@@ -359,6 +388,7 @@ def main():
         del qd, kd, vd
         torch.cuda.empty_cache()
         result["secondary"] = bench_secondary(pc, torch, max(args.steps, 5), args.warmup)
+        result["self_information"] = bench_self_info(pc, torch, max(args.steps, 5))
         result["ceilings"] = bench_ceilings(pc, torch)
         print(f"[bench] secondary done; ceilings {result['ceilings']}", file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:

@@ -95,6 +95,22 @@ int pc_chunk_query_scores(const pc_shape* shape, const void* q, const void* k,
                           void* ws, size_t ws_bytes, void* stream);
 size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* shape);
 
+/* ---- Eq. 3 ----------------------------------------------------------------------------------
+ * Self-information of the query tokens given each chunk, from the language model's logits:
+ *   token_nll[c, t] = log sum_v exp(logits[c, t, v]) - logits[c, t, targets[t]]      (nats)
+ *   info[c]         = sum_t token_nll[c, t] = -log P(X^q | X^c), or its negative if negate != 0
+ *                     (so that pc_select_chunks_topk, which keeps the largest scores, keeps the
+ *                     chunks of lowest self-information, as Eq. 4 asks)
+ *   logits  [n_chunks, n_tokens, vocab] bf16 (device): row (c, t) = the logits that predict query
+ *           token t after chunk c; producing them (the LM head) is the caller's business
+ *   targets [n_tokens] int32 (device), clamped to [0, vocab);  token_nll [n_chunks, n_tokens] fp32
+ *           out (also the scratch of the reduction: required);  info [n_chunks] fp32 out.
+ * fp32 accumulation in a fixed order (deterministic).  vocab % 8 == 0, 8 <= vocab <= 2^24,
+ * n_chunks * n_tokens < 2^31, logits 16-byte aligned.  No workspace. */
+int pc_chunk_self_information(const void* logits, const int32_t* targets, int32_t n_chunks,
+                              int32_t n_tokens, int32_t vocab, int32_t negate, float* token_nll,
+                              float* info, void* stream);
+
 /* ---- Eq. 3-4 mechanics ---------------------------------------------------------------------
  * Keep a fixed number of chunks: out_idx[0..k) = indices of the k largest chunk_score under
  * the total order (score descending, index ascending), in that rank order; out_score
@@ -177,7 +193,7 @@ typedef enum pc_kernel_id {
   PC_KERNEL_ROPE_TABLE = 0, PC_KERNEL_KV_PREPASS = 1, PC_KERNEL_FLASH = 2, PC_KERNEL_SCORES_P1 = 3,
   PC_KERNEL_SCORES_P2 = 4, PC_KERNEL_CHUNK_SCORE = 5, PC_KERNEL_SELECT_CHUNKS = 6,
   PC_KERNEL_SELECT_TOKENS = 7, PC_KERNEL_GATHER = 8, PC_KERNEL_ROPE_Q = 9, PC_KERNEL_DECODE = 10,
-  PC_KERNEL_MERGE = 11, PC_KERNEL_COUNT = 12
+  PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_COUNT = 13
 } pc_kernel_id;
 int         pc_profile_begin(void);
 int         pc_profile_end(void);

@@ -21,7 +21,7 @@ SYMBOLS = [
     "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
     "pc_select_tokens_calibrated", "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
-    "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling",
+    "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information",
 ]
 
 
@@ -85,6 +85,8 @@ def lib():
     L.pc_kernel_name.restype = c_char_p
     L.pc_mfma_ceiling.argtypes = [c_int, c_int, c_int, P, c_size_t, POINTER(ctypes.c_double), P]
     L.pc_mfma_ceiling.restype = c_int
+    L.pc_chunk_self_information.argtypes = [P, P, c_int32, c_int32, c_int32, c_int32, P, P, P]
+    L.pc_chunk_self_information.restype = c_int
     _lib = L
     return L
 
@@ -147,6 +149,12 @@ def pc_chunk_query_scores(shape, q, k, tok_score, chunk_score, ws, chunk_lens=No
     _check(lib().pc_chunk_query_scores(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(chunk_lens),
                                        _ptr(tok_score),
                                        _ptr(chunk_score), p, n, _stream()), "pc_chunk_query_scores")
+
+
+def pc_chunk_self_information(logits, targets, n_chunks, n_tokens, vocab, negate, token_nll, info):
+    _check(lib().pc_chunk_self_information(_ptr(logits), _ptr(targets), n_chunks, n_tokens, vocab,
+                                           int(bool(negate)), _ptr(token_nll), _ptr(info),
+                                           _stream()), "pc_chunk_self_information")
 
 
 def pc_select_chunks_topk(chunk_score, n, k, out_idx, out_score=None):

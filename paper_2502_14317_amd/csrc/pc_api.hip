@@ -60,7 +60,8 @@ extern "C" const char* pc_kernel_name(int id) {
   static const char* names[PC_KERNEL_COUNT] = {
       "rope_table_kernel", "kv_prepass_kernel", "flash_fwd_kernel", "scores_kernel<1>",
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
-      "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel"};
+      "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
+      "self_info_rows_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -190,6 +191,16 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
   rc = pc_launch_rope_table(table, L, s->head_dim, s->rope_base, st);
   if (rc != PC_OK) return rc;
   return pc_launch_scores(s, q, k, chunk_lens, table, ml, tok_score, chunk_score, st);
+}
+
+extern "C" int pc_chunk_self_information(const void* logits, const int32_t* targets, int32_t n_chunks,
+                                         int32_t n_tokens, int32_t vocab, int32_t negate,
+                                         float* token_nll, float* info, void* stream) {
+  if (!logits || !targets || !token_nll || !info) return PC_ERR_NULL;
+  if (n_chunks < 1 || n_tokens < 1 || vocab < 8 || vocab > (1 << 24) || vocab % 8 != 0) return PC_ERR_SHAPE;
+  if ((long long)n_chunks * n_tokens > 0x7fffffffLL || !pc_aligned(logits, 16)) return PC_ERR_SHAPE;
+  return pc_launch_self_info(logits, targets, n_chunks, n_tokens, vocab, negate, token_nll, info,
+                             (hipStream_t)stream);
 }
 
 extern "C" int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_t k,

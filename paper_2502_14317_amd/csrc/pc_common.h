@@ -125,6 +125,9 @@ struct PcFlashArgs {
 #define PC_NO_CAUSAL (1 << 29)
 int pc_launch_flash(const PcFlashArgs& a, hipStream_t st);
 
+int pc_launch_self_info(const void* logits, const int32_t* targets, int n_chunks, int n_tokens,
+                        int vocab, int negate, float* token_nll, float* info, hipStream_t st);
+
 size_t pc_scores_ml_bytes(const pc_shape* s);
 int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
                      void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st);

@@ -171,3 +171,27 @@ def test_full_decode_and_gather_sampled():
         ro, rl = oracle.global_attention_concat(qf, kf, vf)
         assert_close(dev_bf16_to_f64(out[b, :, gk * G:(gk + 1) * G]), ro, O_ATOL, O_RTOL, f"decode out[b={b},g={gk}]")
         assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"decode lse[b={b},g={gk}]")
+
+
+def test_self_information_full_size_sampled():
+    """Eq. 3 reducer at the 128K workload's size (16 x 512 rows of 128256 bf16 logits, 2.1 GB):
+    sampled rows against the oracle, and every chunk's total against the fp64 sum of the GPU's own
+    per-token terms."""
+    print("self-information 16 x 512 x 128256", flush=True)
+    C, T, V = 16, 512, 128256
+    g = torch.Generator(device="cuda").manual_seed(5)
+    logits = torch.empty((C, T, V), dtype=torch.bfloat16, device="cuda")
+    for c in range(C):
+        logits[c] = (torch.randn((T, V), generator=g, device="cuda") * 2.0).to(torch.bfloat16)
+    targets = torch.randint(0, V, (T,), generator=g, device="cuda", dtype=torch.int32)
+    nll = torch.empty((C, T), dtype=torch.float32, device="cuda")
+    info = torch.empty((C,), dtype=torch.float32, device="cuda")
+    pc.pc_chunk_self_information(logits, targets, C, T, V, False, nll, info)
+    torch.cuda.synchronize()
+    nll_h, info_h, tg = nll.cpu().numpy().astype(np.float64), info.cpu().numpy(), targets.cpu().numpy()
+    r = np.random.default_rng(71)
+    for c, t in zip(r.integers(0, C, 24), r.integers(0, T, 24)):
+        row = logits[c, t].float().cpu().numpy().astype(np.float64)[None, None, :]
+        _, ref = oracle.chunk_self_information(row, [tg[t]])
+        assert abs(nll_h[c, t] - ref[0, 0]) <= 2e-5 + 2e-6 * abs(ref[0, 0]), (c, t, nll_h[c, t], ref[0, 0])
+    np.testing.assert_allclose(info_h, nll_h.sum(axis=1), rtol=2e-6)
