@@ -19,6 +19,8 @@ and follows the paper's order of steps:
                         exceeds lambda (R_H), keep the best of the rest
   gather_kv             Eq. 7: compressed KV cache K_r = K_x[.], V_r = V_x[.]
   global_attention_*    Eq. 9-11: the query attends over [K^1 .. K^C, K^q]
+  decode_steps          decoding stage: one new token per step attends over the compressed
+                        segments, the query block and the tokens generated so far
 
 Readings of the paper taken here (the paper is silent or ambiguous on each):
   * Eq. 1 carries a causal mask (decoder LLMs): key j is visible to row r iff j <= r.
@@ -301,6 +303,39 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
             P, l_p[S, :, h] = _masked_softmax_rows((q_rot[:, h] @ k_self[:, g].T) * scale, causal)
             o_p[S, :, h] = P @ v_self[:, g]
     return lse_merge(o_p, l_p)
+
+
+# --------------------------------------------------------------------------- decoding stage
+def decode_steps(q_new, k_new, v_new, kc, vc, k_tail, v_tail, pos0, rope_base, seg_len=None,
+                 scale=None):
+    """Token-by-token generation after the prefill (sec. 3.1, decoding stage of Eq. 9-11).
+
+    Step t: the new token's q and k [H, D] are rotated at position pos0 + t (positions continue
+    behind the query block), its k and v are appended to the tail (k_tail, v_tail [n0, H_kv, D]:
+    the query block's rotated keys / values), and the token attends, in one softmax, over the
+    compressed segments kc, vc [S, H_kv, k_t, D] (seg_len rows each) and the whole tail, itself
+    included.  q_new [T, H_q, D], k_new, v_new [T, H_kv, D] before RoPE.  Returns o [T, H_q, D],
+    lse [T, H_q] and the final tail (k, v)."""
+    T = q_new.shape[0]
+    Hkv = k_new.shape[1]
+    kt = kc.shape[2]
+    o = np.zeros_like(np.asarray(q_new, dtype=np.float64))
+    lse = np.zeros(o.shape[:2])
+    k_tail, v_tail = np.array(k_tail, dtype=np.float64), np.array(v_tail, dtype=np.float64)
+    for t in range(T):
+        q_rot = rope(q_new[t:t + 1], [pos0 + t], rope_base)
+        k_rot = rope(k_new[t:t + 1], [pos0 + t], rope_base)
+        k_tail = np.concatenate([k_tail, k_rot], axis=0)
+        v_tail = np.concatenate([v_tail, np.asarray(v_new[t:t + 1], dtype=np.float64)], axis=0)
+        n = k_tail.shape[0]
+        pad = max(kt, n)
+        kc_t = np.zeros((kc.shape[0] + 1, Hkv, pad, kc.shape[3])); vc_t = np.zeros_like(kc_t)
+        kc_t[:-1, :, :kt] = kc; vc_t[:-1, :, :kt] = vc
+        kc_t[-1, :, :n] = k_tail.transpose(1, 0, 2); vc_t[-1, :, :n] = v_tail.transpose(1, 0, 2)
+        sl = np.full(kc.shape[0], kt) if seg_len is None else np.asarray(seg_len)
+        o[t:t + 1], lse[t:t + 1] = global_attention_concat(q_rot, kc_t, vc_t, seg_len=np.append(sl, n),
+                                                          scale=scale)
+    return o, lse, (k_tail, v_tail)
 
 
 # --------------------------------------------------------------------------- the whole layer

@@ -564,6 +564,29 @@ def test_self_information_ranks_planted_chunks_first():
     assert np.array_equal(lb, lb2) and np.array_equal(targets, t2)
 
 
+# ------------------------------------------------------------------ decoding stage
+def test_incremental_decode_equals_causal_attention_in_one_shot():
+    """Generating token by token with a growing tail is the textbook KV-cache identity: step t
+    equals row t of one causal attention whose self segment holds all generated tokens, with the
+    compressed segments and the query block fully visible."""
+    r = _rng(61)
+    T, Hq, Hkv, D, S, kt, n0, base, p0 = 5, 4, 2, 8, 2, 6, 3, 1e4, 40
+    qn = r.standard_normal((T, Hq, D)); kn = r.standard_normal((T, Hkv, D)); vn = r.standard_normal((T, Hkv, D))
+    kc = r.standard_normal((S, Hkv, kt, D)); vc = r.standard_normal((S, Hkv, kt, D))
+    k0 = r.standard_normal((n0, Hkv, D)); v0 = r.standard_normal((n0, Hkv, D))
+    sl = np.array([6, 4])
+    o, lse, (kt_, vt_) = oracle.decode_steps(qn, kn, vn, kc, vc, k0, v0, p0, base, seg_len=sl)
+    pos = p0 + np.arange(T)
+    q_rot, k_rot = oracle.rope(qn, pos, base), oracle.rope(kn, pos, base)
+    kc2 = np.zeros((S + 1, Hkv, kt, D)); vc2 = np.zeros_like(kc2)
+    kc2[:S] = kc; vc2[:S] = vc
+    kc2[S, :, :n0] = k0.transpose(1, 0, 2); vc2[S, :, :n0] = v0.transpose(1, 0, 2)
+    o2, lse2 = oracle.global_attention_concat(q_rot, kc2, vc2, k_rot, vn, seg_len=np.append(sl, n0))
+    np.testing.assert_allclose(o, o2, atol=1e-13); np.testing.assert_allclose(lse, lse2, atol=1e-13)
+    np.testing.assert_array_equal(kt_[:n0], k0); np.testing.assert_allclose(kt_[n0:], k_rot, atol=0)
+    assert kt_.shape[0] == n0 + T and np.array_equal(vt_[n0:], vn)
+
+
 def test_workload_plant_makes_relevant_chunks_win():
     """The unit-variance tiny config: the planted chunk must be the top chunk of the oracle."""
     cfg = CFG0U
