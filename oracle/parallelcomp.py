@@ -307,7 +307,7 @@ def global_attention_merged(q_rot, kc, vc, k_self=None, v_self=None, seg_len=Non
 
 # --------------------------------------------------------------------------- decoding stage
 def decode_steps(q_new, k_new, v_new, kc, vc, k_tail, v_tail, pos0, rope_base, seg_len=None,
-                 scale=None):
+                 scale=None, store=None):
     """Token-by-token generation after the prefill (sec. 3.1, decoding stage of Eq. 9-11).
 
     Step t: the new token's q and k [H, D] are rotated at position pos0 + t (positions continue
@@ -315,7 +315,10 @@ def decode_steps(q_new, k_new, v_new, kc, vc, k_tail, v_tail, pos0, rope_base, s
     the query block's rotated keys / values), and the token attends, in one softmax, over the
     compressed segments kc, vc [S, H_kv, k_t, D] (seg_len rows each) and the whole tail, itself
     included.  q_new [T, H_q, D], k_new, v_new [T, H_kv, D] before RoPE.  Returns o [T, H_q, D],
-    lse [T, H_q] and the final tail (k, v)."""
+    lse [T, H_q] and the final tail (k, v).
+    store: the cache's storage format, a function applied once to the rotated key row before it
+    enters the tail (the paper does not state a precision; a 16-bit cache rounds the rotated key
+    there, as the prefill's cache does).  Default: the row is kept in float64."""
     T = q_new.shape[0]
     Hkv = k_new.shape[1]
     kt = kc.shape[2]
@@ -325,6 +328,8 @@ def decode_steps(q_new, k_new, v_new, kc, vc, k_tail, v_tail, pos0, rope_base, s
     for t in range(T):
         q_rot = rope(q_new[t:t + 1], [pos0 + t], rope_base)
         k_rot = rope(k_new[t:t + 1], [pos0 + t], rope_base)
+        if store is not None:
+            k_rot = np.asarray(store(k_rot), dtype=np.float64)
         k_tail = np.concatenate([k_tail, k_rot], axis=0)
         v_tail = np.concatenate([v_tail, np.asarray(v_new[t:t + 1], dtype=np.float64)], axis=0)
         n = k_tail.shape[0]

@@ -585,6 +585,14 @@ def test_incremental_decode_equals_causal_attention_in_one_shot():
     np.testing.assert_allclose(o, o2, atol=1e-13); np.testing.assert_allclose(lse, lse2, atol=1e-13)
     np.testing.assert_array_equal(kt_[:n0], k0); np.testing.assert_allclose(kt_[n0:], k_rot, atol=0)
     assert kt_.shape[0] == n0 + T and np.array_equal(vt_[n0:], vn)
+    # a cache storage format is applied to the rotated key once, on entry, and to nothing else
+    rnd = lambda x: bf16_bits_to_f64(f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
+    o3, lse3, (kt3, vt3) = oracle.decode_steps(qn, kn, vn, kc, vc, k0, v0, p0, base, seg_len=sl, store=rnd)
+    np.testing.assert_array_equal(kt3[n0:], rnd(k_rot)); np.testing.assert_array_equal(kt3[:n0], k0)
+    np.testing.assert_array_equal(vt3, vt_)
+    o4, lse4 = oracle.global_attention_concat(q_rot, kc2, vc2, rnd(k_rot), vn, seg_len=np.append(sl, n0))
+    np.testing.assert_allclose(o3, o4, atol=1e-13); np.testing.assert_allclose(lse3, lse4, atol=1e-13)
+    assert np.abs(o3 - o).max() > 1e-6                      # and it is not a no-op
 
 
 def test_workload_plant_makes_relevant_chunks_win():
