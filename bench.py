@@ -215,6 +215,48 @@ def cpu_baseline(cfg, q, k, v, n_rows_sample=768, n_grows_sample=128):
                        f"est. {total:.1f} s per step")}
 
 
+def bench_decode_steps(pc, torch, cfg, g, n_tokens=64):
+    """The decoding stage as a loop on the decode config: every step appends the new token's
+    rotated K / V to the growing tail (query block of 512 rows first) and attends over the 32
+    compressed segments plus the tail.  Segment lengths stay on the device: no host sync inside
+    the loop."""
+    from paper_2502_14317_amd.layer import DecodeCache
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf = torch.bfloat16
+    cache = DecodeCache(B, S, kt, Hq, Hkv, D, 5.0e5)
+    for b in range(B):
+        cache.kc[b] = (torch.randn(cache.kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+        cache.vc[b] = (torch.randn(cache.kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    cache.seg_len[:, :S].fill_(kt)
+    cache.seg_len[:, S].fill_(512)
+    mk = lambda h: (torch.randn((n_tokens + 4, B, 1, h, D), generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    qn, kn, vn = mk(Hq), mk(Hkv), mk(Hkv)
+    for t in range(4):
+        cache.step(qn[t], kn[t], vn[t], 8192 + t)
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    t0 = time.perf_counter()
+    for t in range(4, 4 + n_tokens):
+        cache.step(qn[t], kn[t], vn[t], 8192 + t)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / n_tokens
+    pc.pc_profile_end()
+    per = {}
+    for name, ms in pc.pc_profile_records():
+        per.setdefault(name, []).append(ms)
+    k_avg = sum(per["decode_attn_kernel"]) / len(per["decode_attn_kernel"]) * 1e-3
+    kv_bytes = 2.0 * B * Hkv * D * 2 * (S * kt + 512 + 4 + n_tokens / 2.0)
+    res = {"workload": f"{cfg.name} + growing tail (512-row query block + {n_tokens} generated tokens)",
+           "ms_per_token_step": dt * 1e3, "tokens_per_s_per_layer": B / dt,
+           "kernel_ms_per_step": {n: round(sum(v) / n_tokens, 4) for n, v in per.items()},
+           "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": kv_bytes / k_avg / 1e9,
+                        "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": kv_bytes / k_avg / PEAK_HBM_BYTES,
+                        "kernel_ms": k_avg * 1e3, "traffic": None}}
+    del cache
+    torch.cuda.empty_cache()
+    return res
+
+
 def bench_secondary(pc, torch, steps, warmup):
     """HBM-bound kernels on the decode config: split-KV attention + merge, and the KV gather."""
     from workloads import CFG4
@@ -255,6 +297,7 @@ def bench_secondary(pc, torch, steps, warmup):
                      "traffic": MEASURED_TRAFFIC.get(("decode_attn_kernel", cfg.name))}}
     del kc, vc
     torch.cuda.empty_cache()
+    out["decode_steps"] = bench_decode_steps(pc, torch, cfg, g)
     # gather: source [B, S, rows, H_kv, D], sorted random k_t-subsets of the rows
     R = cfg.src_rows
     ks = torch.empty((B, S, R, Hkv, D), dtype=bf, device="cuda")

@@ -183,6 +183,25 @@ size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_se
                                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                         int32_t has_self);
 
+/* ---- decoding stage (Eq. 9-11 token by token) ------------------------------------------------
+ * Append the keys / values of n_new newly generated tokens to segment `seg` of the compacted
+ * cache, behind the seg_len[b, seg] rows it holds (the growing tail: query block + generated
+ * tokens), and add n_new to seg_len[b, seg] on the device.  pc_parallel_attn with that seg_len is
+ * then one decode step over [compressed segments ; tail], the new token included.
+ *   k_new, v_new [B, n_new, H_kv, D] bf16; k_new before RoPE if pos0 >= 0 (rotated here at
+ *     positions pos0 + t, which continue behind the query block), already rotated if pos0 < 0
+ *   kc, vc [B, n_seg, H_kv, k_t, D] bf16 in/out;  seg_len [B, n_seg] int32 (device) in/out, or
+ *     [B, n_seg, H_kv] when seg_len_per_head != 0 (the layout pc_parallel_attn takes after
+ *     pc_select_tokens_calibrated; every head of the tail then advances by the same n_new)
+ * Rows that do not fit (seg_len + n_new > k_t) are dropped and seg_len saturates at k_t: size the
+ * tail segment for the longest generation.  Calls on one stream are ordered; no workspace.
+ * Errors: PC_ERR_NULL, PC_ERR_SHAPE (seg outside [0, n_seg), head_dim not 64 / 128, rope_base
+ * <= 1 with pos0 >= 0), PC_ERR_HIP.  batch == 0 or n_new == 0 is a no-op. */
+int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_new, int32_t n_seg,
+                 int32_t seg, int32_t k_t, int32_t n_kv_heads, int32_t head_dim, int32_t pos0,
+                 float rope_base, void* kc, void* vc, int32_t* seg_len, int32_t seg_len_per_head,
+                 void* stream);
+
 /* ---- per-kernel timing (measurement aid; off by default) ------------------------------------
  * While enabled, every kernel the library launches is bracketed by a pair of HIP events recorded
  * on the stream of the call.  pc_profile_begin resets the record list (at most 4096 records are
@@ -193,7 +212,8 @@ typedef enum pc_kernel_id {
   PC_KERNEL_ROPE_TABLE = 0, PC_KERNEL_KV_PREPASS = 1, PC_KERNEL_FLASH = 2, PC_KERNEL_SCORES_P1 = 3,
   PC_KERNEL_SCORES_P2 = 4, PC_KERNEL_CHUNK_SCORE = 5, PC_KERNEL_SELECT_CHUNKS = 6,
   PC_KERNEL_SELECT_TOKENS = 7, PC_KERNEL_GATHER = 8, PC_KERNEL_ROPE_Q = 9, PC_KERNEL_DECODE = 10,
-  PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_COUNT = 13
+  PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_KV_APPEND = 13,
+  PC_KERNEL_COUNT = 14
 } pc_kernel_id;
 int         pc_profile_begin(void);
 int         pc_profile_end(void);

@@ -21,7 +21,7 @@ SYMBOLS = [
     "pc_chunk_query_scores_workspace_bytes", "pc_select_chunks_topk", "pc_select_tokens_topk",
     "pc_select_tokens_calibrated", "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
-    "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information",
+    "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
 ]
 
 
@@ -87,6 +87,8 @@ def lib():
     L.pc_mfma_ceiling.restype = c_int
     L.pc_chunk_self_information.argtypes = [P, P, c_int32, c_int32, c_int32, c_int32, P, P, P]
     L.pc_chunk_self_information.restype = c_int
+    L.pc_kv_append.argtypes = [P, P] + [c_int32] * 8 + [c_float, P, P, P, c_int32, P]
+    L.pc_kv_append.restype = c_int
     _lib = L
     return L
 
@@ -193,6 +195,13 @@ def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t,
                                   _ptr(v_self), batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
                                   head_dim, q_pos0, rope_base, softmax_scale, _ptr(out),
                                   _ptr(lse_out), p, n, _stream()), "pc_parallel_attn")
+
+
+def pc_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_dim, pos0, rope_base,
+                 kc, vc, seg_len, seg_len_per_head=0):
+    _check(lib().pc_kv_append(_ptr(k_new), _ptr(v_new), batch, n_new, n_seg, seg, k_t, n_kv_heads,
+                              head_dim, pos0, rope_base, _ptr(kc), _ptr(vc), _ptr(seg_len),
+                              seg_len_per_head, _stream()), "pc_kv_append")
 
 
 def pc_profile_begin():

@@ -338,6 +338,63 @@ int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int 
   return PC_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Decoding stage: append the K / V rows of newly generated tokens to one segment of the
+// compacted cache (the growing tail behind the query block).  One workgroup per sequence: it
+// reads the segment's length(s), writes the rows behind them (K rotated at pos0 + t when
+// pos0 >= 0, fp64 angles) and, after a barrier that orders every read of a length before its
+// update, stores the new length(s), all on the device, so a decode loop needs no host round
+// trip.  Rows that would not fit the segment's capacity are dropped.
+__global__ __launch_bounds__(256) void kv_append_kernel(
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, int n_new, int n_seg,
+    int seg, int k_t, int n_kv_heads, int D, int pos0, double log_base, uint16_t* __restrict__ kc,
+    uint16_t* __restrict__ vc, int32_t* __restrict__ seg_len, int per_head) {
+  const int b = blockIdx.x;
+  const int half = D / 2;
+  const long long len_base = per_head ? ((long long)b * n_seg + seg) * n_kv_heads
+                                      : (long long)b * n_seg + seg;
+  const long long items = (long long)n_new * n_kv_heads * half;
+  for (long long it = threadIdx.x; it < items; it += blockDim.x) {
+    const int i = (int)(it % half);
+    const int g = (int)((it / half) % n_kv_heads);
+    const int t = (int)(it / ((long long)half * n_kv_heads));
+    const int len = min(max(seg_len[len_base + (per_head ? g : 0)], 0), k_t);
+    if (len + t >= k_t) continue;                          // no room left in this head's segment
+    const long long src = (((long long)b * n_new + t) * n_kv_heads + g) * D;
+    const long long dst = ((((long long)b * n_seg + seg) * n_kv_heads + g) * k_t + len + t) * D;
+    const uint16_t a1 = k_new[src + i], a2 = k_new[src + i + half];
+    if (pos0 >= 0) {
+      const double theta = exp(-2.0 * (double)i / (double)D * log_base);
+      double sn, cs;
+      sincos((double)(pos0 + t) * theta, &sn, &cs);
+      const float x1 = bf16_bits_to_f32(a1), x2 = bf16_bits_to_f32(a2);
+      kc[dst + i] = (uint16_t)f32_to_bf16_bits((float)(x1 * cs - x2 * sn));
+      kc[dst + i + half] = (uint16_t)f32_to_bf16_bits((float)(x2 * cs + x1 * sn));
+    } else {
+      kc[dst + i] = a1; kc[dst + i + half] = a2;
+    }
+    vc[dst + i] = v_new[src + i]; vc[dst + i + half] = v_new[src + i + half];
+  }
+  __syncthreads();                                         // every length has been read
+  const int n_len = per_head ? n_kv_heads : 1;
+  for (int g = threadIdx.x; g < n_len; g += blockDim.x) {
+    const int len = min(max(seg_len[len_base + g], 0), k_t);
+    seg_len[len_base + g] = len + min(n_new, k_t - len);
+  }
+}
+
+int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_new, int n_seg,
+                        int seg, int k_t, int n_kv_heads, int head_dim, int pos0, float base,
+                        void* kc, void* vc, int32_t* seg_len, int seg_len_per_head, hipStream_t st) {
+  PcProfScope prof(PC_KERNEL_KV_APPEND, st);
+  hipLaunchKernelGGL(kv_append_kernel, dim3(batch), dim3(256), 0, st, (const uint16_t*)k_new,
+                     (const uint16_t*)v_new, n_new, n_seg, seg, k_t, n_kv_heads, head_dim, pos0,
+                     log((double)(pos0 >= 0 ? base : 2.0f)), (uint16_t*)kc, (uint16_t*)vc, seg_len,
+                     seg_len_per_head);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
 template <int D>
 static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStream_t st) {
   const long long blocks = (long long)batch * a.n_kv_heads * a.n_seg * a.n_split;

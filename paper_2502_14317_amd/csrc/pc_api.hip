@@ -61,7 +61,7 @@ extern "C" const char* pc_kernel_name(int id) {
       "rope_table_kernel", "kv_prepass_kernel", "flash_fwd_kernel", "scores_kernel<1>",
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
-      "self_info_rows_kernel"};
+      "self_info_rows_kernel", "kv_append_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -191,6 +191,21 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
   rc = pc_launch_rope_table(table, L, s->head_dim, s->rope_base, st);
   if (rc != PC_OK) return rc;
   return pc_launch_scores(s, q, k, chunk_lens, table, ml, tok_score, chunk_score, st);
+}
+
+extern "C" int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_new,
+                            int32_t n_seg, int32_t seg, int32_t k_t, int32_t n_kv_heads,
+                            int32_t head_dim, int32_t pos0, float rope_base, void* kc, void* vc,
+                            int32_t* seg_len, int32_t seg_len_per_head, void* stream) {
+  if (!k_new || !v_new || !kc || !vc || !seg_len) return PC_ERR_NULL;
+  if (batch < 0 || n_new < 0 || n_seg < 1 || seg < 0 || seg >= n_seg || k_t < 1 || n_kv_heads < 1)
+    return PC_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
+  if (pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
+  if (batch == 0 || n_new == 0) return PC_OK;
+  return pc_launch_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_dim,
+                             pos0, rope_base, kc, vc, seg_len, seg_len_per_head != 0,
+                             (hipStream_t)stream);
 }
 
 extern "C" int pc_chunk_self_information(const void* logits, const int32_t* targets, int32_t n_chunks,

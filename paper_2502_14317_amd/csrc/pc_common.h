@@ -135,6 +135,10 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
                      int pos0, float base, hipStream_t st);
 int pc_decode_keys_per_wg(int k_t);
+int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_new, int n_seg,
+                        int seg, int k_t, int n_kv_heads, int head_dim, int pos0, float base,
+                        void* kc, void* vc, int32_t* seg_len, int seg_len_per_head,
+                        hipStream_t st);
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
                      int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
                      int head_dim, float scale, float* part_o, float* part_lse, int n_parts,

@@ -159,3 +159,50 @@ class StreamingParallelComp:
                            n_seg, self.kt_n, self.Hq, self.Hkv, self.D, self.w, self.rope_base,
                            self.scale, self.global_o, self.global_lse, self.ws)
         return self.global_o
+
+
+class DecodeCache:
+    """The decoding stage (sec. 3.1, Eq. 9-11 token by token): the compressed segments of B
+    sequences plus one tail segment that starts as the query block's keys / values and grows by
+    one row per generated token.  Segment lengths live on the device and are advanced by
+    pc_kv_append, so a run of decode steps is a run of library calls with no host round trip.
+    A step = pc_kv_append (rotate and store the new token's K, V) + pc_parallel_attn (the new
+    token's query over [segments ; tail], itself included)."""
+
+    def __init__(self, batch, n_seg, keep_tokens, n_q_heads, n_kv_heads, head_dim, rope_base,
+                 softmax_scale=0.0, device="cuda"):
+        self.B, self.S, self.kt = batch, n_seg + 1, keep_tokens          # last segment = tail
+        self.Hq, self.Hkv, self.D = n_q_heads, n_kv_heads, head_dim
+        self.rope_base, self.scale = rope_base, softmax_scale
+        bf, i32 = torch.bfloat16, torch.int32
+        self.kc = torch.zeros((batch, self.S, n_kv_heads, keep_tokens, head_dim), dtype=bf, device=device)
+        self.vc = torch.zeros_like(self.kc)
+        self.seg_len = torch.zeros((batch, self.S), dtype=i32, device=device)
+        self.out = torch.empty((batch, 1, n_q_heads, head_dim), dtype=bf, device=device)
+        self.lse = torch.empty((batch, n_q_heads, 1), dtype=torch.float32, device=device)
+        self.ws = B.alloc_workspace(B.pc_parallel_attn_workspace_bytes(
+            batch, 1, self.S, keep_tokens, n_q_heads, n_kv_heads, head_dim, False), device)
+
+    def load(self, kc, vc, seg_len, k_tail, v_tail):
+        """kc, vc [B, n_seg, H_kv, k_t, D] compacted segments (plain copies into the cache),
+        seg_len [B, n_seg] or None (all k_t), k_tail, v_tail [B, n0, H_kv, D] rotated keys /
+        values of the query block (appended through the library as already-rotated rows)."""
+        n = self.S - 1
+        self.kc[:, :n].copy_(kc); self.vc[:, :n].copy_(vc)
+        if seg_len is None:
+            self.seg_len[:, :n].fill_(self.kt)
+        else:
+            self.seg_len[:, :n].copy_(seg_len)
+        self.seg_len[:, n].zero_()
+        B.pc_kv_append(k_tail, v_tail, self.B, k_tail.shape[1], self.S, n, self.kt, self.Hkv, self.D,
+                       -1, self.rope_base, self.kc, self.vc, self.seg_len)
+
+    def step(self, q_new, k_new, v_new, pos):
+        """q_new [B, 1, H_q, D], k_new, v_new [B, 1, H_kv, D] before RoPE; pos = the token's
+        position (continues behind the query block).  Returns out [B, 1, H_q, D]."""
+        B.pc_kv_append(k_new, v_new, self.B, 1, self.S, self.S - 1, self.kt, self.Hkv, self.D, pos,
+                       self.rope_base, self.kc, self.vc, self.seg_len)
+        B.pc_parallel_attn(q_new, self.kc, self.vc, self.seg_len, None, None, self.B, 1, self.S,
+                           self.kt, self.Hq, self.Hkv, self.D, pos, self.rope_base, self.scale,
+                           self.out, self.lse, self.ws)
+        return self.out

@@ -79,6 +79,15 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_parallel_attn(one, one, one, one, 2, None, None, *args, one, None, one, 1 << 30, None) == -2
     bad_args = (1, 1, 2, 64, 8, 3, 128, -1, 1e4, 0.0)
     assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
+    # decoding stage: append to the tail segment
+    ok = (2, 1, 3, 2, 64, 2, 128, 10, 1e4)          # batch, n_new, n_seg, seg, k_t, H_kv, D, pos0, base
+    assert L.pc_kv_append(None, one, *ok, one, one, one, 0, None) == -1
+    assert L.pc_kv_append(one, one, *ok, one, one, None, 0, None) == -1
+    for i, value in ((3, 3), (3, -1), (6, 96), (8, 0.5), (4, 0), (2, 0)):   # seg, seg, D, base, k_t, n_seg
+        bad = list(ok); bad[i] = value
+        assert L.pc_kv_append(one, one, *bad, one, one, one, 0, None) == -2, (i, value)
+    assert L.pc_kv_append(one, one, 2, 0, *ok[2:], one, one, one, 0, None) == 0    # nothing to append
+    assert L.pc_kv_append(one, one, 0, 1, *ok[2:], one, one, one, 0, None) == 0
 
 
 def test_workspace_sizes_are_positive_and_monotone():
