@@ -213,7 +213,7 @@ typedef enum pc_kernel_id {
   PC_KERNEL_SCORES_P2 = 4, PC_KERNEL_CHUNK_SCORE = 5, PC_KERNEL_SELECT_CHUNKS = 6,
   PC_KERNEL_SELECT_TOKENS = 7, PC_KERNEL_GATHER = 8, PC_KERNEL_ROPE_Q = 9, PC_KERNEL_DECODE = 10,
   PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_KV_APPEND = 13,
-  PC_KERNEL_COUNT = 14
+  PC_KERNEL_SCORES_LSE = 14, PC_KERNEL_COUNT = 15
 } pc_kernel_id;
 int         pc_profile_begin(void);
 int         pc_profile_end(void);

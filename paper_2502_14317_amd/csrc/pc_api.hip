@@ -61,7 +61,7 @@ extern "C" const char* pc_kernel_name(int id) {
       "rope_table_kernel", "kv_prepass_kernel", "flash_fwd_kernel", "scores_kernel<1>",
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
-      "self_info_rows_kernel", "kv_append_kernel"};
+      "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 

@@ -354,9 +354,10 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
   // more than 2^8; until then p = exp2(s - m_run) <= 256 and O, l keep their scale.  The P V
   // products of step j - 1 (old reference) are all issued in region 1, so O is rescaled after it.
   // has_pv / has_qk are compile-time: the first step has no previous P V, the last no next K Q^T.
-  // Steps that lie wholly above a wavefront's rows on the diagonal are not skipped: their
-  // logits are masked to -inf, so they add exact zeros (straight-line code keeps the register
-  // allocation of the whole loop tight; the waste is under 3 % of the steps at 8K rows).
+  // Steps that lie wholly above a wavefront's rows on the diagonal: those inside the loop are
+  // not skipped, their logits are masked to -inf and add exact zeros (straight-line code keeps
+  // the register allocation of the loop tight); the ones at the very end (the last period and
+  // the last step) are left out per wavefront, see the end of the main loop.
   constexpr int NM = NB * KS;                      // MFMAs per region (= 2 NB DB)
   constexpr int MAX_SL = NM / 4;                   // slices of region 1 that take the row maxima
   constexpr int NG = 16 * NB + 1;                  // probability groups per step
@@ -547,14 +548,29 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
       step(mask_tag, yes{}, yes{}, no{}, 2 * p + 2, 0, s_buf[0], s_buf[1], p_buf[0], p_buf[1]);
     };
     const int n_plain = min(T - 1, max(0, (J0 - 1) / 2));   // periods whose steps need no mask
+    // Last step with a key visible to any row of this wavefront.  On the diagonal the steps
+    // behind it hold only masked keys: the wavefront keeps the workgroup's barrier count but
+    // leaves their arithmetic out (the tile loads of the last period only repeat tile T - 1).
+    const int j_need = __builtin_amdgcn_readfirstlane(
+        min(row0 + 32 * NB - 1 + a.causal_offset, n_valid - 1) >> 5);
+    const bool skip_last_period = T >= 2 && j_need < 2 * T - 3;
+    const int n_periods = skip_last_period ? T - 2 : T - 1;
     int p = 0;
-    for (; p < n_plain; ++p) period(no_mask{}, p);
-    for (; p < T - 1; ++p) period(with_mask{}, p);
+    for (; p < min(n_plain, n_periods); ++p) period(no_mask{}, p);
+    for (; p < n_periods; ++p) period(with_mask{}, p);
+    if (skip_last_period) {
+      PC_WAIT_VMCNT(0);
+      __syncthreads();                                       // the barrier of period T - 2
+    }
     // ---- last period: step 2T-1 and the trailing P V
     PC_WAIT_VMCNT(0);
     __syncthreads();
-    step(with_mask{}, yes{}, no{}, no{}, 2 * T - 1, 0, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
-    last_pv(p_buf[1]);
+    if (j_need >= 2 * T - 1) {
+      step(with_mask{}, yes{}, no{}, no{}, 2 * T - 1, 0, s_buf[1], s_buf[0], p_buf[1], p_buf[0]);
+      last_pv(p_buf[1]);
+    } else {
+      last_pv(p_buf[0]);                                     // P V of the last step that ran (an even one)
+    }
   }
 
   // ---- epilogue: lane halves hold disjoint key subsets of the same query

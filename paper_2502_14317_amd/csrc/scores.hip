@@ -12,9 +12,10 @@
 // Two passes over the keys, both fully parallel over 256-key blocks:
 //   pass 1  (S^T = K Q^T, a lane owns a voting row)  per-block running max / sum of every
 //           voting row -> workspace [c, g, key block, column] (m, l)
-//   pass 2  (S = Q K^T, a lane owns a key)           combine the blocks' (m, l) into the row
-//           logsumexp, recompute the logits, p = exp2(s - lse) and sum p over the columns
-//           (voting rows x heads of the group) for each key -> tok_score
+//   between the passes a small kernel combines the blocks' (m, l) into the row logsumexp
+//   pass 2  (S = Q K^T, a lane owns a key)           recompute the logits, p = exp2(s - lse)
+//           and sum p over the columns (voting rows x heads of the group) for each key
+//           -> tok_score
 // A third kernel sums tok_score per chunk in a fixed order (deterministic) -> chunk_score.
 #include "pc_common.h"
 #include <math.h>
@@ -31,6 +32,7 @@ struct PcScoreArgs {
   const int32_t* chunk_lens; // [C] context rows per chunk or nullptr (= w)
   const float2* table;     // [L, D/2] (cos, sin)
   float2* ml;              // workspace [C, H_kv, n_kb, n_cols] (max in log2 units, sum)
+  float* lse2;             // workspace [C, H_kv, n_cols] row logsumexp in log2 units
   float* tok_score;        // [C, H_kv, w]
   int L, w, w_obs, n_q_heads, n_kv_heads, n_kb, n_cols;
   float scale_log2;
@@ -62,16 +64,8 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
   const long long ml_base = (((long long)c * a.n_kv_heads + g) * a.n_kb) * a.n_cols;
 
   if (PASS == 2) {
-    for (int col = tid; col < a.n_cols; col += PC_SC_THREADS) {
-      float M = -INFINITY;
-      for (int kb = 0; kb < a.n_kb; ++kb) M = fmaxf(M, a.ml[ml_base + (long long)kb * a.n_cols + col].x);
-      float sum = 0.f;
-      for (int kb = 0; kb < a.n_kb; ++kb) {
-        const float2 v = a.ml[ml_base + (long long)kb * a.n_cols + col];
-        if (v.y > 0.f) sum += v.y * exp2f(v.x - M);
-      }
-      lse2_lds[col] = M + log2f(sum);
-    }
+    const float* lse2 = a.lse2 + ((long long)c * a.n_kv_heads + g) * a.n_cols;
+    for (int col = tid; col < a.n_cols; col += PC_SC_THREADS) lse2_lds[col] = lse2[col];
   }
 
   float tok_acc[PC_SC_KB / PC_SC_TILE][2];
@@ -240,6 +234,35 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
   }
 }
 
+// Row logsumexp (log2 units) of every voting row from the per-key-block (max, sum) of pass 1,
+// combined in block order.  One thread per column; the loads of a batch of blocks are
+// independent, so a thread waits for memory n_kb / 8 times, not n_kb times.
+__global__ __launch_bounds__(128) void scores_lse_kernel(const float2* __restrict__ ml,
+                                                         float* __restrict__ lse2, int n_kb,
+                                                         int n_cols) {
+  const int col = blockIdx.y * 128 + threadIdx.x;
+  if (col >= n_cols) return;
+  const float2* src = ml + (long long)blockIdx.x * n_kb * n_cols + col;
+  float M = -INFINITY;
+  for (int kb0 = 0; kb0 < n_kb; kb0 += 8) {
+    float2 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = src[(long long)min(kb0 + i, n_kb - 1) * n_cols];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) M = fmaxf(M, v[i].x);
+  }
+  float sum = 0.f;
+  for (int kb0 = 0; kb0 < n_kb; kb0 += 8) {
+    float2 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = src[(long long)min(kb0 + i, n_kb - 1) * n_cols];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (kb0 + i < n_kb && v[i].y > 0.f) sum += v[i].y * exp2f(v[i].x - M);
+  }
+  lse2[(long long)blockIdx.x * n_cols + col] = M + log2f(sum);
+}
+
 // chunk_score[c] = sum of tok_score[c, :, :], summed in a fixed order (thread-strided partial
 // sums, then a tree over the workgroup), so the result does not depend on timing.
 __global__ __launch_bounds__(1024) void chunk_score_kernel(const float* __restrict__ tok_score,
@@ -262,7 +285,9 @@ size_t pc_scores_ml_bytes(const pc_shape* s) {
   const int L = s->chunk_len + s->query_len;
   const int n_kb = (L + PC_SC_KB - 1) / PC_SC_KB;
   const int n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
-  return (size_t)s->n_chunks * s->n_kv_heads * n_kb * n_cols * sizeof(float2);
+  // per-block (max, sum) of pass 1, then the combined row logsumexp
+  return (size_t)s->n_chunks * s->n_kv_heads * n_kb * n_cols * sizeof(float2) +
+         (size_t)s->n_chunks * s->n_kv_heads * n_cols * sizeof(float);
 }
 
 int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
@@ -276,11 +301,17 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   a.n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
   const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   a.scale_log2 = scale * PC_SC_LOG2E;
+  a.lse2 = (float*)(a.ml + (size_t)s->n_chunks * s->n_kv_heads * a.n_kb * a.n_cols);
   dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
   {
     PcProfScope prof(PC_KERNEL_SCORES_P1, st);
     if (s->head_dim == 128) hipLaunchKernelGGL((scores_kernel<128, 1>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((scores_kernel<64, 1>), grid, block, 0, st, a);
+  }
+  {
+    PcProfScope prof(PC_KERNEL_SCORES_LSE, st);
+    hipLaunchKernelGGL(scores_lse_kernel, dim3(s->n_chunks * s->n_kv_heads, (a.n_cols + 127) / 128),
+                       dim3(128), 0, st, a.ml, a.lse2, a.n_kb, a.n_cols);
   }
   {
     PcProfScope prof(PC_KERNEL_SCORES_P2, st);
