@@ -46,7 +46,7 @@ __device__ __forceinline__ void split_bf16x2(float x0, float x1, uint32_t& hi, u
 }
 
 template <int D, int PASS>
-__global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
+__global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a) {
   constexpr int KS = D / 16, HALF = D / 2, KSTRIDE = D + 8;
   __shared__ __attribute__((aligned(16))) uint16_t k_hi[PC_SC_TILE * KSTRIDE];
   __shared__ __attribute__((aligned(16))) uint16_t k_lo[PC_SC_TILE * KSTRIDE];
@@ -68,9 +68,9 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
     for (int col = tid; col < a.n_cols; col += PC_SC_THREADS) lse2_lds[col] = lse2[col];
   }
 
-  float tok_acc[PC_SC_KB / PC_SC_TILE][2];
-#pragma unroll
-  for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) tok_acc[t][0] = tok_acc[t][1] = 0.f;
+  // pass 2: every wavefront accumulates its columns' share of the keys' sums in its own LDS row
+  if (PASS == 2)
+    for (int i = lane; i < PC_SC_KB; i += PC_WAVE) tok_part[wave][i] = 0.f;
 
   const int n_rounds = (n_cb + PC_SC_WAVES - 1) / PC_SC_WAVES;
   for (int round = 0; round < n_rounds; ++round) {
@@ -122,24 +122,38 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
       }
     }
 
+    // K tile staging, split in two so that the loads of tile t + 1 are in flight while the
+    // matrix cores work on tile t: fetch (global -> registers), stage (rotate in fp32, split
+    // hi / lo, registers -> LDS)
+    constexpr int ITEMS = PC_SC_TILE * (HALF / 8) / PC_SC_THREADS;     // per thread and tile
+    static_assert(ITEMS >= 1 && PC_SC_TILE * (HALF / 8) % PC_SC_THREADS == 0, "tile / thread mismatch");
+    uint4 pf_x1[ITEMS], pf_x2[ITEMS];
+    float4 pf_cs[ITEMS][4];
+    auto fetch = [&](int key0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) {
-      const int key0 = kblock * PC_SC_KB + t * PC_SC_TILE;
-      if (key0 >= a.L) break;                               // uniform over the workgroup
-      __syncthreads();                                      // previous tile fully consumed
-      // ---- stage 64 keys: rotate in fp32, split hi / lo
-      for (int it = tid; it < PC_SC_TILE * (HALF / 8); it += PC_SC_THREADS) {
+      for (int u = 0; u < ITEMS; ++u) {
+        const int it = tid + u * PC_SC_THREADS;
         const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
         const int row = min(key0 + r, a.L - 1);
         const uint16_t* krow = a.k + (((long long)c * a.L + row) * a.n_kv_heads + g) * D;
-        const uint4 x1 = *(const uint4*)(krow + i0);
-        const uint4 x2 = *(const uint4*)(krow + HALF + i0);
-        const uint32_t aw[4] = {x1.x, x1.y, x1.z, x1.w}, bw[4] = {x2.x, x2.y, x2.z, x2.w};
-        const float2* cs = a.table + (long long)row * HALF + i0;
+        pf_x1[u] = *(const uint4*)(krow + i0);
+        pf_x2[u] = *(const uint4*)(krow + HALF + i0);
+        const float4* cs4 = (const float4*)(a.table + (long long)row * HALF + i0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pf_cs[u][e] = cs4[e];
+      }
+    };
+    auto stage = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int u = 0; u < ITEMS; ++u) {
+        const int it = tid + u * PC_SC_THREADS;
+        const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
+        const uint32_t aw[4] = {pf_x1[u].x, pf_x1[u].y, pf_x1[u].z, pf_x1[u].w};
+        const uint32_t bw[4] = {pf_x2[u].x, pf_x2[u].y, pf_x2[u].z, pf_x2[u].w};
         uint32_t h1[4], l1[4], h2[4], l2[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+          const float2 c0 = make_float2(pf_cs[u][e].x, pf_cs[u][e].y), c1 = make_float2(pf_cs[u][e].z, pf_cs[u][e].w);
           const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
           const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
           split_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y, h1[e], l1[e]);
@@ -150,7 +164,18 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
         *(uint4*)(k_hi + r * KSTRIDE + HALF + i0) = make_uint4(h2[0], h2[1], h2[2], h2[3]);
         *(uint4*)(k_lo + r * KSTRIDE + HALF + i0) = make_uint4(l2[0], l2[1], l2[2], l2[3]);
       }
+    };
+    if (kblock * PC_SC_KB < a.L) fetch(kblock * PC_SC_KB);
+
+    // one loop body (not unrolled): leaves room for the prefetch registers
+#pragma unroll 1
+    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) {
+      const int key0 = kblock * PC_SC_KB + t * PC_SC_TILE;
+      if (key0 >= a.L) break;                               // uniform over the workgroup
+      __syncthreads();                                      // previous tile fully consumed
+      stage();
       __syncthreads();
+      if (t + 1 < PC_SC_KB / PC_SC_TILE && key0 + PC_SC_TILE < a.L) fetch(key0 + PC_SC_TILE);
       if (!active) continue;
 
 #pragma unroll
@@ -198,7 +223,8 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
             const float p = __builtin_amdgcn_exp2f(s[r] * a.scale_log2 - lse_r[r]);
             sum += (key <= qrow_r[r]) ? p : 0.f;
           }
-          tok_acc[t][kb] += sum;
+          sum += __shfl_xor(sum, 32);
+          if (hf == 0) tok_part[wave][t * PC_SC_TILE + 32 * kb + n] += sum;
         }
       }
     }
@@ -216,13 +242,6 @@ __global__ __launch_bounds__(PC_SC_THREADS) void scores_kernel(PcScoreArgs a) {
   }
 
   if (PASS == 2) {
-#pragma unroll
-    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const float x = tok_acc[t][kb] + __shfl_xor(tok_acc[t][kb], 32);
-        if (hf == 0) tok_part[wave][t * PC_SC_TILE + 32 * kb + n] = x;
-      }
     __syncthreads();
     const int key = kblock * PC_SC_KB + tid;
     if (key < a.w) {
