@@ -21,6 +21,11 @@ and follows the paper's order of steps:
   global_attention_*    Eq. 9-11: the query attends over [K^1 .. K^C, K^q]
   decode_steps          decoding stage: one new token per step attends over the compressed
                         segments, the query block and the tokens generated so far
+  fp8_e4m3_*, quantize_kv_fp8, dequantize_kv_fp8
+                        an 8-bit storage format for the compressed cache of the decoding stage
+                        (not in the paper, which leaves the cache precision open): the
+                        published OCP 8-bit float E4M3 encoding with one scale per (segment,
+                        KV head); attention then runs on the dequantised values unchanged
 
 Readings of the paper taken here (the paper is silent or ambiguous on each):
   * Eq. 1 carries a causal mask (decoder LLMs): key j is visible to row r iff j <= r.
@@ -46,6 +51,12 @@ Readings of the paper taken here (the paper is silent or ambiguous on each):
     cumulative score is strictly above lambda; lambda is never given (a parameter).  Combined
     with compression, R_H is evicted first and the top-k of the remaining tokens is kept, so a
     head keeps min(k, w - |R_H|) tokens.  A NaN score is not above lambda.
+
+  * 8-bit cache (extension, the paper has none): scale = amax / 448 per (segment, KV head)
+    over the valid rows, in float32 (1 if amax = 0); code = E4M3(float32(x) / scale), round to
+    nearest, ties to the even code, saturating at +-448; rows behind seg_len get code 0.  The
+    division and the rounding decide an integer, so both are taken in float32 on both sides.
+    PARITY UNPINNED against the paper (it has no such format); pinned to the format's definition.
 
 Pins (tests/test_oracle_pins.py): brute-force softmax in pure Python loops; closed forms
 (K = 0, V = 1, position 0, norm preservation, shift invariance); a library attention routine
@@ -341,6 +352,65 @@ def decode_steps(q_new, k_new, v_new, kc, vc, k_tail, v_tail, pos0, rope_base, s
         o[t:t + 1], lse[t:t + 1] = global_attention_concat(q_rot, kc_t, vc_t, seg_len=np.append(sl, n),
                                                           scale=scale)
     return o, lse, (k_tail, v_tail)
+
+
+# --------------------------------------------------------------------------- 8-bit cache
+def fp8_e4m3_decode(codes):
+    """OCP 8-bit float E4M3 (finite-only variant): 1 sign, 4 exponent (bias 7), 3 mantissa bits.
+    Exponent field 0 is subnormal (m / 8 * 2^-6); exponent 15 with mantissa 7 is NaN; there are
+    no infinities, the largest magnitude is 1.75 * 2^8 = 448.  uint8 -> float64."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = (c & 0x7).astype(np.float64)
+    val = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7.0))
+    val = np.where((e == 15) & ((c & 0x7) == 7), np.nan, val)
+    return sign * val
+
+
+def fp8_e4m3_encode(x):
+    """Nearest E4M3 code of every finite float32 x: the representable value closest to x, the
+    one with the even code on a tie, +-448 beyond the range (saturating); the sign of x is
+    kept (-0.0 -> 0x80).  Written as the definition: a search over all 127 finite magnitudes."""
+    x = np.asarray(x, dtype=np.float32)
+    mags = fp8_e4m3_decode(np.arange(0x7F, dtype=np.uint8))            # codes 0x00..0x7E ascending
+    a = np.abs(x.astype(np.float64))
+    hi = np.searchsorted(mags, a, side="left").clip(1, 0x7E)            # first magnitude >= |x|
+    lo = hi - 1
+    d_lo, d_hi = a - mags[lo], mags[hi] - a
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(a >= mags[0x7E], 0x7E, code)
+    return (code | np.where(np.signbit(x), 0x80, 0)).astype(np.uint8)
+
+
+def quantize_kv_fp8(kc, vc, seg_len=None):
+    """kc, vc [S, H_kv, k_t, D] (values exactly representable in float32) -> codes uint8 of the
+    same shape and scales float32 [S, H_kv] for each: scale = max |x| over the segment's valid
+    rows / 448 (1 where that maximum is 0), code = E4M3(float32(x) / scale) in float32
+    arithmetic; rows behind seg_len ([S] or [S, H_kv]) get code 0."""
+    S, Hkv, kt, D = kc.shape
+    seg_len = _seg_len_per_head(seg_len, S, Hkv, kt)
+    out = []
+    for x in (kc, vc):
+        x32 = np.asarray(x, dtype=np.float32)
+        codes = np.zeros(x32.shape, dtype=np.uint8)
+        scale = np.ones((S, Hkv), dtype=np.float32)
+        for s_ in range(S):
+            for g in range(Hkv):
+                n = int(seg_len[s_, g])
+                if n == 0:
+                    continue
+                amax = np.abs(x32[s_, g, :n]).max()
+                if amax > 0:
+                    scale[s_, g] = amax / np.float32(448.0)
+                codes[s_, g, :n] = fp8_e4m3_encode(x32[s_, g, :n] / scale[s_, g])
+        out += [codes, scale]
+    return tuple(out)            # k_codes, k_scale, v_codes, v_scale
+
+
+def dequantize_kv_fp8(codes, scale):
+    """codes uint8 [S, H_kv, k_t, D], scale [S, H_kv] -> float64 values code * scale (exact)."""
+    return fp8_e4m3_decode(codes) * np.asarray(scale, dtype=np.float64)[:, :, None, None]
 
 
 # --------------------------------------------------------------------------- the whole layer

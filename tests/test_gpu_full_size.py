@@ -173,6 +173,50 @@ def test_full_decode_and_gather_sampled():
         assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"decode lse[b={b},g={gk}]")
 
 
+def test_full_decode_steps_sampled():
+    """The decoding stage at the decode config's size: 16 sequences x (32 compressed segments +
+    a tail that starts as a 512-row query block), three generated tokens; sampled (sequence, KV
+    group) pairs of every step against the oracle's decode_steps."""
+    from paper_2502_14317_amd.layer import DecodeCache
+    from workloads import f32_to_bf16_bits, bf16_bits_to_f64
+    cfg = CFG4
+    _say(f"decode steps {cfg.name} + tail")
+    g = torch.Generator(device="cuda").manual_seed(6)
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf, n0, T, base, pos0 = torch.bfloat16, 512, 3, 5.0e5, 8192
+    cache = DecodeCache(B, S, kt, Hq, Hkv, D, base)
+    kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(B):
+        kc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
+        vc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
+    k0 = torch.randn((B, n0, Hkv, D), generator=g, device="cuda").to(bf)
+    v0 = torch.randn((B, n0, Hkv, D), generator=g, device="cuda").to(bf)
+    qn = torch.randn((T, B, 1, Hq, D), generator=g, device="cuda").to(bf)
+    kn = torch.randn((T, B, 1, Hkv, D), generator=g, device="cuda").to(bf)
+    vn = torch.randn((T, B, 1, Hkv, D), generator=g, device="cuda").to(bf)
+    cache.load(kc, vc, None, k0, v0)
+    outs, lses = [], []
+    for t in range(T):
+        cache.step(qn[t], kn[t], vn[t], pos0 + t)
+        outs.append(cache.out.clone()); lses.append(cache.lse.clone())
+    torch.cuda.synchronize()
+    assert (cache.seg_len[:, S] == n0 + T).all() and (cache.seg_len[:, :S] == kt).all()
+    G = Hq // Hkv
+    to_bf16 = lambda x: bf16_bits_to_f64(f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
+    for (b, gk) in ((0, 0), (9, 5), (15, 7)):
+        hs = slice(gk * G, (gk + 1) * G)
+        ro, rl, _ = oracle.decode_steps(
+            dev_bf16_to_f64(qn[:, b, 0, hs]), dev_bf16_to_f64(kn[:, b, 0, gk:gk + 1]),
+            dev_bf16_to_f64(vn[:, b, 0, gk:gk + 1]), dev_bf16_to_f64(kc[b, :, gk:gk + 1]),
+            dev_bf16_to_f64(vc[b, :, gk:gk + 1]), dev_bf16_to_f64(k0[b, :, gk:gk + 1]),
+            dev_bf16_to_f64(v0[b, :, gk:gk + 1]), pos0, base, store=to_bf16)
+        go = np.stack([dev_bf16_to_f64(o[b, 0, hs]) for o in outs])
+        gl = np.stack([l[b, hs, 0].cpu().numpy() for l in lses])
+        assert_close(go, ro, O_ATOL, O_RTOL, f"decode steps out[b={b},g={gk}]")
+        assert_close(gl, rl, LSE_ATOL, 1e-3, f"decode steps lse[b={b},g={gk}]")
+
+
 def test_self_information_full_size_sampled():
     """Eq. 3 reducer at the 128K workload's size (16 x 512 rows of 128256 bf16 logits, 2.1 GB):
     sampled rows against the oracle, and every chunk's total against the fp64 sum of the GPU's own

@@ -595,6 +595,82 @@ def test_incremental_decode_equals_causal_attention_in_one_shot():
     assert np.abs(o3 - o).max() > 1e-6                      # and it is not a no-op
 
 
+# ------------------------------------------------------------------ 8-bit cache format
+def test_fp8_e4m3_decode_closed_forms_and_library_view():
+    d = oracle.fp8_e4m3_decode
+    assert d([0x00])[0] == 0.0 and d([0x38])[0] == 1.0 and d([0xC0])[0] == -2.0
+    assert d([0x01])[0] == 2.0 ** -9 and d([0x07])[0] == 7 * 2.0 ** -9       # subnormals
+    assert d([0x08])[0] == 2.0 ** -6 and d([0x7E])[0] == 448.0                # min normal, max
+    assert np.isnan(d([0x7F])[0]) and np.isnan(d([0xFF])[0])
+    assert d([0x39])[0] == 1.125 and d([0x78])[0] == 256.0
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(d(codes), lib)                              # NaNs compare equal here
+    mags = d(np.arange(0x7F, dtype=np.uint8))
+    assert (np.diff(mags) > 0).all()                                          # code order = value order
+
+
+def test_fp8_e4m3_encode_round_trip_ties_saturation_and_library_conversion():
+    enc, dec = oracle.fp8_e4m3_encode, oracle.fp8_e4m3_decode
+    finite = np.array([c for c in range(256) if c & 0x7F != 0x7F], dtype=np.uint8)
+    np.testing.assert_array_equal(enc(dec(finite).astype(np.float32)), finite)     # identity on the grid
+    # ties: the midpoint of two neighbours goes to the even code; brute force in plain Python
+    mags = [float(v) for v in dec(np.arange(0x7F, dtype=np.uint8))]
+    for c in range(0x7E):
+        mid = np.float32((mags[c] + mags[c + 1]) / 2)           # exact: one more mantissa bit
+        assert float(mid) == (mags[c] + mags[c + 1]) / 2
+        want = c if c % 2 == 0 else c + 1
+        assert enc([mid])[0] == want and enc([-mid])[0] == (want | 0x80)
+        below, above = np.nextafter(mid, np.float32(0)), np.nextafter(mid, np.float32(1e9))
+        assert enc([below])[0] == c and enc([above])[0] == c + 1
+    assert enc([1.0625])[0] == 0x38 and enc([1.1875])[0] == 0x3A              # worked ties
+    assert enc([448.0])[0] == 0x7E and enc([463.9])[0] == 0x7E and enc([1e30])[0] == 0x7E
+    assert enc([-1e30])[0] == 0xFE and enc([0.0])[0] == 0x00 and enc([-0.0])[0] == 0x80
+    assert enc([2.0 ** -10])[0] == 0x00 and enc([1.5 * 2.0 ** -10])[0] == 0x01   # half the smallest: tie -> 0
+    # a library conversion (round to nearest even) on every bf16 value inside the range and on
+    # random float32 values
+    allb = bf16_bits_to_f64(np.arange(65536, dtype=np.uint16)).astype(np.float32)
+    allb = allb[np.isfinite(allb) & (np.abs(allb) <= 448)]
+    r = _rng(71)
+    rnd = (r.standard_normal(100000) * r.choice([1e-3, 0.02, 1, 30, 200], 100000)).astype(np.float32).clip(-448, 448)
+    for x in (allb, rnd):
+        lib = torch.from_numpy(x.copy()).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        np.testing.assert_array_equal(enc(x), lib)
+
+
+def test_quantize_kv_fp8_scale_padding_and_error_bound():
+    r = _rng(72)
+    S, H, kt, D = 3, 2, 40, 16
+    kc = bf16_bits_to_f64(f32_to_bf16_bits(r.standard_normal((S, H, kt, D)).astype(np.float32) * 3))
+    vc = bf16_bits_to_f64(f32_to_bf16_bits(r.standard_normal((S, H, kt, D)).astype(np.float32)))
+    kc[1, 1] = 0.0                                              # an all-zero segment
+    kc[0, 0, 35:] = 1e6                                         # huge values in rows nobody may read
+    sl = np.array([[35, 40], [40, 40], [0, 7]])
+    k8, ks, v8, vs = oracle.quantize_kv_fp8(kc, vc, sl)
+    assert k8.dtype == np.uint8 and ks.dtype == np.float32 and ks.shape == (S, H)
+    for s_ in range(S):
+        for g in range(H):
+            n = sl[s_, g]
+            for x, c8, sc in ((kc, k8, ks), (vc, v8, vs)):
+                assert (c8[s_, g, n:] == 0).all()                              # padding rows
+                amax = np.abs(x[s_, g, :n]).max() if n else 0.0
+                want = np.float32(amax) / np.float32(448) if amax > 0 else np.float32(1)
+                assert sc[s_, g] == want
+                if amax > 0:
+                    top = np.unravel_index(np.abs(x[s_, g, :n]).argmax(), (n, D))
+                    assert c8[s_, g][top] & 0x7F == 0x7E                      # the largest element is +-448
+                dq = oracle.dequantize_kv_fp8(c8, sc)[s_, g, :n]
+                err = np.abs(dq - x[s_, g, :n])
+                # half a unit in the last place: 2^-4 relative for normals, scale * 2^-10 below them
+                assert (err <= np.maximum(np.abs(x[s_, g, :n]) * 2.0 ** -4, float(sc[s_, g]) * 2.0 ** -10) * (1 + 1e-6)).all()
+    assert (k8[1, 1] == 0).all() and ks[1, 1] == 1.0
+    # uniform seg_len forms agree
+    a = oracle.quantize_kv_fp8(kc[:, :, :30], vc[:, :, :30])
+    b = oracle.quantize_kv_fp8(kc[:, :, :30], vc[:, :, :30], np.full(S, 30))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+
+
 def test_workload_plant_makes_relevant_chunks_win():
     """The unit-variance tiny config: the planted chunk must be the top chunk of the oracle."""
     cfg = CFG0U
