@@ -257,6 +257,59 @@ def bench_decode_steps(pc, torch, cfg, g, n_tokens=64):
     return res
 
 
+def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
+    """The decode config with the compressed segments in 8 bits (E4M3 + per-segment scales): the
+    quantisation pass (read 2 B, write 1 B per element) and the split-KV attention over half the
+    bytes."""
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf = torch.bfloat16
+    kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(B):
+        kc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+        vc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    k8 = torch.empty(kc.shape, dtype=torch.uint8, device="cuda"); v8 = torch.empty_like(k8)
+    ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); vs = torch.empty_like(ks)
+    q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda") * cfg.entry_scale).to(bf)
+    o = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, 1, S, kt, 0, Hq, Hkv, D))
+    quant = lambda: pc.pc_kv_quantize_fp8(kc, vc, None, B, S, kt, Hkv, D, k8, v8, ks, vs)
+    run = lambda: pc.pc_parallel_attn_fp8(q, k8, v8, ks, vs, None, None, None, None, 0, B, 1, S, kt, Hq, Hkv,
+                                          D, -1, 1.0e4, 0.0, o, None, ws)
+    for _ in range(warmup):
+        quant(); run()
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    for _ in range(3):
+        quant()
+    t0 = time.perf_counter()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    pc.pc_profile_end()
+    per = {}
+    for name, ms in pc.pc_profile_records():
+        per.setdefault(name, []).append(ms)
+    k_avg = sum(per["decode_attn_fp8_kernel"]) / len(per["decode_attn_fp8_kernel"]) * 1e-3
+    q_avg = sum(per["kv_quantize_fp8_kernel"]) / len(per["kv_quantize_fp8_kernel"]) * 1e-3
+    kv_bytes = 2.0 * kc.numel()                       # K and V codes, one byte each
+    q_bytes = 2.0 * kc.numel() * 3                    # quantisation: read 2 B, write 1 B per element
+    res = {"workload": cfg.name + " with 8-bit (E4M3) segments", "ms_per_step": dt * 1e3,
+           "tokens_per_s_per_layer": B / dt,
+           "roofline": {"bound": "hbm", "kernel": "decode_attn_fp8_kernel", "achieved": kv_bytes / k_avg / 1e9,
+                        "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": kv_bytes / k_avg / PEAK_HBM_BYTES,
+                        "kernel_ms": k_avg * 1e3, "traffic": None},
+           "quantize": {"bound": "hbm", "kernel": "kv_quantize_fp8_kernel", "achieved": q_bytes / q_avg / 1e9,
+                        "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": q_bytes / q_avg / PEAK_HBM_BYTES,
+                        "kernel_ms": q_avg * 1e3, "traffic": None}}
+    del kc, vc, k8, v8
+    torch.cuda.empty_cache()
+    return res
+
+
 def bench_secondary(pc, torch, steps, warmup):
     """HBM-bound kernels on the decode config: split-KV attention + merge, and the KV gather."""
     from workloads import CFG4
@@ -298,6 +351,7 @@ def bench_secondary(pc, torch, steps, warmup):
     del kc, vc
     torch.cuda.empty_cache()
     out["decode_steps"] = bench_decode_steps(pc, torch, cfg, g)
+    out["decode_attn_fp8"] = bench_decode_fp8(pc, torch, cfg, g, steps, warmup)
     # gather: source [B, S, rows, H_kv, D], sorted random k_t-subsets of the rows
     R = cfg.src_rows
     ks = torch.empty((B, S, R, Hkv, D), dtype=bf, device="cuda")

@@ -202,6 +202,42 @@ int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_
                  float rope_base, void* kc, void* vc, int32_t* seg_len, int32_t seg_len_per_head,
                  void* stream);
 
+/* ---- 8-bit compressed cache for the decoding stage (extension) -------------------------------
+ * The paper leaves the precision of the cache open (its decoding stage, Eq. 9-11 with one query
+ * row, reads the whole compressed cache per token: the ms/token column of its throughput table).
+ * Storing the compressed segments in 8 bits halves those bytes.  Format: OCP 8-bit float E4M3
+ * (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest magnitude 448, no infinities),
+ * one fp32 scale per (sequence, segment, KV head) for K and one for V:
+ *   scale = max |x| over the segment's valid rows / 448 (1 if that maximum is 0), in fp32
+ *   code  = E4M3(x / scale), fp32 division, round to nearest (ties to the even code), saturating
+ * pc_kv_quantize_fp8:
+ *   kc, vc [B, S, H_kv, k_t, D] bf16 (finite values);  seg_len as in pc_parallel_attn, nullable
+ *   k8, v8 [B, S, H_kv, k_t, D] uint8 out (rows behind seg_len get code 0)
+ *   k_scale, v_scale [B, S, H_kv] fp32 out.   Pointers 16-byte aligned.  No workspace.
+ *   B = 0 or S = 0 is a no-op (pointers are not looked at).
+ * pc_parallel_attn_fp8: pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 8, else
+ * PC_ERR_UNSUPPORTED) over the 8-bit segments plus, optionally, one 16-bit tail segment (the
+ * query block and the generated tokens, grown by pc_kv_append with n_seg = 1):
+ *   k_tail, v_tail [B, 1, H_kv, tail_cap, D] bf16 rotated, tail_len [B] int32 (device); all
+ *     three NULL and tail_cap = 0 for no tail.
+ *   out = softmax over { dequantised segments } U { tail rows } exactly as pc_parallel_attn
+ *   computes it on the dequantised values code * scale (each is exact in bf16).
+ * Other arguments, errors and the workspace rule as pc_parallel_attn. */
+int pc_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
+                       int32_t seg_len_per_head, int32_t batch, int32_t n_seg, int32_t k_t,
+                       int32_t n_kv_heads, int32_t head_dim, void* k8, void* v8, float* k_scale,
+                       float* v_scale, void* stream);
+int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v8, const float* k_scale,
+                         const float* v_scale, const int32_t* seg_len, int32_t seg_len_per_head,
+                         const void* k_tail, const void* v_tail, const int32_t* tail_len,
+                         int32_t tail_cap, int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t q_pos0,
+                         float rope_base, float softmax_scale, void* out, float* lse_out, void* ws,
+                         size_t ws_bytes, void* stream);
+size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
+                                            int32_t tail_cap, int32_t n_q_heads, int32_t n_kv_heads,
+                                            int32_t head_dim);
+
 /* ---- per-kernel timing (measurement aid; off by default) ------------------------------------
  * While enabled, every kernel the library launches is bracketed by a pair of HIP events recorded
  * on the stream of the call.  pc_profile_begin resets the record list (at most 4096 records are
@@ -213,7 +249,8 @@ typedef enum pc_kernel_id {
   PC_KERNEL_SCORES_P2 = 4, PC_KERNEL_CHUNK_SCORE = 5, PC_KERNEL_SELECT_CHUNKS = 6,
   PC_KERNEL_SELECT_TOKENS = 7, PC_KERNEL_GATHER = 8, PC_KERNEL_ROPE_Q = 9, PC_KERNEL_DECODE = 10,
   PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_KV_APPEND = 13,
-  PC_KERNEL_SCORES_LSE = 14, PC_KERNEL_COUNT = 15
+  PC_KERNEL_SCORES_LSE = 14, PC_KERNEL_KV_QUANTIZE = 15, PC_KERNEL_DECODE_FP8 = 16,
+  PC_KERNEL_COUNT = 17
 } pc_kernel_id;
 int         pc_profile_begin(void);
 int         pc_profile_end(void);

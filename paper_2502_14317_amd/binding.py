@@ -22,6 +22,7 @@ SYMBOLS = [
     "pc_select_tokens_calibrated", "pc_gather_kv", "pc_parallel_attn", "pc_parallel_attn_workspace_bytes", "pc_status_string",
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
+    "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
 ]
 
 
@@ -89,6 +90,13 @@ def lib():
     L.pc_chunk_self_information.restype = c_int
     L.pc_kv_append.argtypes = [P, P] + [c_int32] * 8 + [c_float, P, P, P, c_int32, P]
     L.pc_kv_append.restype = c_int
+    L.pc_kv_quantize_fp8.argtypes = [P, P, P] + [c_int32] * 6 + [P, P, P, P, P]
+    L.pc_kv_quantize_fp8.restype = c_int
+    L.pc_parallel_attn_fp8.argtypes = ([P] * 6 + [c_int32] + [P] * 3 + [c_int32] * 9 +
+                                       [c_float, c_float, P, P, P, c_size_t, P])
+    L.pc_parallel_attn_fp8.restype = c_int
+    L.pc_parallel_attn_fp8_workspace_bytes.argtypes = [c_int32] * 8
+    L.pc_parallel_attn_fp8_workspace_bytes.restype = c_size_t
     _lib = L
     return L
 
@@ -202,6 +210,29 @@ def pc_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_d
     _check(lib().pc_kv_append(_ptr(k_new), _ptr(v_new), batch, n_new, n_seg, seg, k_t, n_kv_heads,
                               head_dim, pos0, rope_base, _ptr(kc), _ptr(vc), _ptr(seg_len),
                               seg_len_per_head, _stream()), "pc_kv_append")
+
+
+def pc_kv_quantize_fp8(kc, vc, seg_len, batch, n_seg, k_t, n_kv_heads, head_dim, k8, v8, k_scale,
+                       v_scale, seg_len_per_head=0):
+    _check(lib().pc_kv_quantize_fp8(_ptr(kc), _ptr(vc), _ptr(seg_len), seg_len_per_head, batch, n_seg,
+                                    k_t, n_kv_heads, head_dim, _ptr(k8), _ptr(v8), _ptr(k_scale),
+                                    _ptr(v_scale), _stream()), "pc_kv_quantize_fp8")
+
+
+def pc_parallel_attn_fp8_workspace_bytes(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim):
+    return int(lib().pc_parallel_attn_fp8_workspace_bytes(batch, n_q, n_seg, k_t, tail_cap, n_q_heads,
+                                                          n_kv_heads, head_dim))
+
+
+def pc_parallel_attn_fp8(q, k8, v8, k_scale, v_scale, seg_len, k_tail, v_tail, tail_len, tail_cap, batch,
+                         n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base,
+                         softmax_scale, out, lse_out, ws, seg_len_per_head=0):
+    p, n = _ws(ws)
+    _check(lib().pc_parallel_attn_fp8(_ptr(q), _ptr(k8), _ptr(v8), _ptr(k_scale), _ptr(v_scale),
+                                      _ptr(seg_len), seg_len_per_head, _ptr(k_tail), _ptr(v_tail),
+                                      _ptr(tail_len), tail_cap, batch, n_q, n_seg, k_t, n_q_heads,
+                                      n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale,
+                                      _ptr(out), _ptr(lse_out), p, n, _stream()), "pc_parallel_attn_fp8")
 
 
 def pc_profile_begin():

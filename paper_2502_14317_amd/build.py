@@ -8,7 +8,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libparallelcomp.so")
 SOURCES = ["pc_api.hip", "gather.hip", "select.hip", "decode_attn.hip", "prefill_attn.hip",
-           "scores.hip", "ceiling.hip", "self_info.hip"]
+           "scores.hip", "ceiling.hip", "self_info.hip", "decode_attn_fp8.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument",

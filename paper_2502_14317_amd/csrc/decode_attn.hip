@@ -34,6 +34,7 @@ struct PcDecodeArgs {
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
   int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
+  int part0;              // index of this launch's first partial among the n_parts
   float scale_log2;       // softmax scale * log2(e)
 };
 
@@ -136,26 +137,29 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
     bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
     bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
     const float m_new = fmaxf(m_run, bmax);          // finite: every block holds a valid key
-    const float alpha = exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // arguments <= 0: the bare instruction
     m_run = m_new;
     float psum = 0.f;
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float p = exp2f(sv[bi][j] - m_new);
+        const float p = __builtin_amdgcn_exp2f(sv[bi][j] - m_new);
         psum += p;
         if (c16 < NQ) p_lds[wave][16 * bi + 4 * kk + j][c16] = p;
       }
     l_run = l_run * alpha + psum;
-    if (kk == 0 && c16 < NQ) alpha_lds[wave][c16] = alpha;
+    const bool moved = __any(alpha != 1.0f);         // some column's maximum grew (rare after the first keys)
+    if (moved && kk == 0 && c16 < NQ) alpha_lds[wave][c16] = alpha;
     PC_WAVE_LDS_SYNC();
-    // rescale, then o[n][:] += p[key][n] * v[key][:]
+    // rescale (only when a maximum moved), then o[n][:] += p[key][n] * v[key][:]
+    if (moved) {
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      const float al = alpha_lds[wave][n];
+      for (int n = 0; n < NQ; ++n) {
+        const float al = alpha_lds[wave][n];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o_acc[n][e] *= al;
+        for (int e = 0; e < 8; ++e) o_acc[n][e] *= al;
+      }
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   __syncthreads();
 
   // ---- merge the 4 wavefronts, write one partial per workgroup
-  const int part = s * a.n_split + split;
+  const int part = a.part0 + s * a.n_split + split;
   for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
     const int n = idx / D, d = idx % D;
     float M = -INFINITY;
@@ -419,8 +423,9 @@ int pc_decode_keys_per_wg(int k_t) {
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
                      int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
                      int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
-                     hipStream_t st) {
+                     int part0, hipStream_t st) {
   PcDecodeArgs a;
+  a.part0 = part0;
   a.q = (const uint16_t*)q_rot; a.kc = (const uint16_t*)kc; a.vc = (const uint16_t*)vc;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;

@@ -1,0 +1,377 @@
+// 8-bit compressed cache for the decoding stage (Eq. 9-11 with few query rows).
+//
+// The decode kernel reads every K / V byte once and is bound by HBM bandwidth, so storing the
+// compressed segments in 8 bits halves its time.  Format: OCP 8-bit float E4M3 (1 sign, 4
+// exponent bits with bias 7, 3 mantissa bits, largest magnitude 448, no infinities), one fp32
+// scale per (sequence, segment, KV head) for K and one for V:
+//   scale = max |x| over the segment's valid rows / 448   (1 if that maximum is 0)
+//   code  = E4M3(x / scale), round to nearest even, saturating
+// The paper leaves the cache precision open; this format is an extension of this library.
+//
+// kv_quantize_fp8_kernel   one workgroup per (sequence, segment, KV head, K or V): maximum,
+//                          then codes; the second sweep re-reads the 512 KiB segment from L2.
+// decode_attn_fp8_kernel   the split-KV kernel of decode_attn.hip on 8-bit operands: codes are
+//                          widened in registers (every E4M3 value is exact in bf16), K enters
+//                          the same 16x16x32 bf16 MFMA, the scales are folded into the logit
+//                          scale and into the partial output.  A lane loads the D / 4
+//                          consecutive bytes of its K row that it feeds to the matrix core
+//                          (the query operand is permuted to match), and 16 bytes of a V row.
+#include "pc_common.h"
+#include <math.h>
+
+#define PC_D8_WAVES 4
+#define PC_D8_ITER_KEYS 32
+#define PC_D8_LOG2E 1.4426950408889634f
+#define PC_E4M3_MAX 448.0f
+
+#define PC_D8_WAVE_LDS_SYNC()                                \
+  do {                                                       \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   \
+    __builtin_amdgcn_wave_barrier();                         \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");   \
+  } while (0)
+
+typedef float pc_f2 __attribute__((ext_vector_type(2)));
+
+// ------------------------------------------------------------------------------------------
+// Quantisation.  blockIdx.x = (b, s, g), blockIdx.y = 0 (K) or 1 (V).
+__global__ __launch_bounds__(256) void kv_quantize_fp8_kernel(
+    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+    const int32_t* __restrict__ seg_len, int per_head, int n_kv_heads, int k_t, int D,
+    uint8_t* __restrict__ k8, uint8_t* __restrict__ v8, float* __restrict__ k_scale,
+    float* __restrict__ v_scale) {
+  __shared__ uint32_t red[256 / PC_WAVE];
+  const long long seg = blockIdx.x;
+  const uint16_t* src = (blockIdx.y ? vc : kc) + seg * (long long)k_t * D;
+  uint8_t* dst = (blockIdx.y ? v8 : k8) + seg * (long long)k_t * D;
+  float* scale_out = blockIdx.y ? v_scale : k_scale;
+  const int len = seg_len ? min(max(seg_len[per_head ? seg : seg / n_kv_heads], 0), k_t) : k_t;
+  const long long n_valid = (long long)len * D / 8, n_all = (long long)k_t * D / 8;   // 8-element groups
+
+  // largest magnitude: bf16 magnitudes order like their 15-bit patterns
+  uint32_t amax = 0;
+  for (long long i = threadIdx.x; i < n_valid; i += blockDim.x) {
+    const uint4 x = *(const uint4*)(src + 8 * i);
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) amax = max(amax, max(w[e] & 0x7fffu, (w[e] >> 16) & 0x7fffu));
+  }
+#pragma unroll
+  for (int off = PC_WAVE / 2; off > 0; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off));
+  if (threadIdx.x % PC_WAVE == 0) red[threadIdx.x / PC_WAVE] = amax;
+  __syncthreads();
+  amax = 0;
+#pragma unroll
+  for (int w = 0; w < 256 / PC_WAVE; ++w) amax = max(amax, red[w]);
+  const float fmax_ = __uint_as_float(amax << 16);
+  const float scale = fmax_ > 0.f ? fmax_ / PC_E4M3_MAX : 1.0f;
+  if (threadIdx.x == 0) scale_out[seg] = scale;
+
+  for (long long i = threadIdx.x; i < n_all; i += blockDim.x) {
+    uint2 code = make_uint2(0u, 0u);
+    if (i < n_valid) {
+      const uint4 x = *(const uint4*)(src + 8 * i);
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        f[2 * e] = fminf(fmaxf(bf16_lo_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
+        f[2 * e + 1] = fminf(fmaxf(bf16_hi_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
+      }
+      uint32_t c0 = 0, c1 = 0;
+      c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], c0, false);
+      c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], c0, true);
+      c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], c1, false);
+      c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], c1, true);
+      code = make_uint2(c0, c1);
+    }
+    *(uint2*)(dst + 8 * i) = code;
+  }
+}
+
+int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
+                              int seg_len_per_head, long long n_segs, int n_kv_heads, int k_t,
+                              int head_dim, void* k8, void* v8, float* k_scale, float* v_scale,
+                              hipStream_t st) {
+  if (n_segs == 0) return PC_OK;
+  if (n_segs > 0x7fffffffLL) return PC_ERR_SHAPE;
+  PcProfScope prof(PC_KERNEL_KV_QUANTIZE, st);
+  hipLaunchKernelGGL(kv_quantize_fp8_kernel, dim3((unsigned)n_segs, 2), dim3(256), 0, st,
+                     (const uint16_t*)kc, (const uint16_t*)vc, seg_len, seg_len_per_head, n_kv_heads,
+                     k_t, head_dim, (uint8_t*)k8, (uint8_t*)v8, k_scale, v_scale);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+struct PcDecode8Args {
+  const uint16_t* q;      // rotated queries [B, n_q, H_q, D] bf16
+  const uint8_t* k8;      // [B, S, H_kv, k_t, D] E4M3 codes
+  const uint8_t* v8;
+  const float* k_scale;   // [B, S, H_kv]
+  const float* v_scale;
+  const int32_t* seg_len; // [B, S] ([B, S, H_kv] if seg_len_per_head) or nullptr
+  int seg_len_per_head;
+  float* part_o;          // [B, P, n_q, H_q, D]
+  float* part_lse;        // [B, P, n_q, H_q]
+  int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
+  float scale_log2;       // softmax scale * log2(e)
+};
+
+// four E4M3 codes of one 32-bit word -> two packed bf16 pairs (exact)
+__device__ __forceinline__ void pc_e4m3x4_to_bf16(uint32_t w, uint32_t& lo, uint32_t& hi) {
+  const pc_f2 a = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
+  const pc_f2 b = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+  lo = pack_bf16x2(a.x, a.y);
+  hi = pack_bf16x2(b.x, b.y);
+}
+
+template <int D, int NQ>
+__global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(PcDecode8Args a) {
+  constexpr int KSTEPS = D / 32;            // MFMA k-steps; a lane owns 8 KSTEPS = D / 4 bytes of each of its K rows
+  constexpr int KQ = D / 64;                // 16-byte loads per lane and 16-key block
+  constexpr int LPR = D / 16;               // lanes per V row (16 codes each)
+  constexpr int RPI = PC_WAVE / LPR;        // V rows per load instruction
+  constexpr int VLOADS = PC_D8_ITER_KEYS / RPI;
+  constexpr int KBLK = PC_D8_ITER_KEYS / 16;
+
+  __shared__ float p_lds[PC_D8_WAVES][PC_D8_ITER_KEYS][NQ];
+  __shared__ float alpha_lds[PC_D8_WAVES][NQ];
+  __shared__ float red_o[PC_D8_WAVES][NQ][D];
+  __shared__ float red_m[PC_D8_WAVES][NQ], red_l[PC_D8_WAVES][NQ];
+
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int n_cols = a.n_q * G;             // valid query columns (<= NQ)
+  const int lane = threadIdx.x % PC_WAVE, wave = threadIdx.x / PC_WAVE;
+  const int kk = lane / 16, c16 = lane % 16;
+
+  int bid = blockIdx.x;
+  const int split = bid % a.n_split; bid /= a.n_split;
+  const int s = bid % a.n_seg;       bid /= a.n_seg;
+  const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
+  const int b = bid;
+
+  const long long seg_id = ((long long)b * a.n_seg + s) * a.n_kv_heads + g;
+  const int len_idx = a.seg_len_per_head ? (int)seg_id : b * a.n_seg + s;
+  const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
+  const uint8_t* kseg = a.k8 + seg_id * a.k_t * D;
+  const uint8_t* vseg = a.v8 + seg_id * a.k_t * D;
+  const float k_sc = a.k_scale[seg_id] * a.scale_log2;     // logits in log2 units
+  const float v_sc = a.v_scale[seg_id];
+
+  const int wg_begin = split * a.keys_per_wg;
+  const int wg_end = min(len, wg_begin + a.keys_per_wg);
+  const int per_wave = a.keys_per_wg / PC_D8_WAVES;        // multiple of PC_D8_ITER_KEYS
+  const int w_begin = wg_begin + wave * per_wave;
+  const int w_end = min(wg_end, w_begin + per_wave);
+
+  // B operand: column c16 = (t, head-in-group); k-step j of lane group kk covers
+  // d = 64 (j / 2) + 16 kk + 8 (j % 2) .. + 7, the bytes the lane loads of its K rows (load i of
+  // a row takes bytes 64 i + 16 kk .. + 15, so the 4 lanes of a row read 64 contiguous bytes)
+  bf16x8 bq[KSTEPS];
+  {
+    const bool valid = c16 < n_cols;
+    const int t = valid ? c16 / G : 0, hg = valid ? c16 % G : 0;
+    const uint16_t* qrow = a.q + (((long long)b * a.n_q + t) * a.n_q_heads + g * G + hg) * D;
+#pragma unroll
+    for (int j = 0; j < KSTEPS; ++j) {
+      uint4 raw = valid ? *(const uint4*)(qrow + 64 * (j / 2) + 16 * kk + 8 * (j % 2)) : make_uint4(0, 0, 0, 0);
+      bq[j] = *(bf16x8*)&raw;
+    }
+  }
+
+  float m_run = -INFINITY, l_run = 0.f;     // of column c16 (this lane's share of the sum)
+  float o_acc[NQ][16];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[n][e] = 0.f;
+
+  const int v_row = lane / LPR, v_piece = lane % LPR;
+
+  // three register buffers: the loads of two iterations (2 x 8 KiB per wavefront) stay in flight
+  uint4 kbuf[3][KBLK][KQ], vbuf[3][VLOADS];
+  auto issue_loads = [&](int buf, int key0) {
+#pragma unroll
+    for (int bi = 0; bi < KBLK; ++bi) {
+      const int row = min(key0 + 16 * bi + c16, len - 1);
+#pragma unroll
+      for (int i = 0; i < KQ; ++i)
+        kbuf[buf][bi][i] = *(const uint4*)(kseg + (long long)row * D + 64 * i + 16 * kk);
+    }
+#pragma unroll
+    for (int i = 0; i < VLOADS; ++i) {
+      const int row = min(key0 + RPI * i + v_row, len - 1);
+      vbuf[buf][i] = *(const uint4*)(vseg + (long long)row * D + 16 * v_piece);
+    }
+  };
+
+  auto consume = [&](int buf, int key0) {
+    floatx4 acc[KBLK];
+#pragma unroll
+    for (int bi = 0; bi < KBLK; ++bi) {
+      acc[bi] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < KSTEPS; ++j) {
+        // k-step j: words 2 (j % 2), 2 (j % 2) + 1 of the lane's load j / 2
+        const uint4 raw = kbuf[buf][bi][j / 2];
+        const uint32_t w0 = (j % 2) ? raw.z : raw.x, w1 = (j % 2) ? raw.w : raw.y;
+        u32x4 kb16;
+        uint32_t lo, hi;
+        pc_e4m3x4_to_bf16(w0, lo, hi); kb16[0] = lo; kb16[1] = hi;
+        pc_e4m3x4_to_bf16(w1, lo, hi); kb16[2] = lo; kb16[3] = hi;
+        acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8*)&kb16, bq[j], acc[bi], 0, 0, 0);
+      }
+    }
+    float sv[KBLK][4];
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int bi = 0; bi < KBLK; ++bi)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int key = key0 + 16 * bi + 4 * kk + j;
+        sv[bi][j] = (key < w_end) ? acc[bi][j] * k_sc : -INFINITY;
+        bmax = fmaxf(bmax, sv[bi][j]);
+      }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+    const float m_new = fmaxf(m_run, bmax);          // finite: every block holds a valid key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // arguments <= 0: the bare instruction
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < KBLK; ++bi)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float p = __builtin_amdgcn_exp2f(sv[bi][j] - m_new);
+        psum += p;
+        if (c16 < NQ) p_lds[wave][16 * bi + 4 * kk + j][c16] = p;
+      }
+    l_run = l_run * alpha + psum;
+    const bool moved = __any(alpha != 1.0f);         // some column's maximum grew (rare after the first keys)
+    if (moved && kk == 0 && c16 < NQ) alpha_lds[wave][c16] = alpha;
+    PC_D8_WAVE_LDS_SYNC();
+    if (moved) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        const float al = alpha_lds[wave][n];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[n][e] *= al;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < VLOADS; ++i) {
+      const int key_local = RPI * i + v_row;
+      const uint4 raw = vbuf[buf][i];
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      float vf[16];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const pc_f2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[e], false);
+        const pc_f2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[e], true);
+        vf[4 * e] = lo.x; vf[4 * e + 1] = lo.y; vf[4 * e + 2] = hi.x; vf[4 * e + 3] = hi.y;
+      }
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        const float p = p_lds[wave][key_local][n];    // 0 for masked keys
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[n][e] = fmaf(p, vf[e], o_acc[n][e]);
+      }
+    }
+    PC_D8_WAVE_LDS_SYNC();
+  };
+
+  if (w_begin < w_end) {
+    issue_loads(0, w_begin);
+    if (w_begin + PC_D8_ITER_KEYS < w_end) issue_loads(1, w_begin + PC_D8_ITER_KEYS);
+    auto iter = [&](int cur, int fill, int key0) __attribute__((always_inline)) {
+      if (key0 + 2 * PC_D8_ITER_KEYS < w_end) issue_loads(fill, key0 + 2 * PC_D8_ITER_KEYS);
+      consume(cur, key0);
+    };
+    int key0 = w_begin;
+    while (true) {
+      iter(0, 2, key0); key0 += PC_D8_ITER_KEYS;
+      if (key0 >= w_end) break;
+      iter(1, 0, key0); key0 += PC_D8_ITER_KEYS;
+      if (key0 >= w_end) break;
+      iter(2, 1, key0); key0 += PC_D8_ITER_KEYS;
+      if (key0 >= w_end) break;
+    }
+  }
+
+  // ---- wavefront totals: sum the per-lane shares
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float x = o_acc[n][e];
+#pragma unroll
+      for (int off = LPR; off < PC_WAVE; off <<= 1) x += __shfl_xor(x, off);
+      o_acc[n][e] = x;
+    }
+  if (kk == 0 && c16 < NQ) { red_m[wave][c16] = m_run; red_l[wave][c16] = l_run; }
+  if (v_row == 0) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red_o[wave][n][16 * v_piece + e] = o_acc[n][e];
+  }
+  __syncthreads();
+
+  // ---- merge the 4 wavefronts, write one partial per workgroup (values scaled back)
+  const int part = s * a.n_split + split;
+  for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
+    const int n = idx / D, d = idx % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < PC_D8_WAVES; ++w) M = fmaxf(M, red_m[w][n]);
+    float num = 0.f, den = 0.f;
+    if (M > -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < PC_D8_WAVES; ++w) {
+        const float sc = exp2f(red_m[w][n] - M);
+        num += sc * red_o[w][n][d];
+        den += sc * red_l[w][n];
+      }
+    }
+    const int t = n / G, hg = n % G;
+    const long long row = (((long long)b * a.n_parts + part) * a.n_q + t) * a.n_q_heads + g * G + hg;
+    a.part_o[row * D + d] = (den > 0.f) ? num / den * v_sc : 0.f;
+    if (d == 0) a.part_lse[row] = (den > 0.f) ? (M + log2f(den)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
+template <int D>
+static int launch_decode8_d(const PcDecode8Args& a, int batch, int nq_pad, hipStream_t st) {
+  const long long blocks = (long long)batch * a.n_kv_heads * a.n_seg * a.n_split;
+  if (blocks == 0) return PC_OK;
+  if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
+  dim3 grid((unsigned)blocks), block(PC_D8_WAVES * PC_WAVE);
+  PcProfScope prof(PC_KERNEL_DECODE_FP8, st);
+  if (nq_pad == 4) hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 8>), grid, block, 0, st, a);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
+int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, const float* k_scale,
+                         const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
+                         int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                         int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
+                         hipStream_t st) {
+  PcDecode8Args a;
+  a.q = (const uint16_t*)q_rot; a.k8 = (const uint8_t*)k8; a.v8 = (const uint8_t*)v8;
+  a.k_scale = k_scale; a.v_scale = v_scale;
+  a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
+  a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
+  a.keys_per_wg = pc_decode_keys_per_wg(k_t);
+  a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;
+  a.n_parts = n_parts;
+  a.scale_log2 = scale * PC_D8_LOG2E;
+  const int cols = n_q * (n_q_heads / n_kv_heads);
+  if (cols > 8) return PC_ERR_UNSUPPORTED;
+  return head_dim == 128 ? launch_decode8_d<128>(a, batch, cols <= 4 ? 4 : 8, st)
+                         : launch_decode8_d<64>(a, batch, cols <= 4 ? 4 : 8, st);
+}

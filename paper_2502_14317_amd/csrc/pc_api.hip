@@ -61,7 +61,8 @@ extern "C" const char* pc_kernel_name(int id) {
       "rope_table_kernel", "kv_prepass_kernel", "flash_fwd_kernel", "scores_kernel<1>",
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
-      "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel"};
+      "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel", "kv_quantize_fp8_kernel",
+      "decode_attn_fp8_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -206,6 +207,113 @@ extern "C" int pc_kv_append(const void* k_new, const void* v_new, int32_t batch,
   return pc_launch_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_dim,
                              pos0, rope_base, kc, vc, seg_len, seg_len_per_head != 0,
                              (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------- 8-bit cache
+extern "C" int pc_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
+                                  int32_t seg_len_per_head, int32_t batch, int32_t n_seg,
+                                  int32_t k_t, int32_t n_kv_heads, int32_t head_dim, void* k8,
+                                  void* v8, float* k_scale, float* v_scale, void* stream) {
+  if (batch < 0 || n_seg < 0 || k_t < 1 || n_kv_heads < 1) return PC_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
+  if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
+  if (batch == 0 || n_seg == 0) return PC_OK;            // nothing to quantise
+  if (!kc || !vc || !k8 || !v8 || !k_scale || !v_scale) return PC_ERR_NULL;
+  if (!pc_aligned(kc, 16) || !pc_aligned(vc, 16) || !pc_aligned(k8, 16) || !pc_aligned(v8, 16))
+    return PC_ERR_SHAPE;
+  return pc_launch_kv_quantize_fp8(kc, vc, seg_len, seg_len_per_head,
+                                   (long long)batch * n_seg * n_kv_heads, n_kv_heads, k_t, head_dim,
+                                   k8, v8, k_scale, v_scale, (hipStream_t)stream);
+}
+
+struct Par8Ws {
+  size_t q_rot, part_o, part_lse, total;
+  int n_parts, parts8;
+};
+
+static Par8Ws par8_ws_layout(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads, int D) {
+  Par8Ws w;
+  const int kpw = pc_decode_keys_per_wg(k_t);
+  w.parts8 = n_seg * ((k_t + kpw - 1) / kpw);
+  w.n_parts = w.parts8;
+  if (tail_cap > 0) {
+    const int kpt = pc_decode_keys_per_wg(tail_cap);
+    w.n_parts += (tail_cap + kpt - 1) / kpt;
+  }
+  size_t off = 0;
+  const size_t rows = (size_t)batch * n_q * n_q_heads;
+  w.q_rot = off;    off = pc_align_up(off + rows * D * 2, kAlign);
+  w.part_o = off;   off = pc_align_up(off + rows * (size_t)w.n_parts * D * sizeof(float), kAlign);
+  w.part_lse = off; off = pc_align_up(off + rows * (size_t)w.n_parts * sizeof(float), kAlign);
+  w.total = off;
+  return w;
+}
+
+static int check_par8(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads,
+                      int n_kv_heads, int D) {
+  if (batch < 1 || n_q < 1 || n_seg < 0 || k_t < 1 || tail_cap < 0) return PC_ERR_SHAPE;
+  if (n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % n_kv_heads != 0) return PC_ERR_SHAPE;
+  if (D != 64 && D != 128) return PC_ERR_SHAPE;
+  if (k_t > (1 << 24) || tail_cap > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
+  if (n_seg == 0 && tail_cap == 0) return PC_ERR_SHAPE;
+  if ((long long)n_q * (n_q_heads / n_kv_heads) > 8) return PC_ERR_UNSUPPORTED;
+  return PC_OK;
+}
+
+extern "C" size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg,
+                                                       int32_t k_t, int32_t tail_cap,
+                                                       int32_t n_q_heads, int32_t n_kv_heads,
+                                                       int32_t head_dim) {
+  if (check_par8(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim) != PC_OK) return 0;
+  return par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, head_dim).total;
+}
+
+extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v8,
+                                    const float* k_scale, const float* v_scale,
+                                    const int32_t* seg_len, int32_t seg_len_per_head,
+                                    const void* k_tail, const void* v_tail, const int32_t* tail_len,
+                                    int32_t tail_cap, int32_t batch, int32_t n_q, int32_t n_seg,
+                                    int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
+                                    int32_t head_dim, int32_t q_pos0, float rope_base,
+                                    float softmax_scale, void* out, float* lse_out, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  int rc = check_par8(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim);
+  if (rc != PC_OK) return rc;
+  if (!q || !out) return PC_ERR_NULL;
+  if (n_seg > 0 && (!k8 || !v8 || !k_scale || !v_scale)) return PC_ERR_NULL;
+  if (tail_cap > 0 && (!k_tail || !v_tail || !tail_len)) return PC_ERR_NULL;
+  if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
+  if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
+  if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
+  if (n_seg > 0 && (!pc_aligned(k8, 16) || !pc_aligned(v8, 16))) return PC_ERR_SHAPE;
+  const int D = head_dim;
+  const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, D);
+  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)ws;
+  const float scale = eff_scale(softmax_scale, D);
+  const void* q_rot = q;
+  if (q_pos0 >= 0) {
+    rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
+                          q_pos0, rope_base, st);
+    if (rc != PC_OK) return rc;
+    q_rot = base + w.q_rot;
+  }
+  float* part_o = (float*)(base + w.part_o);
+  float* part_lse = (float*)(base + w.part_lse);
+  if (n_seg > 0) {
+    rc = pc_launch_decode_fp8(q_rot, k8, v8, k_scale, v_scale, seg_len, seg_len_per_head, batch, n_q,
+                              n_seg, k_t, n_q_heads, n_kv_heads, D, scale, part_o, part_lse,
+                              w.n_parts, st);
+    if (rc != PC_OK) return rc;
+  }
+  if (tail_cap > 0) {     // the 16-bit tail: one more segment of the split-KV kernel
+    rc = pc_launch_decode(q_rot, k_tail, v_tail, tail_len, 0, batch, n_q, 1, tail_cap, n_q_heads,
+                          n_kv_heads, D, scale, part_o, part_lse, w.n_parts, w.parts8, st);
+    if (rc != PC_OK) return rc;
+  }
+  return pc_launch_merge(part_o, part_lse, q_rot, nullptr, nullptr, out, lse_out, batch, n_q,
+                         n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
 }
 
 extern "C" int pc_chunk_self_information(const void* logits, const int32_t* targets, int32_t n_chunks,
@@ -356,7 +464,7 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
   if (w.small) {
     if (n_seg > 0) {
       rc = pc_launch_decode(q_rot, kc, vc, seg_len, seg_len_per_head, batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
-                            D, scale, part_o, part_lse, w.n_parts, st);
+                            D, scale, part_o, part_lse, w.n_parts, 0, st);
       if (rc != PC_OK) return rc;
     }
     return pc_launch_merge(part_o, part_lse, q_rot, k_self, v_self, out, lse_out, batch, n_q,

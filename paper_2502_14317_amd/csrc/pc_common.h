@@ -141,8 +141,17 @@ int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_n
                         hipStream_t st);
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
                      int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
-                     int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
+                     int head_dim, float scale, float* part_o, float* part_lse, int n_parts, int part0,
                      hipStream_t st);
+int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
+                              int seg_len_per_head, long long n_segs, int n_kv_heads, int k_t,
+                              int head_dim, void* k8, void* v8, float* k_scale, float* v_scale,
+                              hipStream_t st);
+int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, const float* k_scale,
+                         const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
+                         int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
+                         int head_dim, float scale, float* part_o, float* part_lse, int n_parts,
+                         hipStream_t st);
 int pc_launch_merge(const float* part_o, const float* part_lse, const void* q_rot,
                     const void* k_self, const void* v_self, void* out, float* lse_out, int batch,
                     int n_q, int n_q_heads, int n_kv_heads, int head_dim, int n_parts, float scale,

@@ -206,3 +206,51 @@ class DecodeCache:
                            self.kt, self.Hq, self.Hkv, self.D, pos, self.rope_base, self.scale,
                            self.out, self.lse, self.ws)
         return self.out
+
+
+class DecodeCacheFp8:
+    """DecodeCache with the compressed segments stored in 8 bits (E4M3 codes + one scale per
+    sequence, segment and KV head, written once by pc_kv_quantize_fp8 when the cache is loaded)
+    and the growing tail kept in bf16 as a one-segment cache of its own.  A step =
+    pc_kv_append on the tail + pc_parallel_attn_fp8 over [8-bit segments ; tail]."""
+
+    def __init__(self, batch, n_seg, keep_tokens, tail_cap, n_q_heads, n_kv_heads, head_dim, rope_base,
+                 softmax_scale=0.0, device="cuda"):
+        self.B, self.S, self.kt, self.cap = batch, n_seg, keep_tokens, tail_cap
+        self.Hq, self.Hkv, self.D = n_q_heads, n_kv_heads, head_dim
+        self.rope_base, self.scale = rope_base, softmax_scale
+        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        self.k8 = torch.zeros((batch, n_seg, n_kv_heads, keep_tokens, head_dim), dtype=torch.uint8, device=device)
+        self.v8 = torch.zeros_like(self.k8)
+        self.k_scale = torch.ones((batch, n_seg, n_kv_heads), dtype=f32, device=device)
+        self.v_scale = torch.ones_like(self.k_scale)
+        self.seg_len = torch.zeros((batch, n_seg), dtype=i32, device=device)
+        self.k_tail = torch.zeros((batch, 1, n_kv_heads, tail_cap, head_dim), dtype=bf, device=device)
+        self.v_tail = torch.zeros_like(self.k_tail)
+        self.tail_len = torch.zeros((batch, 1), dtype=i32, device=device)
+        self.out = torch.empty((batch, 1, n_q_heads, head_dim), dtype=bf, device=device)
+        self.lse = torch.empty((batch, n_q_heads, 1), dtype=f32, device=device)
+        self.ws = B.alloc_workspace(B.pc_parallel_attn_fp8_workspace_bytes(
+            batch, 1, n_seg, keep_tokens, tail_cap, n_q_heads, n_kv_heads, head_dim), device)
+
+    def load(self, kc, vc, seg_len, k_tail, v_tail):
+        """kc, vc [B, n_seg, H_kv, k_t, D] bf16 compacted segments (quantised here), seg_len
+        [B, n_seg] or None, k_tail, v_tail [B, n0, H_kv, D] rotated keys / values of the query block."""
+        if seg_len is None:
+            self.seg_len.fill_(self.kt)
+        else:
+            self.seg_len.copy_(seg_len)
+        B.pc_kv_quantize_fp8(kc, vc, self.seg_len, self.B, self.S, self.kt, self.Hkv, self.D, self.k8,
+                             self.v8, self.k_scale, self.v_scale)
+        self.tail_len.zero_()
+        B.pc_kv_append(k_tail, v_tail, self.B, k_tail.shape[1], 1, 0, self.cap, self.Hkv, self.D, -1,
+                       self.rope_base, self.k_tail, self.v_tail, self.tail_len)
+
+    def step(self, q_new, k_new, v_new, pos):
+        B.pc_kv_append(k_new, v_new, self.B, 1, 1, 0, self.cap, self.Hkv, self.D, pos, self.rope_base,
+                       self.k_tail, self.v_tail, self.tail_len)
+        B.pc_parallel_attn_fp8(q_new, self.k8, self.v8, self.k_scale, self.v_scale, self.seg_len,
+                               self.k_tail, self.v_tail, self.tail_len, self.cap, self.B, 1, self.S,
+                               self.kt, self.Hq, self.Hkv, self.D, pos, self.rope_base, self.scale,
+                               self.out, self.lse, self.ws)
+        return self.out

@@ -88,6 +88,26 @@ def test_null_and_shape_errors_before_any_gpu_work():
         assert L.pc_kv_append(one, one, *bad, one, one, one, 0, None) == -2, (i, value)
     assert L.pc_kv_append(one, one, 2, 0, *ok[2:], one, one, one, 0, None) == 0    # nothing to append
     assert L.pc_kv_append(one, one, 0, 1, *ok[2:], one, one, one, 0, None) == 0
+    # 8-bit cache
+    qa = (0, 2, 3, 64, 2, 128)                      # seg_len_per_head, batch, n_seg, k_t, H_kv, D
+    assert L.pc_kv_quantize_fp8(None, one, None, *qa, one, one, one, one, None) == -1
+    assert L.pc_kv_quantize_fp8(None, None, None, 0, 2, 0, 64, 2, 128, None, None, None, None, None) == 0   # no segments
+    assert L.pc_kv_quantize_fp8(one, one, None, *qa, one, one, None, one, None) == -1
+    assert L.pc_kv_quantize_fp8(one, one, None, 0, 2, 3, 64, 2, 96, one, one, one, one, None) == -2
+    assert L.pc_kv_quantize_fp8(one, one, None, 2, 2, 3, 64, 2, 128, one, one, one, one, None) == -2
+    assert L.pc_kv_quantize_fp8(one, one, None, 0, 0, 3, 64, 2, 128, one, one, one, one, None) == 0   # empty batch
+    pa = (0, 1, 1, 2, 64, 8, 2, 128, -1)            # tail_cap, batch, n_q, n_seg, k_t, H_q, H_kv, D, q_pos0
+    call = lambda q, k8, tail, args, wsb: L.pc_parallel_attn_fp8(q, k8, one, one, one, None, 0, tail, tail, tail,
+                                                                 *args, 1e4, 0.0, one, None, one, wsb, None)
+    assert call(None, one, None, pa, 1 << 30) == -1
+    assert call(one, None, None, pa, 1 << 30) == -1
+    assert call(one, one, None, pa, 8) == -3
+    assert call(one, one, None, (16,) + pa[1:], 1 << 30) == -1                  # tail_cap > 0 without a tail
+    assert call(one, one, None, (0, 1, 3, 2, 64, 8, 2, 128, -1), 1 << 30) == -5  # 12 query columns
+    assert call(one, one, None, (0, 1, 1, 0, 64, 8, 2, 128, -1), 1 << 30) == -2  # nothing to attend to
+    assert pc.pc_parallel_attn_fp8_workspace_bytes(1, 3, 2, 64, 0, 8, 2, 128) == 0
+    a8 = pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 0, 8, 2, 128)
+    assert 0 < a8 < pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 512, 8, 2, 128)
 
 
 def test_workspace_sizes_are_positive_and_monotone():

@@ -1,0 +1,205 @@
+"""GPU parity of the 8-bit (E4M3) compressed cache: codes and scales bit-exact against the CPU
+oracle's encoder, attention over the 8-bit segments (+ a 16-bit tail) against the oracle's
+attention on the dequantised values."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_14317_amd as pc
+from workloads import CFG4, f32_to_bf16_bits, bf16_bits_to_f64
+from helpers import (O_ATOL, O_RTOL, LSE_ATOL, bits_to_dev, dev_bf16_to_f64, assert_close)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _mk(r, shape, s=1.0):
+    return f32_to_bf16_bits((r.standard_normal(shape) * s).astype(np.float32))
+
+
+def _quantize(kc_bits, vc_bits, seg_len, per_head):
+    B, S, Hkv, kt, D = kc_bits.shape
+    k8 = torch.full((B, S, Hkv, kt, D), 0x55, dtype=torch.uint8, device="cuda")
+    v8 = torch.full_like(k8, 0x55)
+    ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda")
+    vs = torch.empty_like(ks)
+    pc.pc_kv_quantize_fp8(bits_to_dev(kc_bits), bits_to_dev(vc_bits),
+                          None if seg_len is None else torch.from_numpy(seg_len).cuda(), B, S, kt, Hkv, D,
+                          k8, v8, ks, vs, seg_len_per_head=per_head)
+    torch.cuda.synchronize()
+    return k8, v8, ks, vs
+
+
+def test_quantize_every_bf16_value_bit_exact():
+    """Scale exactly 1 (the segment's maximum is 448): the codes of all bf16 values of magnitude
+    <= 448 must be the oracle's, which pins rounding, ties, subnormals and signs."""
+    _say("fp8 quantize: all bf16 values")
+    allb = np.arange(65536, dtype=np.uint16)
+    with np.errstate(invalid="ignore"):                      # the NaN patterns are dropped below
+        f = bf16_bits_to_f64(allb)
+    allb = allb[np.isfinite(f) & (np.abs(f) <= 448)]
+    D = 128
+    kt = (allb.size + D - 1) // D
+    bits = np.zeros((1, 1, 1, kt, D), dtype=np.uint16)
+    bits.reshape(-1)[:allb.size] = allb
+    k8, v8, ks, vs = _quantize(bits, bits[:, :, :, ::-1].copy(), None, 0)
+    rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(bits[0]), bf16_bits_to_f64(bits[0, :, :, ::-1]))
+    assert ks.item() == 1.0 and vs.item() == 1.0 and rks[0, 0] == 1.0
+    np.testing.assert_array_equal(k8.cpu().numpy()[0], rk8)
+    np.testing.assert_array_equal(v8.cpu().numpy()[0], rv8)
+
+
+@pytest.mark.parametrize("D,per_head", [(128, 0), (64, 1)])
+def test_quantize_random_segments_bit_exact(D, per_head):
+    _say(f"fp8 quantize: random segments D={D} per_head={per_head}")
+    r = np.random.default_rng([51, D])
+    B, S, Hkv, kt = 2, 3, 2, 100
+    kc, vc = _mk(r, (B, S, Hkv, kt, D), 2.5), _mk(r, (B, S, Hkv, kt, D), 0.3)
+    kc[0, 0, 0, 5] = f32_to_bf16_bits(np.full(D, 37.0, dtype=np.float32))      # an outlier row (sink-like)
+    kc[1, 2, 1] = 0                                                            # an all-zero segment
+    sl = r.integers(0, kt + 1, size=(B, S, Hkv) if per_head else (B, S)).astype(np.int32)
+    sl[0, 0] = kt
+    k8, v8, ks, vs = _quantize(kc, vc, sl, per_head)
+    for b in range(B):
+        rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]), sl[b])
+        np.testing.assert_array_equal(ks[b].cpu().numpy(), rks)
+        np.testing.assert_array_equal(vs[b].cpu().numpy(), rvs)
+        np.testing.assert_array_equal(k8[b].cpu().numpy(), rk8)
+        np.testing.assert_array_equal(v8[b].cpu().numpy(), rv8)
+
+
+def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed):
+    _say(f"fp8 attention {name}: B={B} n_q={n_q} S={S} kt={kt} H={Hq}/{Hkv} D={D} tail={tail_cap} ragged={ragged}")
+    r = np.random.default_rng([52, seed])
+    q = _mk(r, (B, n_q, Hq, D), 3.0)
+    kc, vc = _mk(r, (B, S, Hkv, kt, D)), _mk(r, (B, S, Hkv, kt, D))
+    sl = r.integers(0, kt + 1, size=(B, S)).astype(np.int32) if ragged else None
+    if ragged:
+        sl[0, 0] = kt
+    k8, v8, ks, vs = _quantize(kc, vc, sl, 0)
+    kt_bits = vt_bits = tl = None
+    if tail_cap:
+        kt_bits, vt_bits = _mk(r, (B, 1, Hkv, tail_cap, D)), _mk(r, (B, 1, Hkv, tail_cap, D))
+        tl = r.integers(1, tail_cap + 1, size=(B,)).astype(np.int32)
+    out = torch.empty((B, n_q, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, Hq, n_q), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, n_q, S, kt, tail_cap, Hq, Hkv, D))
+    pc.pc_parallel_attn_fp8(bits_to_dev(q), k8, v8, ks, vs, None if sl is None else torch.from_numpy(sl).cuda(),
+                            bits_to_dev(kt_bits) if tail_cap else None, bits_to_dev(vt_bits) if tail_cap else None,
+                            torch.from_numpy(tl).cuda() if tail_cap else None, tail_cap, B, n_q, S, kt, Hq, Hkv, D,
+                            q_pos0, 1.0e4, 0.0, out, lse, ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        # the oracle quantises on its own (bit-equal to the GPU's codes, tested above) and attends
+        # over its dequantised values
+        rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]),
+                                                    None if sl is None else sl[b])
+        kd, vd = oracle.dequantize_kv_fp8(rk8, rks), oracle.dequantize_kv_fp8(rv8, rvs)
+        seg_len = np.full(S, kt) if sl is None else sl[b].astype(np.int64)
+        if tail_cap:
+            pad = max(kt, tail_cap)
+            K = np.zeros((S + 1, Hkv, pad, D)); V = np.zeros_like(K)
+            K[:S, :, :kt] = kd; V[:S, :, :kt] = vd
+            K[S, :, :tail_cap] = bf16_bits_to_f64(kt_bits[b, 0]); V[S, :, :tail_cap] = bf16_bits_to_f64(vt_bits[b, 0])
+            kd, vd, seg_len = K, V, np.append(seg_len, tl[b])
+        qf = bf16_bits_to_f64(q[b])
+        if q_pos0 >= 0:
+            qf = oracle.rope(qf, q_pos0 + np.arange(n_q), 1.0e4)
+        ro, rl = oracle.global_attention_concat(qf, kd, vd, seg_len=seg_len)
+        assert_close(dev_bf16_to_f64(out[b]), ro, O_ATOL, O_RTOL, f"{name} out[b={b}]")
+        assert_close(lse[b].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"{name} lse[b={b}]")
+
+
+def test_fp8_attention_gqa_with_tail():
+    _attn_case("gqa-tail", 2, 1, 4, 1100, 8, 2, 128, 70, 4000, True, 1)
+
+
+def test_fp8_attention_mha64_and_two_rows():
+    _attn_case("mha64", 3, 1, 3, 333, 4, 4, 64, 0, -1, True, 2)
+    _attn_case("nq2-g4", 1, 2, 2, 2048, 8, 2, 128, 1500, -1, False, 3)
+    _attn_case("tail-only", 2, 1, 0, 64, 4, 2, 64, 40, 7, False, 4)
+
+
+def test_fp8_decode_steps_match_oracle():
+    """The decode loop on the 8-bit cache: segments quantised at load, bf16 tail grown on the
+    device; against the oracle's decode_steps over its own dequantised segments."""
+    from paper_2502_14317_amd.layer import DecodeCacheFp8
+    Bn, S, kt, Hq, Hkv, D, n0, T, base, pos0, cap = 2, 3, 160, 8, 2, 128, 37, 7, 5.0e5, 700, 64
+    _say(f"fp8 decode steps: B={Bn} S={S} kt={kt} H={Hq}/{Hkv} D={D} n0={n0} T={T}")
+    r = np.random.default_rng([53])
+    kc, vc = _mk(r, (Bn, S, Hkv, kt, D)), _mk(r, (Bn, S, Hkv, kt, D))
+    k0, v0 = _mk(r, (Bn, n0, Hkv, D)), _mk(r, (Bn, n0, Hkv, D))
+    qn, kn, vn = _mk(r, (Bn, T, Hq, D), 3.0), _mk(r, (Bn, T, Hkv, D)), _mk(r, (Bn, T, Hkv, D))
+    sl = r.integers(1, kt + 1, size=(Bn, S)).astype(np.int32)
+    cache = DecodeCacheFp8(Bn, S, kt, cap, Hq, Hkv, D, base)
+    cache.load(bits_to_dev(kc), bits_to_dev(vc), torch.from_numpy(sl).cuda(), bits_to_dev(k0), bits_to_dev(v0))
+    qd, kd, vd = bits_to_dev(qn), bits_to_dev(kn), bits_to_dev(vn)
+    outs, lses = [], []
+    for t in range(T):
+        cache.step(qd[:, t:t + 1].contiguous(), kd[:, t:t + 1].contiguous(), vd[:, t:t + 1].contiguous(), pos0 + t)
+        outs.append(cache.out.clone()); lses.append(cache.lse.clone())
+    torch.cuda.synchronize()
+    assert (cache.tail_len.cpu().numpy() == n0 + T).all()
+    to_bf16 = lambda x: bf16_bits_to_f64(f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
+    for b in range(Bn):
+        rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]), sl[b])
+        ro, rl, _ = oracle.decode_steps(bf16_bits_to_f64(qn[b]), bf16_bits_to_f64(kn[b]), bf16_bits_to_f64(vn[b]),
+                                        oracle.dequantize_kv_fp8(rk8, rks), oracle.dequantize_kv_fp8(rv8, rvs),
+                                        bf16_bits_to_f64(k0[b]), bf16_bits_to_f64(v0[b]), pos0, base,
+                                        seg_len=sl[b], store=to_bf16)
+        go = np.stack([dev_bf16_to_f64(o[b, 0]) for o in outs])
+        gl = np.stack([l[b, :, 0].cpu().numpy() for l in lses])
+        assert_close(go, ro, O_ATOL, O_RTOL, f"fp8 decode steps out[b={b}]")
+        assert_close(gl, rl, LSE_ATOL, 1e-3, f"fp8 decode steps lse[b={b}]")
+
+
+def test_fp8_attention_rejects_many_query_columns():
+    one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pc.PcError) as e:
+        pc.pc_parallel_attn_fp8(one, one, one, one, one, None, None, None, None, 0, 1, 4, 1, 64, 32, 8, 128,
+                                -1, 1.0e4, 0.0, one, None, one)
+    assert e.value.status == -5                             # PC_ERR_UNSUPPORTED
+
+
+def test_fp8_decode_full_size_sampled():
+    """The decode config (16 sequences x 32 segments x 2048 rows x 8 KV heads) in 8 bits: sampled
+    (sequence, KV group) pairs against the oracle on its own codes, and the codes themselves on
+    sampled segments."""
+    cfg = CFG4
+    _say(f"fp8 decode {cfg.name}")
+    g = torch.Generator(device="cuda").manual_seed(8)
+    B, S, Hkv, kt, D, Hq = cfg.batch, cfg.n_seg, cfg.n_kv_heads, cfg.keep_tokens, cfg.head_dim, cfg.n_q_heads
+    bf = torch.bfloat16
+    kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
+    vc = torch.empty_like(kc)
+    for b in range(B):
+        kc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
+        vc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
+    k8 = torch.empty(kc.shape, dtype=torch.uint8, device="cuda"); v8 = torch.empty_like(k8)
+    ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); vs = torch.empty_like(ks)
+    pc.pc_kv_quantize_fp8(kc, vc, None, B, S, kt, Hkv, D, k8, v8, ks, vs)
+    q = torch.randn((B, 1, Hq, D), generator=g, device="cuda").to(bf)
+    out = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, 1, S, kt, 0, Hq, Hkv, D))
+    pc.pc_parallel_attn_fp8(q, k8, v8, ks, vs, None, None, None, None, 0, B, 1, S, kt, Hq, Hkv, D, -1, 1.0e4,
+                            0.0, out, lse, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    G = Hq // Hkv
+    for (b, gk) in ((0, 0), (6, 2), (15, 7)):
+        kf = dev_bf16_to_f64(kc[b, :, gk])[:, None]          # [S, 1, kt, D]
+        vf = dev_bf16_to_f64(vc[b, :, gk])[:, None]
+        rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(kf, vf)
+        np.testing.assert_array_equal(k8[b, :, gk].cpu().numpy(), rk8[:, 0])
+        np.testing.assert_array_equal(v8[b, :, gk].cpu().numpy(), rv8[:, 0])
+        np.testing.assert_array_equal(ks[b, :, gk].cpu().numpy(), rks[:, 0])
+        qf = dev_bf16_to_f64(q[b, :, gk * G:(gk + 1) * G])
+        ro, rl = oracle.global_attention_concat(qf, oracle.dequantize_kv_fp8(rk8, rks),
+                                                oracle.dequantize_kv_fp8(rv8, rvs))
+        assert_close(dev_bf16_to_f64(out[b, :, gk * G:(gk + 1) * G]), ro, O_ATOL, O_RTOL, f"fp8 decode out[b={b},g={gk}]")
+        assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"fp8 decode lse[b={b},g={gk}]")
