@@ -258,6 +258,63 @@ def test_chunk_prefill_and_layer(cfg):
         assert_close(dev_bf16_to_f64(layer.global_o[0]), ref["global_o"], O_ATOL, O_RTOL, "global_o (oracle sel)")
 
 
+def test_layer_keeping_everything_is_one_softmax_over_all_chunks():
+    """The degenerate case of the method: every chunk and every token kept.  The global attention
+    of the query block is then one softmax over all rotated context keys and the query's own
+    (the identity behind Eq. 9-11), whatever order the chunks were ranked in."""
+    import dataclasses
+    cfg = dataclasses.replace(CFG1_SMALL, keep_chunks=CFG1_SMALL.n_chunks, keep_tokens=CFG1_SMALL.chunk_len)
+    _say(f"layer keeping everything {cfg.name}")
+    q, k, v = prefill_inputs(cfg)
+    layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads, cfg.n_kv_heads,
+                              cfg.head_dim, cfg.obs_window, cfg.rope_base, cfg.keep_chunks, cfg.keep_tokens)
+    layer.forward(bits_to_dev(q), bits_to_dev(k), bits_to_dev(v))
+    torch.cuda.synchronize()
+    assert sorted(layer.chunk_idx.cpu().tolist()) == list(range(cfg.n_chunks))
+    assert (layer.tok_idx.cpu().numpy() == np.arange(cfg.chunk_len)).all()
+    qf, kf, vf = (bf16_bits_to_f64(x) for x in (q, k, v))
+    w, pos = cfg.chunk_len, np.arange(cfg.seq_len)
+    k_rot = np.stack([oracle.rope(kf[c], pos, cfg.rope_base) for c in range(cfg.n_chunks)])
+    q_rot = oracle.rope(qf[0], pos, cfg.rope_base)[w:]
+    kc = k_rot[:, :w].transpose(0, 2, 1, 3)                   # [C, H_kv, w, D]
+    vc = vf[:, :w].transpose(0, 2, 1, 3)
+    og, lg = oracle.global_attention_concat(q_rot, kc, vc, k_rot[0, w:], vf[0, w:])
+    assert_close(dev_bf16_to_f64(layer.global_o[0]), og, O_ATOL, O_RTOL, "global_o")
+    assert_close(layer.global_lse[0].cpu().numpy().T, lg, LSE_ATOL, 1e-3, "global_lse")
+
+
+@pytest.mark.parametrize("C,w,wq,Hq,Hkv,D,w_obs,kc_n,kt_n", [(1, 1, 1, 1, 1, 64, 1, 1, 1),
+                                                             (3, 65, 3, 2, 1, 128, 2, 2, 64),
+                                                             (2, 127, 130, 4, 4, 64, 64, 1, 127)],
+                         ids=["one-token", "just-over-a-tile", "long-query"])
+def test_layer_tiny_and_ragged_tail_shapes(C, w, wq, Hq, Hkv, D, w_obs, kc_n, kt_n):
+    """Smallest possible shapes and sizes just past a tile boundary, unit-variance entries."""
+    _say(f"tiny layer C={C} w={w} wq={wq} H={Hq}/{Hkv} D={D}")
+    r = np.random.default_rng([16, C, w, wq])
+    L = w + wq
+    mk = lambda h: f32_to_bf16_bits(r.standard_normal((C, L, h, D)).astype(np.float32))
+    q, k, v = mk(Hq), mk(Hkv), mk(Hkv)
+    q[:, w:] = q[0, w:]; k[:, w:] = k[0, w:]; v[:, w:] = v[0, w:]          # same query rows in every chunk
+    qf, kf, vf = (bf16_bits_to_f64(x) for x in (q, k, v))
+    ref = oracle.parallelcomp_layer(qf, kf, vf, w, w_obs, kc_n, kt_n, 1.0e4)
+    layer = ParallelCompLayer(C, w, wq, Hq, Hkv, D, w_obs, 1.0e4, kc_n, kt_n)
+    layer.forward(bits_to_dev(q), bits_to_dev(k), bits_to_dev(v))
+    torch.cuda.synchronize()
+    assert_close(dev_bf16_to_f64(layer.o), ref["o"], O_ATOL, O_RTOL, "o")
+    assert_close(layer.lse.cpu().numpy().transpose(0, 2, 1), ref["lse"], LSE_ATOL, 1e-3, "lse")
+    assert_close(layer.tok_score.cpu().numpy(), ref["tok_score"], S_ATOL, S_RTOL, "tok_score")
+    g_cidx, g_tidx = layer.chunk_idx.cpu().numpy(), layer.tok_idx.cpu().numpy()
+    assert_selection_matches(g_cidx, ref["chunk_idx"], ref["chunk_score"], "chunk selection")
+    ref_tidx = oracle.select_tokens(ref["tok_score"][g_cidx], kt_n)
+    for s_ in range(kc_n):
+        for g in range(Hkv):
+            assert_selection_matches(g_tidx[s_, g], ref_tidx[s_, g], ref["tok_score"][g_cidx[s_], g], "tokens")
+    kc_ref, vc_ref = oracle.gather_kv(ref["k_rope"], vf, g_cidx, g_tidx)
+    og, lg = oracle.global_attention_concat(ref["q_rot_query"], kc_ref, vc_ref, ref["k_rope"][0, w:], vf[0, w:])
+    assert_close(dev_bf16_to_f64(layer.global_o[0]), og, O_ATOL, O_RTOL, "global_o")
+    assert_close(layer.global_lse[0].cpu().numpy().T, lg, LSE_ATOL, 1e-3, "global_lse")
+
+
 def test_chunk_prefill_without_scores_and_without_k_rope_out():
     cfg = CFG1_SMALL
     _say(f"prefill only {cfg.name}")
