@@ -45,13 +45,22 @@ __device__ __forceinline__ void split_bf16x2(float x0, float x1, uint32_t& hi, u
   lo = pack_bf16x2(x0 - bf16_lo_to_f32(hi), x1 - bf16_hi_to_f32(hi));
 }
 
-template <int D, int PASS>
+// WPC = wavefronts per block of 32 columns.  With 4 or more column blocks (a GQA group of 4
+// heads x 32 voting rows) a wavefront owns a column block and takes both 32-key halves of every
+// 64-key tile (WPC = 1).  With fewer column blocks the wavefronts of a block share its keys
+// instead of idling: WPC = 2 splits the halves of a 64-key tile, WPC = 4 (one column block, e.g.
+// MHA with 32 voting rows) the four 32-key quarters of a 128-key tile.
+template <int D, int PASS, int WPC>
 __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a) {
   constexpr int KS = D / 16, HALF = D / 2, KSTRIDE = D + 8;
-  __shared__ __attribute__((aligned(16))) uint16_t k_hi[PC_SC_TILE * KSTRIDE];
-  __shared__ __attribute__((aligned(16))) uint16_t k_lo[PC_SC_TILE * KSTRIDE];
+  constexpr int TILE = WPC == 4 ? 2 * PC_SC_TILE : PC_SC_TILE;   // keys staged in LDS at a time
+  constexpr int NSUB = TILE / 32;                                // 32-key sub-blocks per tile
+  constexpr int CB_PER_ROUND = PC_SC_WAVES / WPC;
+  __shared__ __attribute__((aligned(16))) uint16_t k_hi[TILE * KSTRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t k_lo[TILE * KSTRIDE];
   __shared__ float lse2_lds[512];
   __shared__ float tok_part[PC_SC_WAVES][PC_SC_KB];
+  __shared__ float2 ml_part[PC_SC_WAVES][32];
 
   const int c = blockIdx.x, g = blockIdx.y, kblock = blockIdx.z;
   const int G = a.n_q_heads / a.n_kv_heads;
@@ -72,9 +81,10 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
   if (PASS == 2)
     for (int i = lane; i < PC_SC_KB; i += PC_WAVE) tok_part[wave][i] = 0.f;
 
-  const int n_rounds = (n_cb + PC_SC_WAVES - 1) / PC_SC_WAVES;
+  const int n_rounds = (n_cb + CB_PER_ROUND - 1) / CB_PER_ROUND;
+  const int kb0 = wave % WPC;                      // this wavefront's first sub-block of a tile
   for (int round = 0; round < n_rounds; ++round) {
-    const int cb = round * PC_SC_WAVES + wave;
+    const int cb = round * CB_PER_ROUND + wave / WPC;
     const bool active = cb < n_cb;
     // ---- this lane's column as an MFMA operand: rotate at the row's position, split hi/lo
     const int col = min(32 * cb + n, a.n_cols - 1);
@@ -124,36 +134,45 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
 
     // K tile staging, split in two so that the loads of tile t + 1 are in flight while the
     // matrix cores work on tile t: fetch (global -> registers), stage (rotate in fp32, split
-    // hi / lo, registers -> LDS)
-    constexpr int ITEMS = PC_SC_TILE * (HALF / 8) / PC_SC_THREADS;     // per thread and tile
-    static_assert(ITEMS >= 1 && PC_SC_TILE * (HALF / 8) % PC_SC_THREADS == 0, "tile / thread mismatch");
+    // hi / lo, registers -> LDS).  A thread always handles the same 8 rotation pairs, of rows
+    // RP apart, so it reads (cos, sin) from the table once, for its first row, and turns them by
+    // the constant angle of RP rows from item to item (one complex multiplication per pair in
+    // fp32, at most PC_SC_KB / RP - 1 in a chain: ~1e-7 relative per link).
+    constexpr int ITEMS = TILE * (HALF / 8) / PC_SC_THREADS;           // per thread and tile
+    constexpr int RP = PC_SC_THREADS / (HALF / 8);                     // rows between a thread's items
+    static_assert(ITEMS >= 1 && TILE * (HALF / 8) % PC_SC_THREADS == 0, "tile / thread mismatch");
+    const int st_r0 = tid / (HALF / 8), st_i0 = (tid % (HALF / 8)) * 8;
     uint4 pf_x1[ITEMS], pf_x2[ITEMS];
-    float4 pf_cs[ITEMS][4];
+    float2 cs_cur[8], cs_step[8];
+    {
+      const float4* c4 = (const float4*)(a.table + (long long)min(kblock * PC_SC_KB + st_r0, a.L - 1) * HALF + st_i0);
+      const float4* s4 = (const float4*)(a.table + (long long)min(RP, a.L - 1) * HALF + st_i0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float4 cv = c4[e], sv4 = s4[e];
+        cs_cur[2 * e] = make_float2(cv.x, cv.y); cs_cur[2 * e + 1] = make_float2(cv.z, cv.w);
+        cs_step[2 * e] = make_float2(sv4.x, sv4.y); cs_step[2 * e + 1] = make_float2(sv4.z, sv4.w);
+      }
+    }
     auto fetch = [&](int key0) __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < ITEMS; ++u) {
-        const int it = tid + u * PC_SC_THREADS;
-        const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
-        const int row = min(key0 + r, a.L - 1);
+        const int row = min(key0 + st_r0 + u * RP, a.L - 1);
         const uint16_t* krow = a.k + (((long long)c * a.L + row) * a.n_kv_heads + g) * D;
-        pf_x1[u] = *(const uint4*)(krow + i0);
-        pf_x2[u] = *(const uint4*)(krow + HALF + i0);
-        const float4* cs4 = (const float4*)(a.table + (long long)row * HALF + i0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pf_cs[u][e] = cs4[e];
+        pf_x1[u] = *(const uint4*)(krow + st_i0);
+        pf_x2[u] = *(const uint4*)(krow + HALF + st_i0);
       }
     };
     auto stage = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < ITEMS; ++u) {
-        const int it = tid + u * PC_SC_THREADS;
-        const int r = it / (HALF / 8), i0 = (it % (HALF / 8)) * 8;
+        const int r = st_r0 + u * RP, i0 = st_i0;
         const uint32_t aw[4] = {pf_x1[u].x, pf_x1[u].y, pf_x1[u].z, pf_x1[u].w};
         const uint32_t bw[4] = {pf_x2[u].x, pf_x2[u].y, pf_x2[u].z, pf_x2[u].w};
         uint32_t h1[4], l1[4], h2[4], l2[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float2 c0 = make_float2(pf_cs[u][e].x, pf_cs[u][e].y), c1 = make_float2(pf_cs[u][e].z, pf_cs[u][e].w);
+          const float2 c0 = cs_cur[2 * e], c1 = cs_cur[2 * e + 1];
           const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
           const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
           split_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y, h1[e], l1[e]);
@@ -163,23 +182,31 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         *(uint4*)(k_lo + r * KSTRIDE + i0) = make_uint4(l1[0], l1[1], l1[2], l1[3]);
         *(uint4*)(k_hi + r * KSTRIDE + HALF + i0) = make_uint4(h2[0], h2[1], h2[2], h2[3]);
         *(uint4*)(k_lo + r * KSTRIDE + HALF + i0) = make_uint4(l2[0], l2[1], l2[2], l2[3]);
+        // (cos, sin) of the thread's next row: angle + RP theta
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float cn = cs_cur[e].x * cs_step[e].x - cs_cur[e].y * cs_step[e].y;
+          const float sn = cs_cur[e].y * cs_step[e].x + cs_cur[e].x * cs_step[e].y;
+          cs_cur[e] = make_float2(cn, sn);
+        }
       }
     };
     if (kblock * PC_SC_KB < a.L) fetch(kblock * PC_SC_KB);
 
     // one loop body (not unrolled): leaves room for the prefetch registers
 #pragma unroll 1
-    for (int t = 0; t < PC_SC_KB / PC_SC_TILE; ++t) {
-      const int key0 = kblock * PC_SC_KB + t * PC_SC_TILE;
+    for (int t = 0; t < PC_SC_KB / TILE; ++t) {
+      const int key0 = kblock * PC_SC_KB + t * TILE;
       if (key0 >= a.L) break;                               // uniform over the workgroup
       __syncthreads();                                      // previous tile fully consumed
       stage();
       __syncthreads();
-      if (t + 1 < PC_SC_KB / PC_SC_TILE && key0 + PC_SC_TILE < a.L) fetch(key0 + PC_SC_TILE);
+      if (t + 1 < PC_SC_KB / TILE && key0 + TILE < a.L) fetch(key0 + TILE);
       if (!active) continue;
 
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kq = 0; kq < NSUB / WPC; ++kq) {
+        const int kb = kb0 + kq * WPC;
         floatx16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -224,19 +251,37 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
             sum += (key <= qrow_r[r]) ? p : 0.f;
           }
           sum += __shfl_xor(sum, 32);
-          if (hf == 0) tok_part[wave][t * PC_SC_TILE + 32 * kb + n] += sum;
+          if (hf == 0) tok_part[wave][t * TILE + 32 * kb + n] += sum;
         }
       }
     }
 
-    if (PASS == 1 && active) {
+    if (PASS == 1) {
+      // the lane halves hold disjoint keys of the same column; then the WPC wavefronts of the
+      // column block (disjoint keys again) are combined in wavefront order
       const float m_o = __shfl_xor(m_run, 32), l_o = __shfl_xor(l_run, 32);
-      const float M = fmaxf(m_run, m_o);
+      float M = fmaxf(m_run, m_o);
       float l = 0.f;
       if (l_run > 0.f) l += l_run * exp2f(m_run - M);
       if (l_o > 0.f) l += l_o * exp2f(m_o - M);
+      if (WPC > 1) {
+        if (hf == 0) ml_part[wave][n] = make_float2(M, l);
+        __syncthreads();
+        if (kb0 == 0) {
+          M = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < WPC; ++i) M = fmaxf(M, ml_part[wave + i][n].x);
+          l = 0.f;
+#pragma unroll
+          for (int i = 0; i < WPC; ++i) {
+            const float2 v = ml_part[wave + i][n];
+            if (v.y > 0.f) l += v.y * exp2f(v.x - M);
+          }
+        }
+        __syncthreads();                               // ml_part free for the next round
+      }
       const int cc = 32 * cb + n;
-      if (hf == 0 && cc < a.n_cols)
+      if (active && kb0 == 0 && hf == 0 && cc < a.n_cols)
         a.ml[ml_base + (long long)kblock * a.n_cols + cc] = make_float2(M, l);
     }
   }
@@ -300,6 +345,20 @@ __global__ __launch_bounds__(1024) void chunk_score_kernel(const float* __restri
   if (threadIdx.x == 0) chunk_score[blockIdx.x] = red[0];
 }
 
+template <int PASS>
+static void launch_scores_pass(int head_dim, int wpc, dim3 grid, dim3 block, hipStream_t st,
+                               const PcScoreArgs& a) {
+  if (head_dim == 128) {
+    if (wpc == 4) hipLaunchKernelGGL((scores_kernel<128, PASS, 4>), grid, block, 0, st, a);
+    else if (wpc == 2) hipLaunchKernelGGL((scores_kernel<128, PASS, 2>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((scores_kernel<128, PASS, 1>), grid, block, 0, st, a);
+  } else {
+    if (wpc == 4) hipLaunchKernelGGL((scores_kernel<64, PASS, 4>), grid, block, 0, st, a);
+    else if (wpc == 2) hipLaunchKernelGGL((scores_kernel<64, PASS, 2>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((scores_kernel<64, PASS, 1>), grid, block, 0, st, a);
+  }
+}
+
 size_t pc_scores_ml_bytes(const pc_shape* s) {
   const int L = s->chunk_len + s->query_len;
   const int n_kb = (L + PC_SC_KB - 1) / PC_SC_KB;
@@ -322,10 +381,11 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   a.scale_log2 = scale * PC_SC_LOG2E;
   a.lse2 = (float*)(a.ml + (size_t)s->n_chunks * s->n_kv_heads * a.n_kb * a.n_cols);
   dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
+  const int n_cb = (a.n_cols + 31) / 32;
+  const int wpc = n_cb == 1 ? 4 : (n_cb == 2 ? 2 : 1);
   {
     PcProfScope prof(PC_KERNEL_SCORES_P1, st);
-    if (s->head_dim == 128) hipLaunchKernelGGL((scores_kernel<128, 1>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((scores_kernel<64, 1>), grid, block, 0, st, a);
+    launch_scores_pass<1>(s->head_dim, wpc, grid, block, st, a);
   }
   {
     PcProfScope prof(PC_KERNEL_SCORES_LSE, st);
@@ -334,8 +394,7 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   }
   {
     PcProfScope prof(PC_KERNEL_SCORES_P2, st);
-    if (s->head_dim == 128) hipLaunchKernelGGL((scores_kernel<128, 2>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((scores_kernel<64, 2>), grid, block, 0, st, a);
+    launch_scores_pass<2>(s->head_dim, wpc, grid, block, st, a);
   }
   PC_LAUNCH_CHECK();
   if (chunk_score) {

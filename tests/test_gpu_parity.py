@@ -337,7 +337,7 @@ def test_scores_obs_window_variants():
     qf, kf = bf16_bits_to_f64(q), bf16_bits_to_f64(k)
     qd, kd = bits_to_dev(q), bits_to_dev(k)
     pos = np.arange(cfg.seq_len)
-    for w_obs in (8, 1, 64):
+    for w_obs in (8, 1, 16, 64):        # 1, 1, 2 and 8 blocks of 32 (row, head) columns
         _say(f"scores w_obs={w_obs}")
         shape = pc.make_shape(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
                               cfg.n_kv_heads, cfg.head_dim, w_obs, cfg.rope_base)
