@@ -33,6 +33,13 @@
 #define PC_FA_BM (PC_FA_WAVES * 32 * PC_FA_NB)   // query rows per workgroup
 #define PC_FA_BN 64                  // keys per tile
 #define PC_LOG2E 1.4426950408889634f
+// orders a wavefront's own LDS writes before its own later LDS reads (no other wavefront involved)
+#define PC_FA_WAVE_LDS_SYNC()                                \
+  do {                                                       \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   \
+    __builtin_amdgcn_wave_barrier();                         \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");   \
+  } while (0)
 #define PC_LN2 0.6931471805599453f
 
 // ------------------------------------------------------------------------------------------
@@ -240,23 +247,65 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     const int ld_row = min(my_row[nb], seq_rows - 1);
     const uint16_t* qrow = (const uint16_t*)a.q + (((long long)seq * a.n_rows + ld_row) * a.n_q_heads + h) * D;
     if (ROPE_Q) {
-      const float2* cs = a.table + (long long)(a.q_pos0 + ld_row) * HALF;
+      // The wavefront's 32 query rows and their (cos, sin) table rows are fetched with
+      // coalesced loads (a load instruction covers whole rows, 1 KiB contiguous where the rows
+      // are adjacent) and handed to the lanes that own them through a private, XOR-swizzled
+      // LDS area in the tile buffers, which are still unused at this point.  A gather straight
+      // into the operand layout (every lane its own row) would touch 32 to 64 cache lines per
+      // instruction and costs several microseconds per workgroup.
+      constexpr int PPR = D / 8;                  // 16-byte pieces per query row (and per table half row)
+      constexpr int RPL = PC_WAVE / PPR;          // rows per load instruction
+      constexpr int NLD = 32 / RPL;               // load instructions per 32 rows
+      constexpr int KS_HALF = D / 64;             // ks iterations served by one half of a table row
+      static_assert(NB == 1, "staging area is sized for one row block per wavefront");
+      uint16_t* st_q = smem + wave * (2 * 32 * D);            // 32 rows x D bf16
+      uint16_t* st_t = st_q + 32 * D;                         // 32 half rows of the table (D bytes x 2)
+      const int l_row = lane / PPR, l_piece = lane % PPR;
+      u32x4 rq[NLD], rt[2][NLD];
 #pragma unroll
-      for (int ks = 0; ks < KS / 2; ++ks) {
-        const int i0 = 16 * ks + 8 * hf;          // pair index of the first half
-        const u32x4 x1 = *(const u32x4*)(qrow + i0);
-        const u32x4 x2 = *(const u32x4*)(qrow + HALF + i0);
-        u32x4 ra, rbv;
+      for (int i = 0; i < NLD; ++i) {
+        const int r = RPL * i + l_row;
+        const int grow = min(row0 + 32 * nb + r, seq_rows - 1);
+        rq[i] = *(const u32x4*)((const uint16_t*)a.q + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece);
+        const char* trow = (const char*)(a.table + (long long)(a.q_pos0 + grow) * HALF);
+        rt[0][i] = *(const u32x4*)(trow + 16 * l_piece);
+        rt[1][i] = *(const u32x4*)(trow + 2 * D + 16 * l_piece);
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
-          const float x1l = bf16_lo_to_f32(x1[e]), x1h = bf16_hi_to_f32(x1[e]);
-          const float x2l = bf16_lo_to_f32(x2[e]), x2h = bf16_hi_to_f32(x2[e]);
-          ra[e] = pack_bf16x2((x1l * c0.x - x2l * c0.y) * c_log2, (x1h * c1.x - x2h * c1.y) * c_log2);
-          rbv[e] = pack_bf16x2((x2l * c0.x + x1l * c0.y) * c_log2, (x2h * c1.x + x1h * c1.y) * c_log2);
+      for (int i = 0; i < NLD; ++i) {
+        const int r = RPL * i + l_row;
+        *(u32x4*)(st_q + (r * PPR + (l_piece ^ (r % PPR))) * 8) = rq[i];
+      }
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          const int r = RPL * i + l_row;
+          *(u32x4*)(st_t + (r * PPR + (l_piece ^ (r % PPR))) * 8) = rt[half][i];
         }
-        bq[nb][ks] = *(bf16x8*)&ra;
-        bq[nb][ks + KS / 2] = *(bf16x8*)&rbv;
+        PC_FA_WAVE_LDS_SYNC();
+#pragma unroll
+        for (int kh = 0; kh < KS_HALF; ++kh) {
+          const int ks = half * KS_HALF + kh;
+          const int pq = 2 * ks + hf;                         // piece of the row's first half; + PPR / 2: second half
+          const u32x4 x1 = *(const u32x4*)(st_q + (n * PPR + (pq ^ (n % PPR))) * 8);
+          const u32x4 x2 = *(const u32x4*)(st_q + (n * PPR + ((pq + PPR / 2) ^ (n % PPR))) * 8);
+          u32x4 ra, rbv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int pt = 8 * kh + 4 * hf + e;               // piece e of the lane's 64 bytes of (cos, sin)
+            const u32x4 cw = *(const u32x4*)(st_t + (n * PPR + (pt ^ (n % PPR))) * 8);
+            const float2 c0 = make_float2(__uint_as_float(cw[0]), __uint_as_float(cw[1]));
+            const float2 c1 = make_float2(__uint_as_float(cw[2]), __uint_as_float(cw[3]));
+            const float x1l = bf16_lo_to_f32(x1[e]), x1h = bf16_hi_to_f32(x1[e]);
+            const float x2l = bf16_lo_to_f32(x2[e]), x2h = bf16_hi_to_f32(x2[e]);
+            ra[e] = pack_bf16x2((x1l * c0.x - x2l * c0.y) * c_log2, (x1h * c1.x - x2h * c1.y) * c_log2);
+            rbv[e] = pack_bf16x2((x2l * c0.x + x1l * c0.y) * c_log2, (x2h * c1.x + x1h * c1.y) * c_log2);
+          }
+          bq[nb][ks] = *(bf16x8*)&ra;
+          bq[nb][ks + KS / 2] = *(bf16x8*)&rbv;
+        }
+        PC_FA_WAVE_LDS_SYNC();                                // the table area is rewritten / the tiles move in
       }
     } else {
 #pragma unroll
@@ -519,6 +568,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
 
   if (T > 0) {
     // ---- prologue: tiles 0 and 1 must have landed before the first step; tiles 2, 3 stay in flight
+    if (ROPE_Q) __syncthreads();                   // every wavefront has left its staging area
     load_k(0);
     load_v(0);
     load_k(min(1, T - 1));
