@@ -629,8 +629,8 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     const float l = pc_xhalf_sum(l_run[nb]);
     const float inv_l = l > 0.f ? 1.f / l : 0.f;
     const float lse = l > 0.f ? m_run[nb] * PC_LN2 + logf(l) : -INFINITY;
-    if (my_row[nb] < seq_rows) {
-      if (PARTIAL) {
+    if (PARTIAL) {
+      if (my_row[nb] < seq_rows) {
         const long long prow = ((((long long)seq * a.n_parts_total + a.part0 + part) * a.n_rows) + my_row[nb]) * a.n_q_heads + h;
         float* po = a.part_o + prow * D;
 #pragma unroll
@@ -642,19 +642,37 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
             *(floatx4*)(po + 32 * db + 8 * i + 4 * hf) = x;
           }
         if (hf == 0) a.part_lse[prow] = lse;
-      } else {
-        uint16_t* orow = (uint16_t*)a.o + (((long long)seq * a.n_rows + my_row[nb]) * a.n_q_heads + h) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            uint2 x;
-            x.x = pack_bf16x2(o_acc[nb][db][4 * i] * inv_l, o_acc[nb][db][4 * i + 1] * inv_l);
-            x.y = pack_bf16x2(o_acc[nb][db][4 * i + 2] * inv_l, o_acc[nb][db][4 * i + 3] * inv_l);
-            *(uint2*)(orow + 32 * db + 8 * i + 4 * hf) = x;
-          }
-        if (hf == 0 && a.lse) a.lse[((long long)seq * a.n_q_heads + h) * a.n_rows + my_row[nb]] = lse;
       }
+    } else {
+      // The lane that owns a query holds its output row in 8-byte pieces; stored from there,
+      // an instruction would touch 32 rows.  The rows go through a swizzled staging area in the
+      // K buffers (nobody reads K after the last barrier: the last step has no next S^T) and
+      // leave as whole 16-byte-per-lane rows, 1 KiB per instruction where rows are adjacent.
+      constexpr int PPR = D / 8, RPL = PC_WAVE / PPR, NLD = 32 / RPL;
+      static_assert(NB == 1 && PC_FA_WAVES * 32 * D <= SM::KBUF * SM::K_ELEMS, "staging area is the K buffers");
+      uint16_t* st_o = smem + wave * (32 * D);
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          uint2 x;
+          x.x = pack_bf16x2(o_acc[nb][db][4 * i] * inv_l, o_acc[nb][db][4 * i + 1] * inv_l);
+          x.y = pack_bf16x2(o_acc[nb][db][4 * i + 2] * inv_l, o_acc[nb][db][4 * i + 3] * inv_l);
+          const int p = 4 * db + i;                             // 16-byte piece of the row; half hf of it
+          *(uint2*)(st_o + (n * PPR + (p ^ (n % PPR))) * 8 + 4 * hf) = x;
+        }
+      PC_FA_WAVE_LDS_SYNC();
+      const int l_row = lane / PPR, l_piece = lane % PPR;
+#pragma unroll
+      for (int k = 0; k < NLD; ++k) {
+        const int r = RPL * k + l_row;
+        const u32x4 x = *(const u32x4*)(st_o + (r * PPR + (l_piece ^ (r % PPR))) * 8);
+        const int grow = row0 + 32 * nb + r;
+        if (grow < seq_rows)
+          *(u32x4*)((uint16_t*)a.o + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece) = x;
+      }
+      if (my_row[nb] < seq_rows && hf == 0 && a.lse)
+        a.lse[((long long)seq * a.n_q_heads + h) * a.n_rows + my_row[nb]] = lse;
     }
   }
 }
