@@ -28,9 +28,12 @@ PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
 # counters read for a plain 1 GiB copy (2048 B per FETCH_SIZE count, 1024 B per WRITE_SIZE count);
 # commands and raw counts: profiles/pmc_hbm_traffic.md.  Keyed by (kernel, workload).
 MEASURED_TRAFFIC = {
-    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.6028e6 * 2048 + 1.0667e6 * 1024,
-    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.0981e6 * 2048 + 1.66e4 * 1024,
-    ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1150e6 * 2048 + 4.1943e6 * 1024,
+    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.5974e6 * 2048 + 1.0650e6 * 1024,
+    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.0980e6 * 2048 + 1.66e4 * 1024,
+    ("decode_attn_fp8_kernel", "cfg4_decode_llama3_8b"): 1.0495e6 * 2048 + 1.66e4 * 1024,
+    ("kv_quantize_fp8_kernel", "cfg4_decode_llama3_8b"): 4.1944e6 * 2048 + 2.0975e6 * 1024,
+    ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1149e6 * 2048 + 4.1943e6 * 1024,
+    ("self_info_rows_kernel", "16x512x128256"): 1.0266e6 * 2048,
 }
 
 
@@ -122,7 +125,8 @@ def bench_self_info(pc, torch, steps):
     return {"workload": "16 chunks x 512 query tokens x vocab 128256, bf16 logits",
             "roofline": {"bound": "hbm", "kernel": "self_info_rows_kernel", "achieved": nbytes / avg / 1e9,
                          "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": nbytes / avg / PEAK_HBM_BYTES,
-                         "kernel_ms": avg * 1e3, "traffic": None}}
+                         "kernel_ms": avg * 1e3,
+                         "traffic": MEASURED_TRAFFIC.get(("self_info_rows_kernel", "16x512x128256"))}}
 
 
 def bench_ceilings(pc, torch):
@@ -301,10 +305,12 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
            "tokens_per_s_per_layer": B / dt,
            "roofline": {"bound": "hbm", "kernel": "decode_attn_fp8_kernel", "achieved": kv_bytes / k_avg / 1e9,
                         "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": kv_bytes / k_avg / PEAK_HBM_BYTES,
-                        "kernel_ms": k_avg * 1e3, "traffic": None},
+                        "kernel_ms": k_avg * 1e3,
+                        "traffic": MEASURED_TRAFFIC.get(("decode_attn_fp8_kernel", cfg.name))},
            "quantize": {"bound": "hbm", "kernel": "kv_quantize_fp8_kernel", "achieved": q_bytes / q_avg / 1e9,
                         "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": q_bytes / q_avg / PEAK_HBM_BYTES,
-                        "kernel_ms": q_avg * 1e3, "traffic": None}}
+                        "kernel_ms": q_avg * 1e3,
+                        "traffic": MEASURED_TRAFFIC.get(("kv_quantize_fp8_kernel", cfg.name))}}
     del kc, vc, k8, v8
     torch.cuda.empty_cache()
     return res
