@@ -9,7 +9,7 @@
 // The paper leaves the cache precision open; this format is an extension of this library.
 //
 // kv_quantize_fp8_kernel   one workgroup per (sequence, segment, KV head, K or V): maximum,
-//                          then codes; the second sweep re-reads the 512 KiB segment from L2.
+//                          then codes; the second sweep reads the segment again (5 bytes per element in all).
 // decode_attn_fp8_kernel   the split-KV kernel of decode_attn.hip on 8-bit operands: codes are
 //                          widened in registers (every E4M3 value is exact in bf16), K enters
 //                          the same 16x16x32 bf16 MFMA, the scales are folded into the logit

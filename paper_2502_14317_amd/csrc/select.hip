@@ -58,6 +58,7 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
   extern __shared__ uint32_t keys[];   // n
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sh_bin, sh_need, sh_evicted;
+  __shared__ uint32_t wave_tot[256 / PC_WAVE];
   __shared__ uint32_t wave_gt[PC_SEL_WAVES], wave_eq[PC_SEL_WAVES];
 
   const int s = blockIdx.x / n_kv_heads;
@@ -88,21 +89,44 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (threadIdx.x < 256) hist[threadIdx.x] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += PC_SEL_THREADS) {
-      const uint32_t key = keys[i];
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    // Histogram of the next 8 bits over the keys that still match the prefix.  Scores of one
+    // chunk are close to each other, so in the upper passes nearly all keys of a wavefront fall
+    // into one bin: the lanes that share the first active lane's bin are counted with a ballot
+    // and added once, the others add one each.
+    for (int i0 = 0; i0 < n; i0 += PC_SEL_THREADS) {
+      const int i = i0 + threadIdx.x;
+      const uint32_t key = i < n ? keys[i] : 0u;
+      const bool live = i < n && (key & mask) == prefix;
+      const uint32_t bin = (key >> shift) & 255u;
+      const unsigned long long todo = __ballot(live);
+      if (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t lead_bin = (uint32_t)__shfl((int)bin, leader);
+        const bool with_leader = live && bin == lead_bin;
+        const unsigned long long same = __ballot(with_leader);
+        if ((int)(threadIdx.x % PC_WAVE) == leader) atomicAdd(&hist[lead_bin], (uint32_t)__popcll(same));
+        if (live && !with_leader) atomicAdd(&hist[bin], 1u);
+      }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t above = 0;
-      int b = 255;
-      for (; b > 0; --b) {
-        const uint32_t h = hist[b];
-        if (above + h >= need) break;
-        above += h;
+    // The bin that holds the need-th largest key: every bin's count of keys above it by a
+    // suffix sum over the 256 bins (4 wavefronts x 64 bins), instead of one thread walking them.
+    {
+      const int t = threadIdx.x, ln = t % PC_WAVE;
+      const uint32_t h = t < 256 ? hist[t] : 0u;
+      uint32_t suf = h;                              // inclusive suffix sum inside the wavefront
+#pragma unroll
+      for (int off = 1; off < PC_WAVE; off <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_down((int)suf, off);
+        if (ln + off < PC_WAVE) suf += up;
       }
-      sh_bin = (uint32_t)b;
-      sh_need = need - above;
+      if (t < 256 && ln == 0) wave_tot[t / PC_WAVE] = suf;
+      __syncthreads();
+      if (t < 256) {
+        uint32_t above = suf - h;                    // keys in higher bins
+        for (int w = t / PC_WAVE + 1; w < 256 / PC_WAVE; ++w) above += wave_tot[w];
+        if (h > 0 && above < need && above + h >= need) { sh_bin = (uint32_t)t; sh_need = need - above; }
+      }
     }
     __syncthreads();
     prefix |= sh_bin << shift;
