@@ -9,7 +9,8 @@
 // The paper leaves the cache precision open; this format is an extension of this library.
 //
 // kv_quantize_fp8_kernel   one workgroup per (sequence, segment, KV head, K or V): maximum,
-//                          then codes; the second sweep reads the segment again (5 bytes per element in all).
+//                          then codes; the second sweep reads the segment again (5 bytes per
+//                          element in all).
 // decode_attn_fp8_kernel   the split-KV kernel of decode_attn.hip on 8-bit operands: codes are
 //                          widened in registers (every E4M3 value is exact in bf16), K enters
 //                          the same 16x16x32 bf16 MFMA, the scales are folded into the logit
@@ -34,13 +35,19 @@
 typedef float pc_f2 __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------------------------------
-// Quantisation.  blockIdx.x = (b, s, g), blockIdx.y = 0 (K) or 1 (V).
-__global__ __launch_bounds__(256) void kv_quantize_fp8_kernel(
+// Quantisation.  blockIdx.x = (b, s, g), blockIdx.y = 0 (K) or 1 (V).  The segment is read twice
+// (maximum, then codes): 5 bytes of traffic per element.  1024 threads with 4 loads each in
+// flight keep HBM busy (6.0 TB/s of actual traffic at the decode config); bounding the
+// workgroups per CU so that the segments between the two sweeps would fit the last-level cache
+// measured no gain.
+#define PC_Q8_THREADS 1024
+#define PC_Q8_UNROLL 4
+__global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
     const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     const int32_t* __restrict__ seg_len, int per_head, int n_kv_heads, int k_t, int D,
     uint8_t* __restrict__ k8, uint8_t* __restrict__ v8, float* __restrict__ k_scale,
     float* __restrict__ v_scale) {
-  __shared__ uint32_t red[256 / PC_WAVE];
+  __shared__ uint32_t red[PC_Q8_THREADS / PC_WAVE];
   const long long seg = blockIdx.x;
   const uint16_t* src = (blockIdx.y ? vc : kc) + seg * (long long)k_t * D;
   uint8_t* dst = (blockIdx.y ? v8 : k8) + seg * (long long)k_t * D;
@@ -50,11 +57,19 @@ __global__ __launch_bounds__(256) void kv_quantize_fp8_kernel(
 
   // largest magnitude: bf16 magnitudes order like their 15-bit patterns
   uint32_t amax = 0;
-  for (long long i = threadIdx.x; i < n_valid; i += blockDim.x) {
-    const uint4 x = *(const uint4*)(src + 8 * i);
-    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+  for (long long i0 = 0; i0 < n_valid; i0 += PC_Q8_THREADS * PC_Q8_UNROLL) {
+    uint4 x[PC_Q8_UNROLL];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) amax = max(amax, max(w[e] & 0x7fffu, (w[e] >> 16) & 0x7fffu));
+    for (int u = 0; u < PC_Q8_UNROLL; ++u) {
+      const long long i = i0 + u * PC_Q8_THREADS + threadIdx.x;
+      x[u] = i < n_valid ? *(const uint4*)(src + 8 * i) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < PC_Q8_UNROLL; ++u) {
+      const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) amax = max(amax, max(w[e] & 0x7fffu, (w[e] >> 16) & 0x7fffu));
+    }
   }
 #pragma unroll
   for (int off = PC_WAVE / 2; off > 0; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off));
@@ -62,30 +77,40 @@ __global__ __launch_bounds__(256) void kv_quantize_fp8_kernel(
   __syncthreads();
   amax = 0;
 #pragma unroll
-  for (int w = 0; w < 256 / PC_WAVE; ++w) amax = max(amax, red[w]);
+  for (int w = 0; w < PC_Q8_THREADS / PC_WAVE; ++w) amax = max(amax, red[w]);
   const float fmax_ = __uint_as_float(amax << 16);
   const float scale = fmax_ > 0.f ? fmax_ / PC_E4M3_MAX : 1.0f;
   if (threadIdx.x == 0) scale_out[seg] = scale;
 
-  for (long long i = threadIdx.x; i < n_all; i += blockDim.x) {
-    uint2 code = make_uint2(0u, 0u);
-    if (i < n_valid) {
-      const uint4 x = *(const uint4*)(src + 8 * i);
-      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-      float f[8];
+  for (long long i0 = 0; i0 < n_all; i0 += PC_Q8_THREADS * PC_Q8_UNROLL) {
+    uint4 x[PC_Q8_UNROLL];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        f[2 * e] = fminf(fmaxf(bf16_lo_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
-        f[2 * e + 1] = fminf(fmaxf(bf16_hi_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
-      }
-      uint32_t c0 = 0, c1 = 0;
-      c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], c0, false);
-      c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], c0, true);
-      c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], c1, false);
-      c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], c1, true);
-      code = make_uint2(c0, c1);
+    for (int u = 0; u < PC_Q8_UNROLL; ++u) {
+      const long long i = i0 + u * PC_Q8_THREADS + threadIdx.x;
+      x[u] = i < n_valid ? *(const uint4*)(src + 8 * i) : make_uint4(0, 0, 0, 0);
     }
-    *(uint2*)(dst + 8 * i) = code;
+#pragma unroll
+    for (int u = 0; u < PC_Q8_UNROLL; ++u) {
+      const long long i = i0 + u * PC_Q8_THREADS + threadIdx.x;
+      if (i >= n_all) continue;
+      uint2 code = make_uint2(0u, 0u);              // rows behind the segment's length
+      if (i < n_valid) {
+        const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          f[2 * e] = fminf(fmaxf(bf16_lo_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
+          f[2 * e + 1] = fminf(fmaxf(bf16_hi_to_f32(w[e]) / scale, -PC_E4M3_MAX), PC_E4M3_MAX);
+        }
+        uint32_t c0 = 0, c1 = 0;
+        c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], c0, false);
+        c0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], c0, true);
+        c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], c1, false);
+        c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], c1, true);
+        code = make_uint2(c0, c1);
+      }
+      *(uint2*)(dst + 8 * i) = code;
+    }
   }
 }
 
@@ -96,7 +121,7 @@ int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg
   if (n_segs == 0) return PC_OK;
   if (n_segs > 0x7fffffffLL) return PC_ERR_SHAPE;
   PcProfScope prof(PC_KERNEL_KV_QUANTIZE, st);
-  hipLaunchKernelGGL(kv_quantize_fp8_kernel, dim3((unsigned)n_segs, 2), dim3(256), 0, st,
+  hipLaunchKernelGGL(kv_quantize_fp8_kernel, dim3((unsigned)n_segs, 2), dim3(PC_Q8_THREADS), 0, st,
                      (const uint16_t*)kc, (const uint16_t*)vc, seg_len, seg_len_per_head, n_kv_heads,
                      k_t, head_dim, (uint8_t*)k8, (uint8_t*)v8, k_scale, v_scale);
   PC_LAUNCH_CHECK();
