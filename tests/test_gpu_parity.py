@@ -283,16 +283,18 @@ def test_layer_keeping_everything_is_one_softmax_over_all_chunks():
     assert_close(layer.global_lse[0].cpu().numpy().T, lg, LSE_ATOL, 1e-3, "global_lse")
 
 
-@pytest.mark.parametrize("C,w,wq,Hq,Hkv,D,w_obs,kc_n,kt_n", [(1, 1, 1, 1, 1, 64, 1, 1, 1),
-                                                             (3, 65, 3, 2, 1, 128, 2, 2, 64),
-                                                             (2, 127, 130, 4, 4, 64, 64, 1, 127)],
-                         ids=["one-token", "just-over-a-tile", "long-query"])
-def test_layer_tiny_and_ragged_tail_shapes(C, w, wq, Hq, Hkv, D, w_obs, kc_n, kt_n):
-    """Smallest possible shapes and sizes just past a tile boundary, unit-variance entries."""
-    _say(f"tiny layer C={C} w={w} wq={wq} H={Hq}/{Hkv} D={D}")
+@pytest.mark.parametrize("C,w,wq,Hq,Hkv,D,w_obs,kc_n,kt_n,gain", [(1, 1, 1, 1, 1, 64, 1, 1, 1, 1.0),
+                                                                  (3, 65, 3, 2, 1, 128, 2, 2, 64, 1.0),
+                                                                  (2, 127, 130, 4, 4, 64, 64, 1, 127, 1.0),
+                                                                  (2, 700, 40, 8, 2, 128, 32, 1, 256, 1.25)],
+                         ids=["one-token", "just-over-a-tile", "long-query", "wider-logits"])
+def test_layer_tiny_and_ragged_tail_shapes(C, w, wq, Hq, Hkv, D, w_obs, kc_n, kt_n, gain):
+    """Smallest possible shapes and sizes just past a tile boundary, unit-variance entries; the
+    last case has logits with a standard deviation of 1.6 (q and k entries x 1.25)."""
+    _say(f"tiny layer C={C} w={w} wq={wq} H={Hq}/{Hkv} D={D} gain={gain}")
     r = np.random.default_rng([16, C, w, wq])
     L = w + wq
-    mk = lambda h: f32_to_bf16_bits(r.standard_normal((C, L, h, D)).astype(np.float32))
+    mk = lambda h: f32_to_bf16_bits(r.standard_normal((C, L, h, D)).astype(np.float32) * gain)
     q, k, v = mk(Hq), mk(Hkv), mk(Hkv)
     q[:, w:] = q[0, w:]; k[:, w:] = k[0, w:]; v[:, w:] = v[0, w:]          # same query rows in every chunk
     qf, kf, vf = (bf16_bits_to_f64(x) for x in (q, k, v))
@@ -313,6 +315,41 @@ def test_layer_tiny_and_ragged_tail_shapes(C, w, wq, Hq, Hkv, D, w_obs, kc_n, kt
     og, lg = oracle.global_attention_concat(ref["q_rot_query"], kc_ref, vc_ref, ref["k_rope"][0, w:], vf[0, w:])
     assert_close(dev_bf16_to_f64(layer.global_o[0]), og, O_ATOL, O_RTOL, "global_o")
     assert_close(layer.global_lse[0].cpu().numpy().T, lg, LSE_ATOL, 1e-3, "global_lse")
+
+
+def test_running_softmax_rescale_keeps_output_and_row_sum_consistent():
+    """Logits with a standard deviation of 9 behind 64 nearly silent keys: the reference of the
+    running softmax starts near 0 and is overtaken again and again, so the rare rescale path
+    runs in most steps.  With identical value rows the output must be that row whatever the
+    probabilities are (logits this large are beyond what bf16 operands resolve to the output
+    tolerance, the normalisation is not), so O and the row sum must have been rescaled together."""
+    C, w, wq, Hq, Hkv, D = 2, 700, 40, 8, 2, 128
+    _say(f"rescale consistency C={C} w={w} wq={wq}")
+    r = np.random.default_rng([17])
+    L = w + wq
+    qf = r.standard_normal((C, L, Hq, D)).astype(np.float32) * 3
+    kf = r.standard_normal((C, L, Hkv, D)).astype(np.float32) * 3
+    kf[:, :64] *= 0.01
+    v0 = r.standard_normal((C, 1, Hkv, D)).astype(np.float32)
+    q, k, v = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf), f32_to_bf16_bits(np.repeat(v0, L, axis=1))
+    shape = pc.make_shape(C, w, wq, Hq, Hkv, D, 32, 1.0e4)
+    o = torch.empty((C, L, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((C, Hq, L), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_chunk_prefill_workspace_bytes(shape))
+    pc.pc_chunk_prefill_attn(shape, bits_to_dev(q), bits_to_dev(k), bits_to_dev(v), o, lse, None, None, None, ws)
+    torch.cuda.synchronize()
+    want = np.repeat(bf16_bits_to_f64(v)[:, :, :, None, :], Hq // Hkv, axis=3).reshape(C, L, Hq, D)
+    assert_close(dev_bf16_to_f64(o), want, O_ATOL, O_RTOL, "o with identical value rows")
+    # the row logsumexp against the oracle on sampled rows: a probability-weighted mean of logit
+    # errors, which grow with the logits (2^-8 relative per rounded operand pair)
+    rows = np.array([0, 63, 64, 100, 333, 699, 700, 739])
+    for c in range(C):
+        pos = np.arange(L)
+        q_rot = oracle.rope(bf16_bits_to_f64(q[c]), pos, 1.0e4)
+        k_rot = oracle.rope(bf16_bits_to_f64(k[c]), pos, 1.0e4)
+        _, rl = oracle.local_attention(q_rot, k_rot, bf16_bits_to_f64(v[c]), rows=rows)
+        gl = lse[c].cpu().numpy().T[rows]
+        assert np.all(np.abs(gl - rl) <= 2.0 ** -8 * np.abs(rl) + LSE_ATOL), np.abs(gl - rl).max()
 
 
 def test_chunk_prefill_without_scores_and_without_k_rope_out():
