@@ -610,6 +610,31 @@ def test_fp8_e4m3_decode_closed_forms_and_library_view():
     assert (np.diff(mags) > 0).all()                                          # code order = value order
 
 
+def test_fp8_e4m3_published_format_constants():
+    """tests/golden/e4m3_format_constants.txt: the characteristic values the format's
+    specification prints (bit patterns and values)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "e4m3_format_constants.txt")
+    seen = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, pattern, value = line.split()
+        if pattern == "-":
+            continue
+        code = int(pattern.replace(".", ""), 2)
+        got = oracle.fp8_e4m3_decode([code])[0]
+        if value == "nan":
+            assert np.isnan(got), name
+        else:
+            assert got == float(value) and np.signbit(got) == value.startswith("-"), (name, got)
+            assert oracle.fp8_e4m3_encode([np.float32(value)])[0] == code, name
+        seen += 1
+    assert seen == 7
+    finite = oracle.fp8_e4m3_decode(np.arange(256, dtype=np.uint8))
+    assert np.isfinite(finite).sum() == 254 and not np.isinf(finite).any()      # no infinities, two NaNs
+
+
 def test_fp8_e4m3_encode_round_trip_ties_saturation_and_library_conversion():
     enc, dec = oracle.fp8_e4m3_encode, oracle.fp8_e4m3_decode
     finite = np.array([c for c in range(256) if c & 0x7F != 0x7F], dtype=np.uint8)
