@@ -254,22 +254,40 @@ struct PcMergeArgs {
   float scale;
 };
 
+#define PC_MERGE_MAX_LDS_PARTS 1024      // weights of up to this many partials are kept in LDS
+
 template <int D>
 __global__ __launch_bounds__(D) void merge_kernel(PcMergeArgs a) {
   __shared__ float red[D / PC_WAVE + 1];
   __shared__ float self_s[16];
+  __shared__ float wgt_lds[PC_MERGE_MAX_LDS_PARTS];
   const int d = threadIdx.x;
   int bid = blockIdx.x;
   const int h = bid % a.n_q_heads; bid /= a.n_q_heads;
   const int t = bid % a.n_q;       bid /= a.n_q;
   const int b = bid;
   const int G = a.n_q_heads / a.n_kv_heads, g = h / G;
+  // partial p of this (b, t, h): row = row0 + p * row_stride
+  const long long row0 = ((long long)b * a.n_parts * a.n_q + t) * a.n_q_heads + h;
+  const long long row_stride = (long long)a.n_q * a.n_q_heads;
+  const bool in_lds = a.n_parts <= PC_MERGE_MAX_LDS_PARTS;
 
+  // the partials' logsumexps, one per thread and round (independent loads), and their maximum
   float M = -INFINITY;
-  for (int p = 0; p < a.n_parts; ++p) {
-    const long long row = (((long long)b * a.n_parts + p) * a.n_q + t) * a.n_q_heads + h;
-    M = fmaxf(M, a.part_lse[row]);
+  for (int p = d; p < a.n_parts; p += D) {
+    const float l = a.part_lse[row0 + p * row_stride];
+    if (in_lds) wgt_lds[p] = l;
+    M = fmaxf(M, l);
   }
+#pragma unroll
+  for (int off = PC_WAVE / 2; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if (d % PC_WAVE == 0) red[d / PC_WAVE] = M;
+  __syncthreads();
+  M = red[0];
+#pragma unroll
+  for (int w = 1; w < D / PC_WAVE; ++w) M = fmaxf(M, red[w]);
+  __syncthreads();                                           // red is reused below
+
   // self segment (only launched with n_q <= 16): logits of keys 0..t
   const bool has_self = a.k_self != nullptr;
   if (has_self) {
@@ -291,11 +309,24 @@ __global__ __launch_bounds__(D) void merge_kernel(PcMergeArgs a) {
   }
   float num = 0.f, den = 0.f;
   if (M > -INFINITY) {
-    for (int p = 0; p < a.n_parts; ++p) {
-      const long long row = (((long long)b * a.n_parts + p) * a.n_q + t) * a.n_q_heads + h;
-      const float wgt = expf(a.part_lse[row] - M);
-      num += wgt * a.part_o[row * D + d];
-      den += wgt;
+    // weights exp(lse_p - M): computed once per partial and kept in LDS; every thread then sums
+    // them in the same (partial) order, so all threads hold the same denominator
+    if (in_lds) {
+      for (int p = d; p < a.n_parts; p += D) wgt_lds[p] = expf(wgt_lds[p] - M);
+      __syncthreads();
+    }
+    constexpr int U = 8;                                     // independent loads in flight per thread
+    for (int p0 = 0; p0 < a.n_parts; p0 += U) {
+      float w[U], x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int p = min(p0 + u, a.n_parts - 1);
+        w[u] = in_lds ? wgt_lds[p] : expf(a.part_lse[row0 + p * row_stride] - M);
+        x[u] = a.part_o[(row0 + p * row_stride) * D + d];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (p0 + u < a.n_parts) { num += w[u] * x[u]; den += w[u]; }
     }
     if (has_self) {
       for (int j = 0; j <= t; ++j) {
