@@ -104,12 +104,12 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
       const int row = min(key0 + 16 * bi + c16, len - 1);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks)
-        kbuf[buf][bi][ks] = *(const uint4*)(kseg + (long long)row * D + 32 * ks + 8 * kk);
+        kbuf[buf][bi][ks] = pc_load_once((const uint4*)(kseg + (long long)row * D + 32 * ks + 8 * kk));
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
       const int row = min(key0 + RPI * i + v_row, len - 1);
-      vbuf[buf][i] = *(const uint4*)(vseg + (long long)row * D + 8 * v_piece);
+      vbuf[buf][i] = pc_load_once((const uint4*)(vseg + (long long)row * D + 8 * v_piece));
     }
   };
 

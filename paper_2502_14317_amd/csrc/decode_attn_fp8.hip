@@ -222,12 +222,12 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
       const int row = min(key0 + 16 * bi + c16, len - 1);
 #pragma unroll
       for (int i = 0; i < KQ; ++i)
-        kbuf[buf][bi][i] = *(const uint4*)(kseg + (long long)row * D + 64 * i + 16 * kk);
+        kbuf[buf][bi][i] = pc_load_once((const uint4*)(kseg + (long long)row * D + 64 * i + 16 * kk));
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
       const int row = min(key0 + RPI * i + v_row, len - 1);
-      vbuf[buf][i] = *(const uint4*)(vseg + (long long)row * D + 16 * v_piece);
+      vbuf[buf][i] = pc_load_once((const uint4*)(vseg + (long long)row * D + 16 * v_piece));
     }
   };
 

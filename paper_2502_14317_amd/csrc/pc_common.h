@@ -56,6 +56,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return *(uint32_t*)&r;
 }
 
+// 16-byte global load / store of data that is touched once (streamed): the non-temporal hint
+// keeps it from displacing reusable lines in the caches
+__device__ __forceinline__ uint4 pc_load_once(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void pc_store_once(uint4* p, uint4 x) {
+  const u32x4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, (u32x4*)p);
+}
+
 // Exchange between lane l and lane l ^ 32 without going through LDS: v_permlane32_swap leaves
 // the low half's values in both halves of the first result and the high half's in the second.
 __device__ __forceinline__ float pc_xhalf_max(float x) {
