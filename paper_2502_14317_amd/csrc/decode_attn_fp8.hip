@@ -87,7 +87,7 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
 #pragma unroll
     for (int u = 0; u < PC_Q8_UNROLL; ++u) {
       const long long i = i0 + u * PC_Q8_THREADS + threadIdx.x;
-      x[u] = i < n_valid ? *(const uint4*)(src + 8 * i) : make_uint4(0, 0, 0, 0);
+      x[u] = i < n_valid ? pc_load_once((const uint4*)(src + 8 * i)) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < PC_Q8_UNROLL; ++u) {
@@ -109,7 +109,8 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
         c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], c1, true);
         code = make_uint2(c0, c1);
       }
-      *(uint2*)(dst + 8 * i) = code;
+      __builtin_nontemporal_store(code.x, (uint32_t*)(dst + 8 * i));
+      __builtin_nontemporal_store(code.y, (uint32_t*)(dst + 8 * i) + 1);
     }
   }
 }

@@ -66,6 +66,8 @@ __device__ __forceinline__ void pc_store_once(uint4* p, uint4 x) {
   const u32x4 v = {x.x, x.y, x.z, x.w};
   __builtin_nontemporal_store(v, (u32x4*)p);
 }
+__device__ __forceinline__ u32x4 pc_load_once(const u32x4* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void pc_store_once(u32x4* p, u32x4 x) { __builtin_nontemporal_store(x, p); }
 
 // Exchange between lane l and lane l ^ 32 without going through LDS: v_permlane32_swap leaves
 // the low half's values in both halves of the first result and the high half's in the second.

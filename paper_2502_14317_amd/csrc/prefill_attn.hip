@@ -95,8 +95,8 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
     uint4 oa = make_uint4(0, 0, 0, 0), ob = make_uint4(0, 0, 0, 0);
     if (row < L) {
       const long long off = ((seq_base + row) * n_kv_heads + g) * D;
-      const uint4 a = *(const uint4*)(k + off + i0);
-      const uint4 b = *(const uint4*)(k + off + HALF + i0);
+      const uint4 a = pc_load_once((const uint4*)(k + off + i0));
+      const uint4 b = pc_load_once((const uint4*)(k + off + HALF + i0));
       if (table != nullptr) {
         const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
         uint32_t ra[4], rb[4];
@@ -115,13 +115,13 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
         oa = a; ob = b;
       }
       if (k_rope != nullptr) {
-        *(uint4*)(k_rope + off + i0) = oa;
-        *(uint4*)(k_rope + off + HALF + i0) = ob;
+        pc_store_once((uint4*)(k_rope + off + i0), oa);
+        pc_store_once((uint4*)(k_rope + off + HALF + i0), ob);
       }
     }
     if (k_img != nullptr) {
-      *(uint4*)(k_img + img + ((i0 / 8) * 64 + r) * 8) = oa;
-      *(uint4*)(k_img + img + (((HALF + i0) / 8) * 64 + r) * 8) = ob;
+      pc_store_once((uint4*)(k_img + img + ((i0 / 8) * 64 + r) * 8), oa);
+      pc_store_once((uint4*)(k_img + img + (((HALF + i0) / 8) * 64 + r) * 8), ob);
     }
   }
 
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
     const int r = it / (D / 8), c8 = (it % (D / 8)) * 8;
     const int row = row0 + r;
     uint4 x = make_uint4(0, 0, 0, 0);
-    if (row < L) x = *(const uint4*)(v + ((seq_base + row) * n_kv_heads + g) * D + c8);
+    if (row < L) x = pc_load_once((const uint4*)(v + ((seq_base + row) * n_kv_heads + g) * D + c8));
     uint32_t* dst = (uint32_t*)(v_lds + r * VSTRIDE + c8);   // 4-byte aligned: VSTRIDE, c8 even
     dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
   }
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
       const uint32_t hi = v_lds[(8 * c + 2 * e + 1) * VSTRIDE + d];
       w[e] = lo | (hi << 16);
     }
-    *(uint4*)(v_img + img + (c * D + d) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    pc_store_once((uint4*)(v_img + img + (c * D + d) * 8), make_uint4(w[0], w[1], w[2], w[3]));
   }
 }
 
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
       for (int i = 0; i < NLD; ++i) {
         const int r = RPL * i + l_row;
         const int grow = min(row0 + 32 * nb + r, seq_rows - 1);
-        rq[i] = *(const u32x4*)((const uint16_t*)a.q + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece);
+        rq[i] = pc_load_once((const u32x4*)((const uint16_t*)a.q + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece));
         const char* trow = (const char*)(a.table + (long long)(a.q_pos0 + grow) * HALF);
         rt[0][i] = *(const u32x4*)(trow + 16 * l_piece);
         rt[1][i] = *(const u32x4*)(trow + 2 * D + 16 * l_piece);
@@ -669,7 +669,7 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
         const u32x4 x = *(const u32x4*)(st_o + (r * PPR + (l_piece ^ (r % PPR))) * 8);
         const int grow = row0 + 32 * nb + r;
         if (grow < seq_rows)
-          *(u32x4*)((uint16_t*)a.o + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece) = x;
+          pc_store_once((u32x4*)((uint16_t*)a.o + (((long long)seq * a.n_rows + grow) * a.n_q_heads + h) * D + 8 * l_piece), x);
       }
       if (my_row[nb] < seq_rows && hf == 0 && a.lse)
         a.lse[((long long)seq * a.n_q_heads + h) * a.n_rows + my_row[nb]] = lse;

@@ -159,8 +159,8 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
       for (int u = 0; u < ITEMS; ++u) {
         const int row = min(key0 + st_r0 + u * RP, a.L - 1);
         const uint16_t* krow = a.k + (((long long)c * a.L + row) * a.n_kv_heads + g) * D;
-        pf_x1[u] = *(const uint4*)(krow + st_i0);
-        pf_x2[u] = *(const uint4*)(krow + HALF + st_i0);
+        pf_x1[u] = pc_load_once((const uint4*)(krow + st_i0));
+        pf_x2[u] = pc_load_once((const uint4*)(krow + HALF + st_i0));
       }
     };
     auto stage = [&]() __attribute__((always_inline)) {
