@@ -444,10 +444,15 @@ static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStre
   return PC_OK;
 }
 
-int pc_decode_keys_per_wg(int k_t) {
-  // 1024 keys per workgroup (256 per wavefront); short segments use one workgroup each.
-  int kpw = 1024;
+int pc_decode_keys_per_wg(int k_t, long long n_groups) {
+  // A workgroup streams up to 2048 keys of one (sequence, KV head, segment) group: the longer
+  // its run, the smaller the share of its start-up and of its partial result (at the decode
+  // config 2048 keys per workgroup reach 80 % of the HBM peak, 1024 reach 75 %, 256 reach 68 %).
+  // Short segments use one workgroup each, and the runs are halved while the launch would have
+  // fewer than four workgroups per CU of a 256-CU part.
+  int kpw = 2048;
   while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && kpw / 2 >= k_t) kpw /= 2;
+  while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && n_groups * ((k_t + kpw - 1) / kpw) < 1024) kpw /= 2;
   return kpw;
 }
 
@@ -460,7 +465,7 @@ int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const in
   a.q = (const uint16_t*)q_rot; a.kc = (const uint16_t*)kc; a.vc = (const uint16_t*)vc;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  a.keys_per_wg = pc_decode_keys_per_wg(k_t);
+  a.keys_per_wg = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
   a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_DEC_LOG2E;

@@ -392,7 +392,7 @@ int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, cons
   a.k_scale = k_scale; a.v_scale = v_scale;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  a.keys_per_wg = pc_decode_keys_per_wg(k_t);
+  a.keys_per_wg = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
   a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_D8_LOG2E;

@@ -231,13 +231,14 @@ struct Par8Ws {
   int n_parts, parts8;
 };
 
-static Par8Ws par8_ws_layout(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads, int D) {
+static Par8Ws par8_ws_layout(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads,
+                             int n_kv_heads, int D) {
   Par8Ws w;
-  const int kpw = pc_decode_keys_per_wg(k_t);
+  const int kpw = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
   w.parts8 = n_seg * ((k_t + kpw - 1) / kpw);
   w.n_parts = w.parts8;
   if (tail_cap > 0) {
-    const int kpt = pc_decode_keys_per_wg(tail_cap);
+    const int kpt = pc_decode_keys_per_wg(tail_cap, (long long)batch * n_kv_heads);
     w.n_parts += (tail_cap + kpt - 1) / kpt;
   }
   size_t off = 0;
@@ -265,7 +266,7 @@ extern "C" size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_
                                                        int32_t n_q_heads, int32_t n_kv_heads,
                                                        int32_t head_dim) {
   if (check_par8(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim) != PC_OK) return 0;
-  return par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, head_dim).total;
+  return par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim).total;
 }
 
 extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v8,
@@ -287,7 +288,7 @@ extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v
   if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
   if (n_seg > 0 && (!pc_aligned(k8, 16) || !pc_aligned(v8, 16))) return PC_ERR_SHAPE;
   const int D = head_dim;
-  const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, D);
+  const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, D);
   if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
@@ -389,7 +390,7 @@ static ParWs par_ws_layout(int batch, int n_q, int n_seg, int k_t, int n_q_heads
   w.ktp = (k_t + 63) / 64 * 64;
   w.nqp = (n_q + 63) / 64 * 64;
   if (w.small) {
-    const int kpw = pc_decode_keys_per_wg(k_t);
+    const int kpw = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
     w.n_parts = n_seg * ((k_t + kpw - 1) / kpw);
   } else {
     w.n_parts = n_seg + (has_self ? 1 : 0);

@@ -147,7 +147,7 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
                      int pos0, float base, hipStream_t st);
-int pc_decode_keys_per_wg(int k_t);
+int pc_decode_keys_per_wg(int k_t, long long n_groups);   // n_groups = batch * H_kv * segments
 int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_new, int n_seg,
                         int seg, int k_t, int n_kv_heads, int head_dim, int pos0, float base,
                         void* kc, void* vc, int32_t* seg_len, int seg_len_per_head,
