@@ -144,12 +144,14 @@ struct PcDecode8Args {
   float scale_log2;       // softmax scale * log2(e)
 };
 
-// four E4M3 codes of one 32-bit word -> two packed bf16 pairs (exact)
+// four E4M3 codes of one 32-bit word -> two packed bf16 pairs (exact: every E4M3 value is a bf16
+// value), one conversion instruction per pair (the scaled form with scale 1)
+typedef __bf16 pc_bf2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void pc_e4m3x4_to_bf16(uint32_t w, uint32_t& lo, uint32_t& hi) {
-  const pc_f2 a = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
-  const pc_f2 b = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
-  lo = pack_bf16x2(a.x, a.y);
-  hi = pack_bf16x2(b.x, b.y);
+  const pc_bf2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  const pc_bf2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
+  lo = *(const uint32_t*)&a;
+  hi = *(const uint32_t*)&b;
 }
 
 template <int D, int NQ>

@@ -157,6 +157,35 @@ def test_fp8_decode_steps_match_oracle():
         assert_close(gl, rl, LSE_ATOL, 1e-3, f"fp8 decode steps lse[b={b}]")
 
 
+def test_fp8_dequantisation_is_exact_for_every_code():
+    """One key per segment and scale 1: the output is the key's value row and, with unit-vector
+    queries and softmax scale 1, the row logsumexp is one element of the key.  Every finite code
+    (subnormals included) must come out as the value the format defines."""
+    _say("fp8 attention: every code exact")
+    codes = np.arange(256, dtype=np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0                       # the two NaN codes
+    vals = oracle.fp8_e4m3_decode(codes)
+    D, Hq = 128, 8
+    one = torch.ones((1, 1, 1), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 1, 1, 0, Hq, 1, D))
+    out = torch.empty((1, 1, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((1, Hq, 1), dtype=torch.float32, device="cuda")
+    for half in range(2):
+        row = torch.from_numpy(codes[128 * half:128 * half + 128].copy()).cuda().view(1, 1, 1, 1, D)
+        for d0 in range(0, D, Hq):
+            q = np.zeros((1, 1, Hq, D), dtype=np.float32)
+            for h in range(Hq):
+                q[0, 0, h, d0 + h] = 1.0
+            pc.pc_parallel_attn_fp8(bits_to_dev(f32_to_bf16_bits(q)), row, row, one, one, None, None, None, None, 0,
+                                    1, 1, 1, 1, Hq, 1, D, -1, 1.0e4, 1.0, out, lse, ws)
+            torch.cuda.synchronize()
+            want = vals[128 * half:128 * half + 128]
+            got_lse = lse[0, :, 0].cpu().numpy().astype(np.float64)
+            np.testing.assert_allclose(got_lse, want[d0:d0 + Hq], rtol=1e-6, atol=1e-12)
+            if d0 == 0:                                      # p = 1: the output is the value row, bit for bit
+                np.testing.assert_array_equal(dev_bf16_to_f64(out[0, 0]), np.broadcast_to(want, (Hq, D)))
+
+
 def test_fp8_attention_rejects_many_query_columns():
     one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(pc.PcError) as e:
