@@ -34,6 +34,7 @@ struct PcDecodeArgs {
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
   int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
+  int seg_per_wg;         // consecutive segments streamed by one workgroup (1 if n_split > 1)
   int part0;              // index of this launch's first partial among the n_parts
   float scale_log2;       // softmax scale * log2(e)
 };
@@ -56,24 +57,44 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   const int lane = threadIdx.x % PC_WAVE, wave = threadIdx.x / PC_WAVE;
   const int kk = lane / 16, c16 = lane % 16;
 
+  const int n_sgroups = (a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg;
   int bid = blockIdx.x;
   const int split = bid % a.n_split; bid /= a.n_split;
-  const int s = bid % a.n_seg;       bid /= a.n_seg;
+  const int sg = bid % n_sgroups;    bid /= n_sgroups;
   const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
   const int b = bid;
+  const int s_first = sg * a.seg_per_wg, s_last = min(a.n_seg, s_first + a.seg_per_wg);
 
-  const int len_idx = a.seg_len_per_head ? (b * a.n_seg + s) * a.n_kv_heads + g : b * a.n_seg + s;
-  const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
-  const long long seg_base = ((((long long)b * a.n_seg + s) * a.n_kv_heads + g) * a.k_t) * D;
-  const uint16_t* kseg = a.kc + seg_base;
-  const uint16_t* vseg = a.vc + seg_base;
-
-  // keys of this wavefront: [w_begin, w_end)
-  const int wg_begin = split * a.keys_per_wg;
-  const int wg_end = min(len, wg_begin + a.keys_per_wg);
+  // A wavefront streams its quarter of the workgroup's key range of every segment of the group,
+  // one segment after the other; the running softmax carries over (same query columns, same KV
+  // head), so a workgroup leaves one partial for all its segments.  A cursor names the next
+  // 32-key block: segment, first key, the segment's base pointers, length and range end.
+  struct Cursor { int s, key0, len, w_end; const uint16_t* k; const uint16_t* v; bool valid; };
   const int per_wave = a.keys_per_wg / PC_DEC_WAVES;      // multiple of PC_DEC_ITER_KEYS
-  const int w_begin = wg_begin + wave * per_wave;
-  const int w_end = min(wg_end, w_begin + per_wave);
+  auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
+    Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
+    for (; s < s_last; ++s) {
+      const int len_idx = a.seg_len_per_head ? (b * a.n_seg + s) * a.n_kv_heads + g : b * a.n_seg + s;
+      const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
+      const int wg_begin = split * a.keys_per_wg;
+      const int wg_end = min(len, wg_begin + a.keys_per_wg);
+      const int w_begin = wg_begin + wave * per_wave;
+      const int w_end = min(wg_end, w_begin + per_wave);
+      if (w_begin < w_end) {
+        const long long seg_base = ((((long long)b * a.n_seg + s) * a.n_kv_heads + g) * a.k_t) * D;
+        c.valid = true; c.s = s; c.key0 = w_begin; c.len = len; c.w_end = w_end;
+        c.k = a.kc + seg_base; c.v = a.vc + seg_base;
+        break;
+      }
+    }
+    return c;
+  };
+  auto next = [&](const Cursor& c) {
+    Cursor n = c;
+    n.key0 += PC_DEC_ITER_KEYS;
+    if (n.key0 >= c.w_end) n = seek(c.s + 1);
+    return n;
+  };
 
   // B operand: column c16 = (t, head-in-group); lane holds d = 32*ks + 8*kk .. +7
   bf16x8 bq[KSTEPS];
@@ -98,22 +119,23 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   const int v_row = lane / LPR, v_piece = lane % LPR;
 
   uint4 kbuf[2][KBLK][KSTEPS], vbuf[2][VLOADS];
-  auto issue_loads = [&](int buf, int key0) {
+  auto issue_loads = [&](int buf, const Cursor& c) {
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi) {
-      const int row = min(key0 + 16 * bi + c16, len - 1);
+      const int row = min(c.key0 + 16 * bi + c16, c.len - 1);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks)
-        kbuf[buf][bi][ks] = pc_load_once((const uint4*)(kseg + (long long)row * D + 32 * ks + 8 * kk));
+        kbuf[buf][bi][ks] = pc_load_once((const uint4*)(c.k + (long long)row * D + 32 * ks + 8 * kk));
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
-      const int row = min(key0 + RPI * i + v_row, len - 1);
-      vbuf[buf][i] = pc_load_once((const uint4*)(vseg + (long long)row * D + 8 * v_piece));
+      const int row = min(c.key0 + RPI * i + v_row, c.len - 1);
+      vbuf[buf][i] = pc_load_once((const uint4*)(c.v + (long long)row * D + 8 * v_piece));
     }
   };
 
-  auto consume = [&](int buf, int key0) {
+  auto consume = [&](int buf, const Cursor& cur) {
+    const int key0 = cur.key0, w_end = cur.w_end;
     // S^T block: keys x columns
     floatx4 acc[KBLK];
 #pragma unroll
@@ -180,18 +202,20 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
     PC_WAVE_LDS_SYNC();
   };
 
-  if (w_begin < w_end) {
-    issue_loads(0, w_begin);
-    int key0 = w_begin;
+  Cursor cur = seek(s_first);
+  if (cur.valid) {
+    issue_loads(0, cur);
     while (true) {
-      if (key0 + PC_DEC_ITER_KEYS < w_end) issue_loads(1, key0 + PC_DEC_ITER_KEYS);
-      consume(0, key0);
-      key0 += PC_DEC_ITER_KEYS;
-      if (key0 >= w_end) break;
-      if (key0 + PC_DEC_ITER_KEYS < w_end) issue_loads(0, key0 + PC_DEC_ITER_KEYS);
-      consume(1, key0);
-      key0 += PC_DEC_ITER_KEYS;
-      if (key0 >= w_end) break;
+      Cursor nx = next(cur);
+      if (nx.valid) issue_loads(1, nx);
+      consume(0, cur);
+      if (!nx.valid) break;
+      cur = nx;
+      nx = next(cur);
+      if (nx.valid) issue_loads(0, nx);
+      consume(1, cur);
+      if (!nx.valid) break;
+      cur = nx;
     }
   }
 
@@ -217,7 +241,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   __syncthreads();
 
   // ---- merge the 4 wavefronts, write one partial per workgroup
-  const int part = a.part0 + s * a.n_split + split;
+  const int part = a.part0 + sg * a.n_split + split;
   for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
     const int n = idx / D, d = idx % D;
     float M = -INFINITY;
@@ -432,7 +456,7 @@ int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_n
 
 template <int D>
 static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStream_t st) {
-  const long long blocks = (long long)batch * a.n_kv_heads * a.n_seg * a.n_split;
+  const long long blocks = (long long)batch * a.n_kv_heads * ((a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg) * a.n_split;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(PC_DEC_WAVES * PC_WAVE);
@@ -444,16 +468,32 @@ static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStre
   return PC_OK;
 }
 
-int pc_decode_keys_per_wg(int k_t, long long n_groups) {
-  // A workgroup streams up to 2048 keys of one (sequence, KV head, segment) group: the longer
-  // its run, the smaller the share of its start-up and of its partial result (at the decode
-  // config 2048 keys per workgroup reach 80 % of the HBM peak, 1024 reach 75 %, 256 reach 68 %).
-  // Short segments use one workgroup each, and the runs are halved while the launch would have
-  // fewer than four workgroups per CU of a 256-CU part.
+PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg) {
+  // A workgroup streams up to 2048 keys of one (sequence, KV head, segment): the longer its run,
+  // the smaller the share of its start-up and of its partial result (at the decode config 256 /
+  // 1024 / 2048 keys per workgroup reach 68 / 75 / 80.5 % of the HBM peak).  Short segments use
+  // one workgroup each, and the runs are halved while the launch would have fewer than four
+  // workgroups per CU of a 256-CU part.  Where a segment fits one workgroup, a workgroup takes
+  // two or four consecutive segments under one running softmax (one partial for all of them):
+  // at the decode config 1 / 2 / 4 segments per workgroup reach 76 / 80 / 83 % on one machine.
+  PcDecodeSplit d;
+  const long long n_groups = n_bg * n_seg;
   int kpw = 2048;
   while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && kpw / 2 >= k_t) kpw /= 2;
   while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && n_groups * ((k_t + kpw - 1) / kpw) < 1024) kpw /= 2;
-  return kpw;
+  d.keys_per_wg = kpw;
+  d.n_split = (k_t + kpw - 1) / kpw;
+  d.seg_per_wg = 1;
+  if (d.n_split == 1) {
+    // workgroups at 2 and 4 segments each; 512 = resident workgroups of a 256-CU part (2 per CU)
+    const long long wgs2 = n_bg * ((n_seg + 1) / 2), wgs4 = n_bg * ((n_seg + 3) / 4);
+    if (wgs2 >= 2048) d.seg_per_wg = 2;
+    // 4 only where the launch still fills the part evenly: whole rounds of resident workgroups,
+    // or so many rounds that a ragged last one does not matter
+    if (d.seg_per_wg == 2 && wgs4 >= 1024 && (wgs4 % 512 == 0 || wgs4 >= 4096)) d.seg_per_wg = 4;
+  }
+  d.n_parts = ((n_seg + d.seg_per_wg - 1) / d.seg_per_wg) * d.n_split;
+  return d;
 }
 
 int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const int32_t* seg_len,
@@ -465,8 +505,8 @@ int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const in
   a.q = (const uint16_t*)q_rot; a.kc = (const uint16_t*)kc; a.vc = (const uint16_t*)vc;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  a.keys_per_wg = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
-  a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;
+  const PcDecodeSplit sp = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads);
+  a.keys_per_wg = sp.keys_per_wg; a.n_split = sp.n_split; a.seg_per_wg = sp.seg_per_wg;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_DEC_LOG2E;
   const int cols = n_q * (n_q_heads / n_kv_heads);

@@ -141,6 +141,7 @@ struct PcDecode8Args {
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
   int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
+  int seg_per_wg;         // consecutive segments streamed by one workgroup (1 if n_split > 1)
   float scale_log2;       // softmax scale * log2(e)
 };
 
@@ -173,25 +174,48 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   const int lane = threadIdx.x % PC_WAVE, wave = threadIdx.x / PC_WAVE;
   const int kk = lane / 16, c16 = lane % 16;
 
+  const int n_sgroups = (a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg;
   int bid = blockIdx.x;
   const int split = bid % a.n_split; bid /= a.n_split;
-  const int s = bid % a.n_seg;       bid /= a.n_seg;
+  const int sg = bid % n_sgroups;    bid /= n_sgroups;
   const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
   const int b = bid;
+  const int s_first = sg * a.seg_per_wg, s_last = min(a.n_seg, s_first + a.seg_per_wg);
 
-  const long long seg_id = ((long long)b * a.n_seg + s) * a.n_kv_heads + g;
-  const int len_idx = a.seg_len_per_head ? (int)seg_id : b * a.n_seg + s;
-  const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
-  const uint8_t* kseg = a.k8 + seg_id * a.k_t * D;
-  const uint8_t* vseg = a.v8 + seg_id * a.k_t * D;
-  const float k_sc = a.k_scale[seg_id] * a.scale_log2;     // logits in log2 units
-  const float v_sc = a.v_scale[seg_id];
-
-  const int wg_begin = split * a.keys_per_wg;
-  const int wg_end = min(len, wg_begin + a.keys_per_wg);
+  // A wavefront streams its quarter of the workgroup's key range of every segment of the group,
+  // one segment after the other, under one running softmax (one partial per workgroup).  A
+  // cursor names the next 32-key block: segment, first key, base pointers, length, range end
+  // and the segment's scales (K: folded into the logit scale; V: applied to the probabilities
+  // that multiply the codes, not to the row sum).
+  struct Cursor { int s, key0, len, w_end; const uint8_t* k; const uint8_t* v; float k_sc, v_sc; bool valid; };
   const int per_wave = a.keys_per_wg / PC_D8_WAVES;        // multiple of PC_D8_ITER_KEYS
-  const int w_begin = wg_begin + wave * per_wave;
-  const int w_end = min(wg_end, w_begin + per_wave);
+  auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
+    Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
+    c.k_sc = 0.f; c.v_sc = 0.f;
+    for (; s < s_last; ++s) {
+      const long long seg_id = ((long long)b * a.n_seg + s) * a.n_kv_heads + g;
+      const int len_idx = a.seg_len_per_head ? (int)seg_id : b * a.n_seg + s;
+      const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
+      const int wg_begin = split * a.keys_per_wg;
+      const int wg_end = min(len, wg_begin + a.keys_per_wg);
+      const int w_begin = wg_begin + wave * per_wave;
+      const int w_end = min(wg_end, w_begin + per_wave);
+      if (w_begin < w_end) {
+        c.valid = true; c.s = s; c.key0 = w_begin; c.len = len; c.w_end = w_end;
+        c.k = a.k8 + seg_id * a.k_t * D; c.v = a.v8 + seg_id * a.k_t * D;
+        c.k_sc = a.k_scale[seg_id] * a.scale_log2;         // logits in log2 units
+        c.v_sc = a.v_scale[seg_id];
+        break;
+      }
+    }
+    return c;
+  };
+  auto next = [&](const Cursor& c) {
+    Cursor n = c;
+    n.key0 += PC_D8_ITER_KEYS;
+    if (n.key0 >= c.w_end) n = seek(c.s + 1);
+    return n;
+  };
 
   // B operand: column c16 = (t, head-in-group); k-step j of lane group kk covers
   // d = 64 (j / 2) + 16 kk + 8 (j % 2) .. + 7, the bytes the lane loads of its K rows (load i of
@@ -219,7 +243,10 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
 
   // three register buffers: the loads of two iterations (2 x 8 KiB per wavefront) stay in flight
   uint4 kbuf[3][KBLK][KQ], vbuf[3][VLOADS];
-  auto issue_loads = [&](int buf, int key0) {
+  auto issue_loads = [&](int buf, const Cursor& c) {
+    const int key0 = c.key0, len = c.len;
+    const uint8_t* kseg = c.k;
+    const uint8_t* vseg = c.v;
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi) {
       const int row = min(key0 + 16 * bi + c16, len - 1);
@@ -234,7 +261,9 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
     }
   };
 
-  auto consume = [&](int buf, int key0) {
+  auto consume = [&](int buf, const Cursor& cur) {
+    const int key0 = cur.key0, w_end = cur.w_end;
+    const float k_sc = cur.k_sc, v_sc = cur.v_sc;
     floatx4 acc[KBLK];
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi) {
@@ -273,7 +302,7 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
       for (int j = 0; j < 4; ++j) {
         const float p = __builtin_amdgcn_exp2f(sv[bi][j] - m_new);
         psum += p;
-        if (c16 < NQ) p_lds[wave][16 * bi + 4 * kk + j][c16] = p;
+        if (c16 < NQ) p_lds[wave][16 * bi + 4 * kk + j][c16] = p * v_sc;
       }
     l_run = l_run * alpha + psum;
     const bool moved = __any(alpha != 1.0f);         // some column's maximum grew (rare after the first keys)
@@ -309,21 +338,23 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
     PC_D8_WAVE_LDS_SYNC();
   };
 
-  if (w_begin < w_end) {
-    issue_loads(0, w_begin);
-    if (w_begin + PC_D8_ITER_KEYS < w_end) issue_loads(1, w_begin + PC_D8_ITER_KEYS);
-    auto iter = [&](int cur, int fill, int key0) __attribute__((always_inline)) {
-      if (key0 + 2 * PC_D8_ITER_KEYS < w_end) issue_loads(fill, key0 + 2 * PC_D8_ITER_KEYS);
-      consume(cur, key0);
+  // three register buffers: the loads of two blocks (2 x 8 KiB per wavefront) stay in flight
+  Cursor c0 = seek(s_first);
+  if (c0.valid) {
+    Cursor c1 = next(c0);
+    issue_loads(0, c0);
+    if (c1.valid) issue_loads(1, c1);
+    auto iter = [&](int cur_buf, int fill_buf) __attribute__((always_inline)) {
+      // c0 = block to consume (in cur_buf), c1 = the block after it (already in flight)
+      Cursor c2 = c1.valid ? next(c1) : c1;
+      if (c2.valid) issue_loads(fill_buf, c2);
+      consume(cur_buf, c0);
+      c0 = c1; c1 = c2;
     };
-    int key0 = w_begin;
     while (true) {
-      iter(0, 2, key0); key0 += PC_D8_ITER_KEYS;
-      if (key0 >= w_end) break;
-      iter(1, 0, key0); key0 += PC_D8_ITER_KEYS;
-      if (key0 >= w_end) break;
-      iter(2, 1, key0); key0 += PC_D8_ITER_KEYS;
-      if (key0 >= w_end) break;
+      iter(0, 2); if (!c0.valid) break;
+      iter(1, 0); if (!c0.valid) break;
+      iter(2, 1); if (!c0.valid) break;
     }
   }
 
@@ -349,7 +380,7 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   __syncthreads();
 
   // ---- merge the 4 wavefronts, write one partial per workgroup (values scaled back)
-  const int part = s * a.n_split + split;
+  const int part = sg * a.n_split + split;
   for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
     const int n = idx / D, d = idx % D;
     float M = -INFINITY;
@@ -366,14 +397,14 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
     }
     const int t = n / G, hg = n % G;
     const long long row = (((long long)b * a.n_parts + part) * a.n_q + t) * a.n_q_heads + g * G + hg;
-    a.part_o[row * D + d] = (den > 0.f) ? num / den * v_sc : 0.f;
+    a.part_o[row * D + d] = (den > 0.f) ? num / den : 0.f;
     if (d == 0) a.part_lse[row] = (den > 0.f) ? (M + log2f(den)) * 0.6931471805599453f : -INFINITY;
   }
 }
 
 template <int D>
 static int launch_decode8_d(const PcDecode8Args& a, int batch, int nq_pad, hipStream_t st) {
-  const long long blocks = (long long)batch * a.n_kv_heads * a.n_seg * a.n_split;
+  const long long blocks = (long long)batch * a.n_kv_heads * ((a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg) * a.n_split;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(PC_D8_WAVES * PC_WAVE);
@@ -394,8 +425,8 @@ int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, cons
   a.k_scale = k_scale; a.v_scale = v_scale;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  a.keys_per_wg = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
-  a.n_split = (k_t + a.keys_per_wg - 1) / a.keys_per_wg;
+  const PcDecodeSplit sp = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads);
+  a.keys_per_wg = sp.keys_per_wg; a.n_split = sp.n_split; a.seg_per_wg = sp.seg_per_wg;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_D8_LOG2E;
   const int cols = n_q * (n_q_heads / n_kv_heads);

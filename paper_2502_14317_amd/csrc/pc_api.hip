@@ -234,13 +234,9 @@ struct Par8Ws {
 static Par8Ws par8_ws_layout(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads,
                              int n_kv_heads, int D) {
   Par8Ws w;
-  const int kpw = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
-  w.parts8 = n_seg * ((k_t + kpw - 1) / kpw);
+  w.parts8 = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
   w.n_parts = w.parts8;
-  if (tail_cap > 0) {
-    const int kpt = pc_decode_keys_per_wg(tail_cap, (long long)batch * n_kv_heads);
-    w.n_parts += (tail_cap + kpt - 1) / kpt;
-  }
+  if (tail_cap > 0) w.n_parts += pc_decode_split(tail_cap, 1, (long long)batch * n_kv_heads).n_parts;
   size_t off = 0;
   const size_t rows = (size_t)batch * n_q * n_q_heads;
   w.q_rot = off;    off = pc_align_up(off + rows * D * 2, kAlign);
@@ -390,8 +386,7 @@ static ParWs par_ws_layout(int batch, int n_q, int n_seg, int k_t, int n_q_heads
   w.ktp = (k_t + 63) / 64 * 64;
   w.nqp = (n_q + 63) / 64 * 64;
   if (w.small) {
-    const int kpw = pc_decode_keys_per_wg(k_t, (long long)batch * n_kv_heads * n_seg);
-    w.n_parts = n_seg * ((k_t + kpw - 1) / kpw);
+    w.n_parts = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
   } else {
     w.n_parts = n_seg + (has_self ? 1 : 0);
   }

@@ -147,7 +147,9 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
                      int pos0, float base, hipStream_t st);
-int pc_decode_keys_per_wg(int k_t, long long n_groups);   // n_groups = batch * H_kv * segments
+// how the split-KV decode kernels cut the keys into workgroups (n_bg = batch * H_kv)
+struct PcDecodeSplit { int keys_per_wg, n_split, seg_per_wg, n_parts; };
+PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg);
 int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_new, int n_seg,
                         int seg, int k_t, int n_kv_heads, int head_dim, int pos0, float base,
                         void* kc, void* vc, int32_t* seg_len, int seg_len_per_head,
