@@ -186,6 +186,12 @@ def test_fp8_dequantisation_is_exact_for_every_code():
                 np.testing.assert_array_equal(dev_bf16_to_f64(out[0, 0]), np.broadcast_to(want, (Hq, D)))
 
 
+def test_fp8_attention_many_ragged_groups():
+    """Enough groups that a workgroup takes several consecutive 8-bit segments, each with its own
+    scales and a ragged length."""
+    _attn_case("many-groups", 64, 1, 8, 48, 16, 8, 64, 0, -1, True, 5)
+
+
 def test_fp8_attention_rejects_many_query_columns():
     one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(pc.PcError) as e:

@@ -176,6 +176,32 @@ def test_parallel_attn_decode_ragged_self_rope():
     _parallel_attn_case("decode-self-only", 1, 3, 0, 64, 4, 2, 64, True, -1, False, 5)
 
 
+def test_parallel_attn_decode_many_ragged_groups():
+    """Enough (sequence, KV head, segment) groups that a workgroup takes several consecutive
+    segments, with ragged lengths (empty segments in the middle and at the end of a group)."""
+    B, S, kt, Hq, Hkv, D = 64, 8, 48, 16, 8, 64
+    _say(f"parallel_attn many groups: B={B} S={S} kt={kt} H={Hq}/{Hkv} D={D}")
+    r = np.random.default_rng([15, 99])
+    mk = lambda shape, sc=1.0: f32_to_bf16_bits((r.standard_normal(shape) * sc).astype(np.float32))
+    q, kc, vc = mk((B, 1, Hq, D), 3.0), mk((B, S, Hkv, kt, D)), mk((B, S, Hkv, kt, D))
+    seg_len = r.integers(0, kt + 1, size=(B, S)).astype(np.int32)
+    seg_len[0] = [kt, 0, 0, 5, 0, kt, 0, 0]
+    seg_len[1] = [0, 0, 0, 0, 0, 0, 0, 1]
+    seg_len[2] = 0                                           # nothing to attend to: zeros, lse = -inf
+    out = torch.empty((B, 1, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(B, 1, S, kt, Hq, Hkv, D, 0))
+    pc.pc_parallel_attn(bits_to_dev(q), bits_to_dev(kc), bits_to_dev(vc), torch.from_numpy(seg_len).cuda(), None, None,
+                        B, 1, S, kt, Hq, Hkv, D, -1, 1.0e4, 0.0, out, lse, ws)
+    torch.cuda.synchronize()
+    assert (dev_bf16_to_f64(out[2]) == 0).all() and torch.isneginf(lse[2]).all()
+    for b in (0, 1, 3, 17, 63):
+        ro, rl = oracle.global_attention_concat(bf16_bits_to_f64(q[b]), bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]),
+                                                seg_len=seg_len[b])
+        assert_close(dev_bf16_to_f64(out[b]), ro, O_ATOL, O_RTOL, f"out[b={b}]")
+        assert_close(lse[b].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"lse[b={b}]")
+
+
 def test_parallel_attn_query_block():
     _parallel_attn_case("block", 1, 104, 3, 200, 8, 2, 128, True, 600, False, 6)
     _parallel_attn_case("block-ragged64", 2, 300, 2, 130, 4, 4, 64, True, -1, True, 7)
