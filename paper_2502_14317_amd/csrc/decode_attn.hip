@@ -70,6 +70,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   // head), so a workgroup leaves one partial for all its segments.  A cursor names the next
   // 32-key block: segment, first key, the segment's base pointers, length and range end.
   struct Cursor { int s, key0, len, w_end; const uint16_t* k; const uint16_t* v; bool valid; };
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wavefront-uniform: cursors live in scalar registers
   const int per_wave = a.keys_per_wg / PC_DEC_WAVES;      // multiple of PC_DEC_ITER_KEYS
   auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
     Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
       const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
       const int wg_begin = split * a.keys_per_wg;
       const int wg_end = min(len, wg_begin + a.keys_per_wg);
-      const int w_begin = wg_begin + wave * per_wave;
+      const int w_begin = wg_begin + wave_u * per_wave;
       const int w_end = min(wg_end, w_begin + per_wave);
       if (w_begin < w_end) {
         const long long seg_base = ((((long long)b * a.n_seg + s) * a.n_kv_heads + g) * a.k_t) * D;

@@ -188,6 +188,7 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   // and the segment's scales (K: folded into the logit scale; V: applied to the probabilities
   // that multiply the codes, not to the row sum).
   struct Cursor { int s, key0, len, w_end; const uint8_t* k; const uint8_t* v; float k_sc, v_sc; bool valid; };
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wavefront-uniform: cursors live in scalar registers
   const int per_wave = a.keys_per_wg / PC_D8_WAVES;        // multiple of PC_D8_ITER_KEYS
   auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
     Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
       const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
       const int wg_begin = split * a.keys_per_wg;
       const int wg_end = min(len, wg_begin + a.keys_per_wg);
-      const int w_begin = wg_begin + wave * per_wave;
+      const int w_begin = wg_begin + wave_u * per_wave;
       const int w_end = min(wg_end, w_begin + per_wave);
       if (w_begin < w_end) {
         c.valid = true; c.s = s; c.key0 = w_begin; c.len = len; c.w_end = w_end;
