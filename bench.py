@@ -29,8 +29,8 @@ PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
 # commands and raw counts: profiles/pmc_hbm_traffic.md.  Keyed by (kernel, workload).
 MEASURED_TRAFFIC = {
     ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.2551e6 * 2048 + 1.0650e6 * 1024,
-    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.1041e6 * 2048 + 8.4e3 * 1024,
-    ("decode_attn_fp8_kernel", "cfg4_decode_llama3_8b"): 1.0536e6 * 2048 + 8.4e3 * 1024,
+    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.1032e6 * 2048 + 2.1e3 * 1024,
+    ("decode_attn_fp8_kernel", "cfg4_decode_llama3_8b"): 1.0518e6 * 2048 + 2.1e3 * 1024,
     ("kv_quantize_fp8_kernel", "cfg4_decode_llama3_8b"): 4.1805e6 * 2048 + 2.0974e6 * 1024,
     ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1136e6 * 2048 + 4.1944e6 * 1024,
     ("self_info_rows_kernel", "16x512x128256"): 1.0266e6 * 2048,
