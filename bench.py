@@ -316,6 +316,42 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
     return res
 
 
+def bench_other_config(pc, torch, name, steps=3, warmup=1):
+    """The same step on another of the five workloads (fewer steps): whole path where the
+    config has an eviction, chunk prefill + scores where it has none (the 512K stress config)."""
+    import numpy as np
+    from paper_2502_14317_amd.layer import ParallelCompLayer
+    from workloads import PREFILL_CONFIGS, prefill_inputs
+    cfg = PREFILL_CONFIGS[name]
+    prefill_only = cfg.keep_chunks == 0
+    q, k, v = prefill_inputs(cfg, threads=min(16, os.cpu_count() or 8))
+    to_dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    del q, k, v
+    layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads, cfg.n_kv_heads,
+                              cfg.head_dim, cfg.obs_window, cfg.rope_base,
+                              0 if prefill_only else cfg.keep_chunks, cfg.keep_tokens)
+    step = (lambda: layer.chunk_prefill(qd, kd, vd, True)) if prefill_only else (lambda: layer.forward(qd, kd, vd))
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    pc.pc_profile_end()
+    fl = [ms for n, ms in pc.pc_profile_records() if n == "flash_fwd_kernel"]
+    fl = fl[0::len(fl) // steps]
+    flash_avg = sum(fl) / len(fl) * 1e-3
+    del layer, qd, kd, vd
+    torch.cuda.empty_cache()
+    return {"step": "chunk prefill + scores" if prefill_only else "whole path", "ms_per_step": dt * 1e3,
+            "tokens_per_s_per_layer": cfg.context_tokens / dt, "flash_kernel_ms": flash_avg * 1e3,
+            "flash_frac_of_bf16_mfma_peak": flash_flops(cfg) / flash_avg / PEAK_BF16_FLOPS}
+
+
 def bench_secondary(pc, torch, steps, warmup):
     """HBM-bound kernels on the decode config: split-KV attention + merge, and the KV gather."""
     from workloads import CFG4
@@ -492,6 +528,9 @@ def main():
         torch.cuda.empty_cache()
         result["secondary"] = bench_secondary(pc, torch, max(args.steps, 5), args.warmup)
         result["self_information"] = bench_self_info(pc, torch, max(args.steps, 5))
+        if args.workload == "cfg1_llama3_8b_128k":
+            result["other_configs"] = {n: bench_other_config(pc, torch, n) for n in
+                                       ("cfg0_tiny_mha", "cfg2_llama2_7b_128k", "cfg3_llama3_8b_512k_stress")}
         result["ceilings"] = bench_ceilings(pc, torch)
         print(f"[bench] secondary done; ceilings {result['ceilings']}", file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:
