@@ -516,6 +516,19 @@ def main():
                      "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(("flash_fwd_kernel", cfg.name))},
         "kernel_ms_per_step": breakdown,
     }
+    # the same step recorded once into a HIP graph and replayed (no per-launch host work)
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        step()
+    gr.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        gr.replay()
+    torch.cuda.synchronize()
+    result["graph_replay"] = {"ms_per_step": (time.perf_counter() - t0) / args.steps * 1e3,
+                              "tokens_per_s_per_layer": cfg.context_tokens / ((time.perf_counter() - t0) / args.steps)}
+    del gr
     if not prefill_only:
         result["calibration"] = bench_calibration(pc, torch, cfg, layer, qd, vd, max(args.steps, 5))
         result["streaming"] = bench_streaming(torch, cfg, qd, kd, vd, max(args.steps // 2, 3))
