@@ -476,17 +476,26 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    pc.pc_profile_begin()
+    # Timed region: only the roofline kernel's launches are bracketed by HIP events (on the
+    # launch stream, inside the library); bracketing all fourteen kernels of a step costs the
+    # step 0.19 ms of event records.  The per-kernel breakdown comes from a second, untimed pass.
+    pc.pc_profile_begin("flash_fwd_kernel")
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     pc.pc_profile_end()
-    recs = pc.pc_profile_records()
+    flash_all = [ms for name, ms in pc.pc_profile_records() if name == "flash_fwd_kernel"]
+    pc.pc_profile_begin()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
     per_kernel = {}
-    for name, ms in recs:
+    for name, ms in pc.pc_profile_records():
         per_kernel.setdefault(name, []).append(ms)
+    per_kernel["flash_fwd_kernel"] = flash_all
     # flash_fwd_kernel runs once per step for the local attention and (full path) twice more in
     # the global attention; the local-attention launch is the first one of every step
     n_flash = len(per_kernel["flash_fwd_kernel"]) // args.steps

@@ -253,6 +253,9 @@ typedef enum pc_kernel_id {
   PC_KERNEL_COUNT = 17
 } pc_kernel_id;
 int         pc_profile_begin(void);
+int         pc_profile_begin_kernel(int kernel_id);   /* as pc_profile_begin, but only the launches of one
+                                                        kernel are bracketed (two event records per kernel
+                                                        cost about 7 us of stream time each) */
 int         pc_profile_end(void);
 int         pc_profile_count(void);
 int         pc_profile_get(int i, int* kernel_id, float* ms);

@@ -23,6 +23,7 @@ SYMBOLS = [
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
     "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
+    "pc_profile_begin_kernel",
 ]
 
 
@@ -235,8 +236,16 @@ def pc_parallel_attn_fp8(q, k8, v8, k_scale, v_scale, seg_len, k_tail, v_tail, t
                                       _ptr(out), _ptr(lse_out), p, n, _stream()), "pc_parallel_attn_fp8")
 
 
-def pc_profile_begin():
-    _check(lib().pc_profile_begin(), "pc_profile_begin")
+def pc_profile_begin(kernel=None):
+    """Start recording per-kernel durations; kernel = a kernel's name: only its launches."""
+    if kernel is None:
+        _check(lib().pc_profile_begin(), "pc_profile_begin")
+        return
+    L = lib()
+    ids = [i for i in range(64) if L.pc_kernel_name(i).decode() == kernel]
+    if not ids:
+        raise ValueError(f"unknown kernel {kernel!r}")
+    _check(L.pc_profile_begin_kernel(ids[0]), "pc_profile_begin_kernel")
 
 
 def pc_profile_end():

@@ -25,6 +25,7 @@ extern "C" const char* pc_status_string(int status) {
 // ---------------------------------------------------------------------------- profiling
 #define PC_PROF_MAX 4096
 static bool g_prof_on = false;
+static int g_prof_only = -1;          // kernel id to record, -1 = every kernel
 static int g_prof_n = 0;
 static int g_prof_created = 0;
 static hipEvent_t g_prof_ev[PC_PROF_MAX][2];
@@ -32,6 +33,7 @@ static int g_prof_id[PC_PROF_MAX];
 
 PcProfScope::PcProfScope(int kernel_id, hipStream_t stream) : slot(-1), st(stream) {
   if (!g_prof_on || g_prof_n >= PC_PROF_MAX) return;
+  if (g_prof_only >= 0 && kernel_id != g_prof_only) return;
   if (g_prof_n >= g_prof_created) {
     if (hipEventCreate(&g_prof_ev[g_prof_n][0]) != hipSuccess) return;
     if (hipEventCreate(&g_prof_ev[g_prof_n][1]) != hipSuccess) return;
@@ -45,7 +47,12 @@ PcProfScope::~PcProfScope() {
   if (slot >= 0) (void)hipEventRecord(g_prof_ev[slot][1], st);
 }
 
-extern "C" int pc_profile_begin(void) { g_prof_n = 0; g_prof_on = true; return PC_OK; }
+extern "C" int pc_profile_begin(void) { g_prof_n = 0; g_prof_only = -1; g_prof_on = true; return PC_OK; }
+extern "C" int pc_profile_begin_kernel(int kernel_id) {
+  if (kernel_id < 0 || kernel_id >= PC_KERNEL_COUNT) return PC_ERR_SHAPE;
+  g_prof_n = 0; g_prof_only = kernel_id; g_prof_on = true;
+  return PC_OK;
+}
 extern "C" int pc_profile_end(void) { g_prof_on = false; return PC_OK; }
 extern "C" int pc_profile_count(void) { return g_prof_n; }
 extern "C" int pc_profile_get(int i, int* kernel_id, float* ms) {
