@@ -129,14 +129,35 @@ def bench_self_info(pc, torch, steps):
                          "traffic": MEASURED_TRAFFIC.get(("self_info_rows_kernel", "16x512x128256"))}}
 
 
+def bench_flash_zero_operands(pc, torch, cfg, layer, qd, kd, vd, steps):
+    """The roofline kernel on all-zero inputs: same instructions, same schedule, but no bits
+    toggle, so the shader clock stays at its maximum.  The difference to the timed run on the
+    workload's data is what the power limit costs; what is left to the peak is the schedule's."""
+    zq, zk, zv = torch.zeros_like(qd), torch.zeros_like(kd), torch.zeros_like(vd)
+    layer.chunk_prefill(zq, zk, zv, False)
+    torch.cuda.synchronize()
+    pc.pc_profile_begin("flash_fwd_kernel")
+    for _ in range(steps):
+        layer.chunk_prefill(zq, zk, zv, False)
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    ms = [m for name, m in pc.pc_profile_records() if name == "flash_fwd_kernel"]
+    avg = sum(ms) / len(ms) * 1e-3
+    del zq, zk, zv
+    return {"kernel_ms": avg * 1e3, "achieved": flash_flops(cfg) / avg / 1e12, "unit": "TFLOP/s",
+            "frac_of_peak": flash_flops(cfg) / avg / PEAK_BF16_FLOPS}
+
+
 def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
-    power-limited), and a plain device copy."""
+    power-limited), the same loop with attention's per-MFMA LDS operand read and softmax element
+    added (the power-limited ceiling of a flash-attention instruction mix), and a plain device copy."""
     n_cus = torch.cuda.get_device_properties(0).multi_processor_count
     scratch = torch.empty((n_cus * 512,), dtype=torch.float32, device="cuda")
     out = {}
-    for name, rnd in (("mfma_constant_operands", 0), ("mfma_random_operands", 1)):
+    for name, rnd in (("mfma_constant_operands", 0), ("mfma_random_operands", 1),
+                      ("mfma_random_operands_attention_mix", 2)):
         best = 0.0
         for rep in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -544,6 +565,7 @@ def main():
     result["graph_replay"] = {"ms_per_step": (time.perf_counter() - t0) / args.steps * 1e3,
                               "tokens_per_s_per_layer": cfg.context_tokens / ((time.perf_counter() - t0) / args.steps)}
     del gr
+    result["flash_zero_operands"] = bench_flash_zero_operands(pc, torch, cfg, layer, qd, kd, vd, max(args.steps // 2, 3))
     if not prefill_only:
         result["calibration"] = bench_calibration(pc, torch, cfg, layer, qd, vd, max(args.steps, 5))
         result["streaming"] = bench_streaming(torch, cfg, qd, kd, vd, max(args.steps // 2, 3))

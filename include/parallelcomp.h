@@ -262,13 +262,17 @@ int         pc_profile_get(int i, int* kernel_id, float* ms);
 const char* pc_kernel_name(int kernel_id);
 
 /* ---- matrix-pipe ceiling (measurement aid) ---------------------------------------------------
- * Enqueues a kernel that does nothing but independent 32x32x16 bf16 MFMAs: n_cus workgroups of 8
- * wavefronts (two per SIMD), iters x 8 MFMAs each, on constant (random_operands = 0) or random
- * operands.  scratch (device, >= n_cus * 512 * 4 bytes) receives one float per lane so the work
- * cannot be optimised away.  *flops (host) receives the floating-point operations the launch
- * performs; the caller times the launch on its stream and divides.  Returns PC_ERR_NULL /
- * PC_ERR_SHAPE (n_cus outside 1..4096, iters outside 1..2^22) / PC_ERR_WORKSPACE / PC_ERR_HIP. */
-int pc_mfma_ceiling(int random_operands, int n_cus, int iters, float* scratch, size_t scratch_bytes,
+ * Enqueues a kernel built around independent 32x32x16 bf16 MFMAs: n_cus workgroups of 8
+ * wavefronts (two per SIMD), iters x 8 MFMAs each.  mode 0: nothing but MFMAs on constant
+ * operands; mode 1: the same on random operands (more bits toggle, the power-limited clock falls);
+ * mode 2: random operands plus, per MFMA, one 16-byte-per-lane LDS read feeding the A operand and
+ * one softmax element on the vector ALU (exponential, add, multiply), the instruction mix of a
+ * flash-attention loop at 32 queries per wavefront.  scratch (device, >= n_cus * 512 * 4 bytes)
+ * receives one float per lane so the work cannot be optimised away.  *flops (host) receives the
+ * MFMA floating-point operations the launch performs; the caller times the launch on its stream
+ * and divides.  Returns PC_ERR_NULL / PC_ERR_SHAPE (mode outside 0..2, n_cus outside 1..4096,
+ * iters outside 1..2^22) / PC_ERR_WORKSPACE / PC_ERR_HIP. */
+int pc_mfma_ceiling(int mode, int n_cus, int iters, float* scratch, size_t scratch_bytes,
                     double* flops, void* stream);
 
 /* ---- housekeeping -------------------------------------------------------------------------- */

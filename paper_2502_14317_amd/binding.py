@@ -252,10 +252,12 @@ def pc_profile_end():
     _check(lib().pc_profile_end(), "pc_profile_end")
 
 
-def pc_mfma_ceiling(random_operands, n_cus, iters, scratch):
-    """Enqueue the MFMA-only ceiling kernel; returns the flops of the launch (time it outside)."""
+def pc_mfma_ceiling(mode, n_cus, iters, scratch):
+    """Enqueue the MFMA ceiling kernel (mode 0 constant operands, 1 random operands, 2 random
+    operands with attention's LDS-read and softmax work); returns the MFMA flops of the launch
+    (time it outside)."""
     flops = ctypes.c_double(0.0)
-    _check(lib().pc_mfma_ceiling(int(bool(random_operands)), n_cus, iters, _ptr(scratch),
+    _check(lib().pc_mfma_ceiling(int(mode), n_cus, iters, _ptr(scratch),
                                  scratch.numel() * scratch.element_size(), ctypes.byref(flops),
                                  _stream()), "pc_mfma_ceiling")
     return flops.value
