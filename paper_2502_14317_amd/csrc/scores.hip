@@ -9,7 +9,9 @@
 // into bf16 hi + lo parts, and q.k = hi.hi + hi.lo + lo.hi (three MFMAs; the lo.lo term is
 // below 2^-16 relative).
 //
-// Two passes over the keys, both fully parallel over 256-key blocks:
+// Two passes over the keys, both fully parallel over key blocks of 256 to 1024 keys (the largest
+// block that still leaves every CU several workgroups: a workgroup's start-up, rotating and
+// splitting its query columns, is then spread over more keys):
 //   pass 1  (S^T = K Q^T, a lane owns a voting row)  per-block running max / sum of every
 //           voting row -> workspace [c, g, key block, column] (m, l)
 //   between the passes a small kernel combines the blocks' (m, l) into the row logsumexp
@@ -22,7 +24,8 @@
 
 #define PC_SC_THREADS 256
 #define PC_SC_WAVES 4
-#define PC_SC_KB 256        // keys per workgroup
+#define PC_SC_KB 256        // keys per workgroup: the smallest block (sizes the workspace)
+#define PC_SC_KB_MAX 1024   // the largest
 #define PC_SC_TILE 64       // keys staged in LDS at a time
 #define PC_SC_LOG2E 1.4426950408889634f
 
@@ -35,7 +38,8 @@ struct PcScoreArgs {
   float* lse2;             // workspace [C, H_kv, n_cols] row logsumexp in log2 units
   float* tok_score;        // [C, H_kv, w]
   int L, w, w_obs, n_q_heads, n_kv_heads, n_kb, n_cols;
-  float scale_log2;
+  int kb_keys;             // keys per workgroup: 256, 512 or 1024 (at most 512 when WPC == 4)
+  float scale_log2;        // softmax scale x log2(e), folded into the query operand
 };
 
 // (x0, x1) -> packed bf16 pair of the values and packed bf16 pair of the rounding remainders
@@ -59,7 +63,8 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
   __shared__ __attribute__((aligned(16))) uint16_t k_hi[TILE * KSTRIDE];
   __shared__ __attribute__((aligned(16))) uint16_t k_lo[TILE * KSTRIDE];
   __shared__ float lse2_lds[512];
-  __shared__ float tok_part[PC_SC_WAVES][PC_SC_KB];
+  constexpr int KB_CAP = WPC == 4 ? PC_SC_KB_MAX / 2 : PC_SC_KB_MAX;   // LDS: two workgroups per CU
+  __shared__ float tok_part[PC_SC_WAVES][PASS == 2 ? KB_CAP : 1];
   __shared__ float2 ml_part[PC_SC_WAVES][32];
 
   const int c = blockIdx.x, g = blockIdx.y, kblock = blockIdx.z;
@@ -79,7 +84,7 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
 
   // pass 2: every wavefront accumulates its columns' share of the keys' sums in its own LDS row
   if (PASS == 2)
-    for (int i = lane; i < PC_SC_KB; i += PC_WAVE) tok_part[wave][i] = 0.f;
+    for (int i = lane; i < a.kb_keys; i += PC_WAVE) tok_part[wave][i] = 0.f;
 
   const int n_rounds = (n_cb + CB_PER_ROUND - 1) / CB_PER_ROUND;
   const int kb0 = wave % WPC;                      // this wavefront's first sub-block of a tile
@@ -105,8 +110,9 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
           const float2 c0 = cs[i0 + 2 * e], c1 = cs[i0 + 2 * e + 1];
           const float x1l = bf16_lo_to_f32(aw[e]), x1h = bf16_hi_to_f32(aw[e]);
           const float x2l = bf16_lo_to_f32(bw[e]), x2h = bf16_hi_to_f32(bw[e]);
-          split_bf16x2(x1l * c0.x - x2l * c0.y, x1h * c1.x - x2h * c1.y, h1[e], l1[e]);
-          split_bf16x2(x2l * c0.x + x1l * c0.y, x2h * c1.x + x1h * c1.y, h2[e], l2[e]);
+          // logits come out of the matrix cores in log2 units: the scale rides on q
+          split_bf16x2((x1l * c0.x - x2l * c0.y) * a.scale_log2, (x1h * c1.x - x2h * c1.y) * a.scale_log2, h1[e], l1[e]);
+          split_bf16x2((x2l * c0.x + x1l * c0.y) * a.scale_log2, (x2h * c1.x + x1h * c1.y) * a.scale_log2, h2[e], l2[e]);
         }
         uint4 t;
         t = make_uint4(h1[0], h1[1], h1[2], h1[3]); qhi[ks] = *(bf16x8*)&t;
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
     // hi / lo, registers -> LDS).  A thread always handles the same 8 rotation pairs, of rows
     // RP apart, so it reads (cos, sin) from the table once, for its first row, and turns them by
     // the constant angle of RP rows from item to item (one complex multiplication per pair in
-    // fp32, at most PC_SC_KB / RP - 1 in a chain: ~1e-7 relative per link).
+    // fp32, at most kb_keys / RP - 1 <= 31 in a chain: ~1e-7 relative per link).
     constexpr int ITEMS = TILE * (HALF / 8) / PC_SC_THREADS;           // per thread and tile
     constexpr int RP = PC_SC_THREADS / (HALF / 8);                     // rows between a thread's items
     static_assert(ITEMS >= 1 && TILE * (HALF / 8) % PC_SC_THREADS == 0, "tile / thread mismatch");
@@ -145,7 +151,7 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
     uint4 pf_x1[ITEMS], pf_x2[ITEMS];
     float2 cs_cur[8], cs_step[8];
     {
-      const float4* c4 = (const float4*)(a.table + (long long)min(kblock * PC_SC_KB + st_r0, a.L - 1) * HALF + st_i0);
+      const float4* c4 = (const float4*)(a.table + (long long)min(kblock * a.kb_keys + st_r0, a.L - 1) * HALF + st_i0);
       const float4* s4 = (const float4*)(a.table + (long long)min(RP, a.L - 1) * HALF + st_i0);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -191,18 +197,22 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         }
       }
     };
-    if (kblock * PC_SC_KB < a.L) fetch(kblock * PC_SC_KB);
+    if (kblock * a.kb_keys < a.L) fetch(kblock * a.kb_keys);
 
     // one loop body (not unrolled): leaves room for the prefetch registers
+    const int n_tiles = a.kb_keys / TILE;
 #pragma unroll 1
-    for (int t = 0; t < PC_SC_KB / TILE; ++t) {
-      const int key0 = kblock * PC_SC_KB + t * TILE;
+    for (int t = 0; t < n_tiles; ++t) {
+      const int key0 = kblock * a.kb_keys + t * TILE;
       if (key0 >= a.L) break;                               // uniform over the workgroup
       __syncthreads();                                      // previous tile fully consumed
       stage();
       __syncthreads();
-      if (t + 1 < PC_SC_KB / TILE && key0 + TILE < a.L) fetch(key0 + TILE);
+      if (t + 1 < n_tiles && key0 + TILE < a.L) fetch(key0 + TILE);
       if (!active) continue;
+      // every key of the tile is visible to every voting row: no causal mask (all but the last
+      // tiles of a sequence; the voting rows sit at its end)
+      const bool unmasked = key0 + TILE - 1 <= first_obs;
 
 #pragma unroll
       for (int kq = 0; kq < NSUB / WPC; ++kq) {
@@ -228,11 +238,16 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         }
         if (PASS == 1) {
           float sv[16], tmax = -INFINITY;
+          if (unmasked) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * hf + (r % 4);
-            sv[r] = (key <= my_qrow) ? s[r] * a.scale_log2 : -INFINITY;
-            tmax = fmaxf(tmax, sv[r]);
+            for (int r = 0; r < 16; ++r) { sv[r] = s[r]; tmax = fmaxf(tmax, sv[r]); }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * hf + (r % 4);
+              sv[r] = (key <= my_qrow) ? s[r] : -INFINITY;
+              tmax = fmaxf(tmax, sv[r]);
+            }
           }
           const float m_new = fmaxf(m_run, tmax);
           if (m_new > -INFINITY) {
@@ -245,10 +260,15 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         } else {
           const int key = key0 + 32 * kb + n;
           float sum = 0.f;
+          if (unmasked) {       // padding columns carry lse = +inf: their p is 0 without a mask
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(s[r] * a.scale_log2 - lse_r[r]);
-            sum += (key <= qrow_r[r]) ? p : 0.f;
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(s[r] - lse_r[r]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float p = __builtin_amdgcn_exp2f(s[r] - lse_r[r]);
+              sum += (key <= qrow_r[r]) ? p : 0.f;
+            }
           }
           sum += __shfl_xor(sum, 32);
           if (hf == 0) tok_part[wave][t * TILE + 32 * kb + n] += sum;
@@ -288,12 +308,14 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
 
   if (PASS == 2) {
     __syncthreads();
-    const int key = kblock * PC_SC_KB + tid;
-    if (key < a.w) {
-      float x = 0.f;
+    for (int i = tid; i < a.kb_keys; i += PC_SC_THREADS) {
+      const int key = kblock * a.kb_keys + i;
+      if (key < a.w) {
+        float x = 0.f;
 #pragma unroll
-      for (int wv = 0; wv < PC_SC_WAVES; ++wv) x += tok_part[wv][tid];
-      a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = key < ctx_len ? x : 0.f;
+        for (int wv = 0; wv < PC_SC_WAVES; ++wv) x += tok_part[wv][i];
+        a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = key < ctx_len ? x : 0.f;
+      }
     }
   }
 }
@@ -375,14 +397,20 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   a.ml = (float2*)ml_ws; a.tok_score = tok_score;
   a.L = s->chunk_len + s->query_len; a.w = s->chunk_len; a.w_obs = s->obs_window;
   a.n_q_heads = s->n_q_heads; a.n_kv_heads = s->n_kv_heads;
-  a.n_kb = (a.L + PC_SC_KB - 1) / PC_SC_KB;
   a.n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
+  const int n_cb = (a.n_cols + 31) / 32;
+  const int wpc = n_cb == 1 ? 4 : (n_cb == 2 ? 2 : 1);
+  // keys per workgroup: double while at least 1024 workgroups (two per workgroup slot) remain
+  a.kb_keys = PC_SC_KB;
+  const int kb_cap = wpc == 4 ? PC_SC_KB_MAX / 2 : PC_SC_KB_MAX;
+  while (a.kb_keys < kb_cap &&
+         (long long)s->n_chunks * s->n_kv_heads * ((a.L + 2 * a.kb_keys - 1) / (2 * a.kb_keys)) >= 1024)
+    a.kb_keys *= 2;
+  a.n_kb = (a.L + a.kb_keys - 1) / a.kb_keys;
   const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   a.scale_log2 = scale * PC_SC_LOG2E;
   a.lse2 = (float*)(a.ml + (size_t)s->n_chunks * s->n_kv_heads * a.n_kb * a.n_cols);
   dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
-  const int n_cb = (a.n_cols + 31) / 32;
-  const int wpc = n_cb == 1 ? 4 : (n_cb == 2 ? 2 : 1);
   {
     PcProfScope prof(PC_KERNEL_SCORES_P1, st);
     launch_scores_pass<1>(s->head_dim, wpc, grid, block, st, a);
