@@ -475,8 +475,8 @@ PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg) {
   // 1024 / 2048 keys per workgroup reach 68 / 75 / 80.5 % of the HBM peak).  Short segments use
   // one workgroup each, and the runs are halved while the launch would have fewer than four
   // workgroups per CU of a 256-CU part.  Where a segment fits one workgroup, a workgroup takes
-  // two or four consecutive segments under one running softmax (one partial for all of them):
-  // at the decode config 1 / 2 / 4 segments per workgroup reach 76 / 80 / 83 % on one machine.
+  // one, two or four consecutive segments under one running softmax (one partial for all of
+  // them): at the decode config 1 / 2 / 4 segments per workgroup reach 76 / 80 / 83 % on one machine.
   PcDecodeSplit d;
   const long long n_groups = n_bg * n_seg;
   int kpw = 2048;
@@ -486,12 +486,22 @@ PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg) {
   d.n_split = (k_t + kpw - 1) / kpw;
   d.seg_per_wg = 1;
   if (d.n_split == 1) {
-    // workgroups at 2 and 4 segments each; 512 = resident workgroups of a 256-CU part (2 per CU)
-    const long long wgs2 = n_bg * ((n_seg + 1) / 2), wgs4 = n_bg * ((n_seg + 3) / 4);
-    if (wgs2 >= 2048) d.seg_per_wg = 2;
-    // 4 only where the launch still fills the part evenly: whole rounds of resident workgroups,
-    // or so many rounds that a ragged last one does not matter
-    if (d.seg_per_wg == 2 && wgs4 >= 1024 && (wgs4 % 512 == 0 || wgs4 >= 4096)) d.seg_per_wg = 4;
+    // Pick 1, 2 or 4 segments per workgroup by a makespan estimate in units of one segment: the
+    // full workgroups run in rounds of 512 (resident workgroups of a 256-CU part, 2 per CU),
+    // the workgroups that take the n_seg % spw left-over segments of every (sequence, KV head)
+    // in rounds after them; each term is divided by the bandwidth fraction measured at that
+    // run length.  A ragged last round of full workgroups costs a whole round, a round of
+    // left-overs only its own length, so e.g. 32 + 1 segments still run four to a workgroup.
+    const double eff[3] = {0.76, 0.80, 0.83};
+    double best = 0.0;
+    for (int i = 0; i < 3; ++i) {
+      const int spw = 1 << i;
+      const long long n_full = n_bg * (n_seg / spw);
+      const int rem = n_seg % spw;
+      const double cost = (double)((n_full + 511) / 512) * spw / eff[i] +
+                          (rem ? (double)((n_bg + 511) / 512) * rem / eff[rem > 1] : 0.0);
+      if (i == 0 || cost < best) { best = cost; d.seg_per_wg = spw; }
+    }
   }
   d.n_parts = ((n_seg + d.seg_per_wg - 1) / d.seg_per_wg) * d.n_split;
   return d;
