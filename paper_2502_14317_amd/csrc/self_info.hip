@@ -6,7 +6,7 @@
 #include "pc_common.h"
 #include <math.h>
 
-#define PC_SI_THREADS 256
+#define PC_SI_THREADS 1024
 #define PC_SI_LOG2E 1.4426950408889634f
 #define PC_SI_LN2 0.6931471805599453f
 
@@ -18,22 +18,37 @@ __global__ __launch_bounds__(PC_SI_THREADS) void self_info_rows_kernel(
   const long long row = blockIdx.x;
   const int t = (int)(row % n_tokens);
   const uint16_t* src = logits + row * vocab;
-  // running maximum m (log2 units) and sum l of 2^(x - m) over this lane's elements
+  // running maximum m (log2 units) and sum l of 2^(x - m) over this lane's elements; four
+  // independent 16-byte loads per round, one update of the running maximum per round
   float m = -INFINITY, l = 0.f;
   const int n_vec = vocab / 8;
-  for (int i = threadIdx.x; i < n_vec; i += PC_SI_THREADS) {
-    const u32x4 x = __builtin_nontemporal_load((const u32x4*)(src + 8 * (long long)i));
-    float f[8];
+  constexpr int U = 4;
+  for (int i0 = threadIdx.x; i0 < n_vec; i0 += U * PC_SI_THREADS) {
+    u32x4 x[U];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      f[2 * e] = bf16_lo_to_f32(x[e]) * PC_SI_LOG2E;
-      f[2 * e + 1] = bf16_hi_to_f32(x[e]) * PC_SI_LOG2E;
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + u * PC_SI_THREADS;
+      // behind the row's end: the first vector again, masked below
+      x[u] = __builtin_nontemporal_load((const u32x4*)(src + 8 * (long long)(i < n_vec ? i : i0)));
     }
-    float vm = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
-    const float m_new = fmaxf(m, vm);
+    float f[U][8], vm = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in = i0 + u * PC_SI_THREADS < n_vec;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        f[u][2 * e] = in ? bf16_lo_to_f32(x[u][e]) : -INFINITY;
+        f[u][2 * e + 1] = in ? bf16_hi_to_f32(x[u][e]) : -INFINITY;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) vm = fmaxf(fmaxf(vm, f[u][e]), f[u][e + 1]);
+    }
+    const float m_new = fmaxf(m, vm * PC_SI_LOG2E);       // log2(e) > 0: the maximum commutes with it
     float s = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(f[e] - m_new);
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(fmaf(f[u][e], PC_SI_LOG2E, -m_new));
     l = l * __builtin_amdgcn_exp2f(m - m_new) + s;      // m = -inf, l = 0 on the first round: 0 * 0
     m = m_new;
   }
