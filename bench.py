@@ -299,7 +299,8 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
     for b in range(B):
         kc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
         vc[b] = (torch.randn(kc.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
-    k8 = torch.empty(kc.shape, dtype=torch.uint8, device="cuda"); v8 = torch.empty_like(k8)
+    from paper_2502_14317_amd.layer import fp8_alloc
+    k8, v8 = fp8_alloc(B, S, Hkv, kt, D), fp8_alloc(B, S, Hkv, kt, D)
     ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); vs = torch.empty_like(ks)
     q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda") * cfg.entry_scale).to(bf)
     o = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")

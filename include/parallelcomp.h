@@ -212,7 +212,16 @@ int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_
  *   code  = E4M3(x / scale), fp32 division, round to nearest (ties to the even code), saturating
  * pc_kv_quantize_fp8:
  *   kc, vc [B, S, H_kv, k_t, D] bf16 (finite values);  seg_len as in pc_parallel_attn, nullable
- *   k8, v8 [B, S, H_kv, k_t, D] uint8 out (rows behind seg_len get code 0)
+ *   k8, v8 [B, S, H_kv, ceil(k_t / 32) * 32 * D] uint8 out: the codes of a segment in blocks of
+ *     32 keys laid out so that every load of the attention kernel reads 1 KiB of consecutive
+ *     bytes and hands each lane its matrix-core operand bytes.  Keys behind seg_len or behind
+ *     k_t carry code 0.
+ *     K block = two 16-key tiles; a tile is D / 64 pieces of 1 KiB; piece i is 64 lanes x 16
+ *     bytes, lane 16 kk + c (kk < 4, c < 16) holding the codes of values d = 64 i + 16 kk .. + 15
+ *     of key c of the tile.
+ *     V block (transposed) = D / 32 pieces of 1 KiB; piece q is 64 lanes x 16 bytes, lane
+ *     16 g + m (g < 4, m < 16) holding [h][j] (h < 2, j < 8) = the code of value d = 32 q + 16 h
+ *     + m of key 4 g + j (j < 4) or 16 + 4 g + (j - 4) (j >= 4) of the block.
  *   k_scale, v_scale [B, S, H_kv] fp32 out.   Pointers 16-byte aligned.  No workspace.
  *   B = 0 or S = 0 is a no-op (pointers are not looked at).
  * pc_parallel_attn_fp8: pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 8, else

@@ -3,9 +3,11 @@
 // per-piece softmaxes that are merged by LSE = log sum exp(lse_p), o = sum exp(lse_p - LSE) o_p).
 //
 // Every K/V byte is read exactly once, so the kernel is bound by HBM bandwidth.  Design:
-//   * one workgroup (4 wavefronts) per (sequence, KV head, segment, split); a wavefront owns a
-//     contiguous run of keys and streams them 32 at a time with 16-byte loads, the next 32
-//     keys already in flight while the current ones are used;
+//   * the keys of a (sequence, KV head) group, all its segments end to end in blocks of 32, are
+//     cut into equal runs, one workgroup (4 wavefronts) each, so that the launch has one
+//     workgroup per CU where the shapes allow (long runs, equal work, no ragged last round);
+//     a wavefront owns a contiguous quarter of the run and streams it 32 keys at a time with
+//     16-byte loads, the next 32 keys already in flight while the current ones are used;
 //   * the query columns of one KV group (n_q * G <= 16) form the N side of a 16x16x32 bf16
 //     MFMA: S^T = K Q^T, so the lane that owns a column owns its running max and sum;
 //   * P V runs on the vector ALUs in the layout the V loads arrive in (D across lanes), with
@@ -33,8 +35,8 @@ struct PcDecodeArgs {
   int seg_len_per_head;
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
-  int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
-  int seg_per_wg;         // consecutive segments streamed by one workgroup (1 if n_split > 1)
+  int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_parts;
+  int parts_grid;         // workgroups (partials) per (sequence, KV head) in this launch
   int part0;              // index of this launch's first partial among the n_parts
   float scale_log2;       // softmax scale * log2(e)
 };
@@ -57,45 +59,27 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   const int lane = threadIdx.x % PC_WAVE, wave = threadIdx.x / PC_WAVE;
   const int kk = lane / 16, c16 = lane % 16;
 
-  const int n_sgroups = (a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg;
   int bid = blockIdx.x;
-  const int split = bid % a.n_split; bid /= a.n_split;
-  const int sg = bid % n_sgroups;    bid /= n_sgroups;
-  const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
+  const int part = bid % a.parts_grid; bid /= a.parts_grid;
+  const int g = bid % a.n_kv_heads;    bid /= a.n_kv_heads;
   const int b = bid;
-  const int s_first = sg * a.seg_per_wg, s_last = min(a.n_seg, s_first + a.seg_per_wg);
 
-  // A wavefront streams its quarter of the workgroup's key range of every segment of the group,
-  // one segment after the other; the running softmax carries over (same query columns, same KV
-  // head), so a workgroup leaves one partial for all its segments.  A cursor names the next
-  // 32-key block: segment, first key, the segment's base pointers, length and range end.
-  struct Cursor { int s, key0, len, w_end; const uint16_t* k; const uint16_t* v; bool valid; };
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wavefront-uniform: cursors live in scalar registers
-  const int per_wave = a.keys_per_wg / PC_DEC_WAVES;      // multiple of PC_DEC_ITER_KEYS
-  auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
-    Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
-    for (; s < s_last; ++s) {
-      const int len_idx = a.seg_len_per_head ? (b * a.n_seg + s) * a.n_kv_heads + g : b * a.n_seg + s;
-      const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
-      const int wg_begin = split * a.keys_per_wg;
-      const int wg_end = min(len, wg_begin + a.keys_per_wg);
-      const int w_begin = wg_begin + wave_u * per_wave;
-      const int w_end = min(wg_end, w_begin + per_wave);
-      if (w_begin < w_end) {
-        const long long seg_base = ((((long long)b * a.n_seg + s) * a.n_kv_heads + g) * a.k_t) * D;
-        c.valid = true; c.s = s; c.key0 = w_begin; c.len = len; c.w_end = w_end;
-        c.k = a.kc + seg_base; c.v = a.vc + seg_base;
-        break;
-      }
+  // A wavefront streams its run of 32-key blocks, through segment boundaries; the running
+  // softmax carries over (same query columns, same KV head), so a workgroup leaves one partial.
+  // A cursor names the next block: where it is, plus the segment's base pointers.
+  struct Cursor { PcBlockCursor at; int key0; const uint16_t* k; const uint16_t* v; bool valid; };
+  PcSegLens lens;
+  lens.seg_len = a.seg_len; lens.per_head = a.seg_len_per_head; lens.n_seg = a.n_seg;
+  lens.n_kv_heads = a.n_kv_heads; lens.k_t = a.k_t; lens.b = b; lens.g = g;
+  auto place = [&](const PcBlockCursor& at) {
+    Cursor c; c.at = at; c.valid = at.valid; c.key0 = 32 * at.blk; c.k = nullptr; c.v = nullptr;
+    if (at.valid) {
+      const long long seg_base = ((((long long)b * a.n_seg + at.s) * a.n_kv_heads + g) * a.k_t) * D;
+      c.k = a.kc + seg_base; c.v = a.vc + seg_base;
     }
     return c;
   };
-  auto next = [&](const Cursor& c) {
-    Cursor n = c;
-    n.key0 += PC_DEC_ITER_KEYS;
-    if (n.key0 >= c.w_end) n = seek(c.s + 1);
-    return n;
-  };
+  auto next = [&](const Cursor& c) { return place(pc_blocks_next(lens, c.at)); };
 
   // B operand: column c16 = (t, head-in-group); lane holds d = 32*ks + 8*kk .. +7
   bf16x8 bq[KSTEPS];
@@ -123,20 +107,20 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   auto issue_loads = [&](int buf, const Cursor& c) {
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi) {
-      const int row = min(c.key0 + 16 * bi + c16, c.len - 1);
+      const int row = min(c.key0 + 16 * bi + c16, c.at.len - 1);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks)
         kbuf[buf][bi][ks] = pc_load_once((const uint4*)(c.k + (long long)row * D + 32 * ks + 8 * kk));
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
-      const int row = min(c.key0 + RPI * i + v_row, c.len - 1);
+      const int row = min(c.key0 + RPI * i + v_row, c.at.len - 1);
       vbuf[buf][i] = pc_load_once((const uint4*)(c.v + (long long)row * D + 8 * v_piece));
     }
   };
 
   auto consume = [&](int buf, const Cursor& cur) {
-    const int key0 = cur.key0, w_end = cur.w_end;
+    const int key0 = cur.key0, w_end = cur.at.len;
     // S^T block: keys x columns
     floatx4 acc[KBLK];
 #pragma unroll
@@ -203,7 +187,8 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
     PC_WAVE_LDS_SYNC();
   };
 
-  Cursor cur = seek(s_first);
+  Cursor cur = place(pc_blocks_begin(lens, part, a.parts_grid, __builtin_amdgcn_readfirstlane(wave),
+                                     PC_DEC_WAVES, lane));
   if (cur.valid) {
     issue_loads(0, cur);
     while (true) {
@@ -242,7 +227,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
   __syncthreads();
 
   // ---- merge the 4 wavefronts, write one partial per workgroup
-  const int part = a.part0 + sg * a.n_split + split;
+  const int part_out = a.part0 + part;
   for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
     const int n = idx / D, d = idx % D;
     float M = -INFINITY;
@@ -258,7 +243,7 @@ __global__ __launch_bounds__(PC_DEC_WAVES * PC_WAVE) void decode_attn_kernel(PcD
       }
     }
     const int t = n / G, hg = n % G;
-    const long long row = (((long long)b * a.n_parts + part) * a.n_q + t) * a.n_q_heads + g * G + hg;
+    const long long row = (((long long)b * a.n_parts + part_out) * a.n_q + t) * a.n_q_heads + g * G + hg;
     a.part_o[row * D + d] = (den > 0.f) ? num / den : 0.f;
     if (d == 0) a.part_lse[row] = (den > 0.f) ? (M + log2f(den)) * 0.6931471805599453f : -INFINITY;
   }
@@ -457,7 +442,7 @@ int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_n
 
 template <int D>
 static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStream_t st) {
-  const long long blocks = (long long)batch * a.n_kv_heads * ((a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg) * a.n_split;
+  const long long blocks = (long long)batch * a.n_kv_heads * a.parts_grid;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(PC_DEC_WAVES * PC_WAVE);
@@ -470,40 +455,28 @@ static int launch_decode_d(const PcDecodeArgs& a, int batch, int nq_pad, hipStre
 }
 
 PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg) {
-  // A workgroup streams up to 2048 keys of one (sequence, KV head, segment): the longer its run,
-  // the smaller the share of its start-up and of its partial result (at the decode config 256 /
-  // 1024 / 2048 keys per workgroup reach 68 / 75 / 80.5 % of the HBM peak).  Short segments use
-  // one workgroup each, and the runs are halved while the launch would have fewer than four
-  // workgroups per CU of a 256-CU part.  Where a segment fits one workgroup, a workgroup takes
-  // one, two or four consecutive segments under one running softmax (one partial for all of
-  // them): at the decode config 1 / 2 / 4 segments per workgroup reach 76 / 80 / 83 % on one machine.
+  // Workgroups (partials) per (sequence, KV head) group.  Measured at the decode config (128
+  // groups of 32 x 2048 keys, bf16): 256 workgroups, one per CU, each streaming half of a
+  // group's keys, reach 89 % of the HBM peak; 512 and 1024
+  // workgroups (the same bytes in shorter runs, two workgroups per CU at a time) 81 %.  Fewer
+  // concurrent streams with longer runs are kinder to the memory system than more occupancy, and
+  // a launch of exactly one round has no ragged end.  So: the number of parts that minimises
+  // rounds / parts (the time of the slowest CU in units of one group's work), each round count
+  // weighted by the bandwidth fraction measured for it; every wavefront keeps at least one
+  // 32-key block at full lengths; at most 64 parts (the merge reads them all).
+  const int n_cu = 256;                                    // MI355X
+  const long long blocks_full = (long long)n_seg * ((k_t + 31) / 32);
+  const long long p_cap = blocks_full / PC_DEC_WAVES;
+  const int p_max = (int)(p_cap < 1 ? 1 : (p_cap > 64 ? 64 : p_cap));
   PcDecodeSplit d;
-  const long long n_groups = n_bg * n_seg;
-  int kpw = 2048;
-  while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && kpw / 2 >= k_t) kpw /= 2;
-  while (kpw > PC_DEC_WAVES * PC_DEC_ITER_KEYS && n_groups * ((k_t + kpw - 1) / kpw) < 1024) kpw /= 2;
-  d.keys_per_wg = kpw;
-  d.n_split = (k_t + kpw - 1) / kpw;
-  d.seg_per_wg = 1;
-  if (d.n_split == 1) {
-    // Pick 1, 2 or 4 segments per workgroup by a makespan estimate in units of one segment: the
-    // full workgroups run in rounds of 512 (resident workgroups of a 256-CU part, 2 per CU),
-    // the workgroups that take the n_seg % spw left-over segments of every (sequence, KV head)
-    // in rounds after them; each term is divided by the bandwidth fraction measured at that
-    // run length.  A ragged last round of full workgroups costs a whole round, a round of
-    // left-overs only its own length, so e.g. 32 + 1 segments still run four to a workgroup.
-    const double eff[3] = {0.76, 0.80, 0.83};
-    double best = 0.0;
-    for (int i = 0; i < 3; ++i) {
-      const int spw = 1 << i;
-      const long long n_full = n_bg * (n_seg / spw);
-      const int rem = n_seg % spw;
-      const double cost = (double)((n_full + 511) / 512) * spw / eff[i] +
-                          (rem ? (double)((n_bg + 511) / 512) * rem / eff[rem > 1] : 0.0);
-      if (i == 0 || cost < best) { best = cost; d.seg_per_wg = spw; }
-    }
+  d.n_parts = n_seg > 0 ? 1 : 0;                           // no segments: no launch, no partial
+  if (n_seg <= 0) return d;
+  double best = 0.0;
+  for (int p = 1; p <= p_max; ++p) {
+    const long long rounds = (n_bg * p + n_cu - 1) / n_cu;
+    const double cost = (double)rounds / p / (rounds == 1 ? 0.89 : 0.81);
+    if (p == 1 || cost < best * (1.0 - 1e-9)) { best = cost; d.n_parts = p; }
   }
-  d.n_parts = ((n_seg + d.seg_per_wg - 1) / d.seg_per_wg) * d.n_split;
   return d;
 }
 
@@ -516,8 +489,7 @@ int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const in
   a.q = (const uint16_t*)q_rot; a.kc = (const uint16_t*)kc; a.vc = (const uint16_t*)vc;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  const PcDecodeSplit sp = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads);
-  a.keys_per_wg = sp.keys_per_wg; a.n_split = sp.n_split; a.seg_per_wg = sp.seg_per_wg;
+  a.parts_grid = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_DEC_LOG2E;
   const int cols = n_q * (n_q_heads / n_kv_heads);

@@ -10,13 +10,27 @@
 //
 // kv_quantize_fp8_kernel   one workgroup per (sequence, segment, KV head, K or V): maximum,
 //                          then codes; the second sweep reads the segment again (5 bytes per
-//                          element in all).
+//                          element in all).  Codes are written in 32-key blocks laid out for
+//                          the matrix cores (below), V transposed.
 // decode_attn_fp8_kernel   the split-KV kernel of decode_attn.hip on 8-bit operands: codes are
-//                          widened in registers (every E4M3 value is exact in bf16), K enters
-//                          the same 16x16x32 bf16 MFMA, the scales are folded into the logit
-//                          scale and into the partial output.  A lane loads the D / 4
-//                          consecutive bytes of its K row that it feeds to the matrix core
-//                          (the query operand is permuted to match), and 16 bytes of a V row.
+//                          widened in registers (every E4M3 value is exact in bf16), both
+//                          products run on the 16x16x32 bf16 MFMA, the scales are folded into the
+//                          logit scale and into the probabilities.  Every load instruction
+//                          of a wavefront reads 1 KiB of consecutive bytes.
+//
+// K block layout.  A block of 32 keys x D codes is two 16-key tiles; a tile is D / 64 pieces of
+// 1 KiB, piece i = 64 lanes x 16 bytes, lane 16 kk + c (kk < 4, c < 16) holding the codes of
+// d = 64 i + 16 kk .. + 15 of key c of the tile: the A operand bytes of that lane for k-steps
+// 2 i and 2 i + 1 of S^T = K Q^T (the query operand is permuted to the same d order).
+//
+// V block layout.  O^T[d, column] += V^T[d, key] P^T[key, column] wants, per lane, 8 keys of one
+// d, and the probabilities a lane holds after the two 16-key logit tiles of a 32-key block are
+// those of keys 4g..4g+3 and 16+4g..16+4g+3 (g = lane / 16).  So the codes of a block of 32 keys
+// x D values are stored as D / 32 pieces of 1 KiB, piece q = 64 lanes x 16 bytes, lane (g, m)
+// = 16 g + m holding [h][j]: h = 0, 1 -> d = 32 q + 16 h + m; j = 0..7 -> key 4 g + j (j < 4),
+// 16 + 4 g + (j - 4) (j >= 4).  A piece is one fully coalesced 16-byte-per-lane load and gives
+// two A operands.  A segment holds ceil(k_t / 32) blocks of K and of V; keys behind k_t or behind
+// the segment's length carry code 0.
 #include "pc_common.h"
 #include <math.h>
 
@@ -25,14 +39,6 @@
 #define PC_D8_LOG2E 1.4426950408889634f
 #define PC_E4M3_MAX 448.0f
 
-#define PC_D8_WAVE_LDS_SYNC()                                \
-  do {                                                       \
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   \
-    __builtin_amdgcn_wave_barrier();                         \
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");   \
-  } while (0)
-
-typedef float pc_f2 __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------------------------------
 // Quantisation.  blockIdx.x = (b, s, g), blockIdx.y = 0 (K) or 1 (V).  The segment is read twice
@@ -48,12 +54,17 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
     uint8_t* __restrict__ k8, uint8_t* __restrict__ v8, float* __restrict__ k_scale,
     float* __restrict__ v_scale) {
   __shared__ uint32_t red[PC_Q8_THREADS / PC_WAVE];
+  __shared__ __attribute__((aligned(16))) uint8_t tile[PC_Q8_THREADS * PC_Q8_UNROLL * 8];   // 32 KiB of codes, block layout
   const long long seg = blockIdx.x;
   const uint16_t* src = (blockIdx.y ? vc : kc) + seg * (long long)k_t * D;
-  uint8_t* dst = (blockIdx.y ? v8 : k8) + seg * (long long)k_t * D;
+  const int n_blk = (k_t + 31) / 32;
+  uint8_t* dst = (blockIdx.y ? v8 : k8) + seg * (long long)n_blk * 32 * D;
   float* scale_out = blockIdx.y ? v_scale : k_scale;
   const int len = seg_len ? min(max(seg_len[per_head ? seg : seg / n_kv_heads], 0), k_t) : k_t;
-  const long long n_valid = (long long)len * D / 8, n_all = (long long)k_t * D / 8;   // 8-element groups
+  // 8-element groups: of the valid rows, and of all rows to write (whole 32-key blocks)
+  const long long n_valid = (long long)len * D / 8;
+  const long long n_all = (long long)n_blk * 32 * D / 8;
+  const int gpr = D / 8;                                   // groups per row
 
   // largest magnitude: bf16 magnitudes order like their 15-bit patterns
   uint32_t amax = 0;
@@ -93,7 +104,7 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
     for (int u = 0; u < PC_Q8_UNROLL; ++u) {
       const long long i = i0 + u * PC_Q8_THREADS + threadIdx.x;
       if (i >= n_all) continue;
-      uint2 code = make_uint2(0u, 0u);              // rows behind the segment's length
+      uint2 code = make_uint2(0u, 0u);              // rows behind the segment's length or behind k_t
       if (i < n_valid) {
         const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
         float f[8];
@@ -109,9 +120,29 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
         c1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], c1, true);
         code = make_uint2(c0, c1);
       }
-      __builtin_nontemporal_store(code.x, (uint32_t*)(dst + 8 * i));
-      __builtin_nontemporal_store(code.y, (uint32_t*)(dst + 8 * i) + 1);
+      // group i = 8 values d0..d0+7 of one key: to its place in the block layout, in LDS
+      const int il = (int)(i - i0);                         // group within this sweep step
+      const int key_l = il / gpr, d0 = (il % gpr) * 8;      // key within the step's rows
+      const int kib = key_l % 32, blk_l = key_l / 32;
+      if (!blockIdx.y) {
+        uint8_t* t = tile + blk_l * 32 * D + (kib / 16) * 16 * D + (d0 / 64) * 1024 +
+                     (16 * ((d0 % 64) / 16) + kib % 16) * 16 + d0 % 16;
+        *(uint2*)t = code;
+      } else {
+        const int g = (kib % 16) / 4, j = kib % 4 + 4 * (kib / 16);
+        uint8_t* t = tile + blk_l * 32 * D + (d0 / 32) * 1024 + g * 256 + ((d0 % 32) / 16) * 8 + j;
+        const int m0 = d0 % 16;                               // m = m0 .. m0 + 7
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          t[(m0 + e) * 16] = (uint8_t)(((e < 4 ? code.x : code.y) >> (8 * (e % 4))) & 0xffu);
+      }
     }
+    // a sweep step covers whole blocks (its rows are a multiple of 32): copy them out
+    __syncthreads();
+    const long long step_bytes = min((long long)PC_Q8_THREADS * PC_Q8_UNROLL * 8, (n_all - i0) * 8);
+    for (long long o = 16LL * threadIdx.x; o < step_bytes; o += 16LL * PC_Q8_THREADS)
+      pc_store_once((uint4*)(dst + i0 * 8 + o), *(const uint4*)(tile + o));
+    __syncthreads();
   }
 }
 
@@ -132,16 +163,16 @@ int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg
 // ------------------------------------------------------------------------------------------
 struct PcDecode8Args {
   const uint16_t* q;      // rotated queries [B, n_q, H_q, D] bf16
-  const uint8_t* k8;      // [B, S, H_kv, k_t, D] E4M3 codes
-  const uint8_t* v8;
+  const uint8_t* k8;      // [B, S, H_kv, ceil(k_t / 32) * 32 * D] E4M3 codes in 32-key blocks
+  const uint8_t* v8;      // the same size, transposed blocks
   const float* k_scale;   // [B, S, H_kv]
   const float* v_scale;
   const int32_t* seg_len; // [B, S] ([B, S, H_kv] if seg_len_per_head) or nullptr
   int seg_len_per_head;
   float* part_o;          // [B, P, n_q, H_q, D]
   float* part_lse;        // [B, P, n_q, H_q]
-  int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_split, keys_per_wg, n_parts;
-  int seg_per_wg;         // consecutive segments streamed by one workgroup (1 if n_split > 1)
+  int n_q, n_seg, k_t, n_q_heads, n_kv_heads, n_parts;
+  int parts_grid;         // workgroups (partials) per (sequence, KV head) in this launch
   float scale_log2;       // softmax scale * log2(e)
 };
 
@@ -159,13 +190,11 @@ template <int D, int NQ>
 __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(PcDecode8Args a) {
   constexpr int KSTEPS = D / 32;            // MFMA k-steps; a lane owns 8 KSTEPS = D / 4 bytes of each of its K rows
   constexpr int KQ = D / 64;                // 16-byte loads per lane and 16-key block
-  constexpr int LPR = D / 16;               // lanes per V row (16 codes each)
-  constexpr int RPI = PC_WAVE / LPR;        // V rows per load instruction
-  constexpr int VLOADS = PC_D8_ITER_KEYS / RPI;
+  constexpr int VLOADS = D / 32;            // 1 KiB pieces of a V block: one 16-byte load per lane each
+  constexpr int MB = D / 16;                // 16-row blocks of O^T
   constexpr int KBLK = PC_D8_ITER_KEYS / 16;
+  static_assert(KBLK == 2, "the V block layout assumes two 16-key logit tiles per block");
 
-  __shared__ float p_lds[PC_D8_WAVES][PC_D8_ITER_KEYS][NQ];
-  __shared__ float alpha_lds[PC_D8_WAVES][NQ];
   __shared__ float red_o[PC_D8_WAVES][NQ][D];
   __shared__ float red_m[PC_D8_WAVES][NQ], red_l[PC_D8_WAVES][NQ];
 
@@ -174,53 +203,34 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   const int lane = threadIdx.x % PC_WAVE, wave = threadIdx.x / PC_WAVE;
   const int kk = lane / 16, c16 = lane % 16;
 
-  const int n_sgroups = (a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg;
   int bid = blockIdx.x;
-  const int split = bid % a.n_split; bid /= a.n_split;
-  const int sg = bid % n_sgroups;    bid /= n_sgroups;
-  const int g = bid % a.n_kv_heads;  bid /= a.n_kv_heads;
+  const int part = bid % a.parts_grid; bid /= a.parts_grid;
+  const int g = bid % a.n_kv_heads;    bid /= a.n_kv_heads;
   const int b = bid;
-  const int s_first = sg * a.seg_per_wg, s_last = min(a.n_seg, s_first + a.seg_per_wg);
 
-  // A wavefront streams its quarter of the workgroup's key range of every segment of the group,
-  // one segment after the other, under one running softmax (one partial per workgroup).  A
-  // cursor names the next 32-key block: segment, first key, base pointers, length, range end
-  // and the segment's scales (K: folded into the logit scale; V: applied to the probabilities
-  // that multiply the codes, not to the row sum).
-  struct Cursor { int s, key0, len, w_end; const uint8_t* k; const uint8_t* v; float k_sc, v_sc; bool valid; };
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // wavefront-uniform: cursors live in scalar registers
-  const int per_wave = a.keys_per_wg / PC_D8_WAVES;        // multiple of PC_D8_ITER_KEYS
-  auto seek = [&](int s) {                                 // first segment >= s with keys for this wavefront
-    Cursor c; c.valid = false; c.s = s; c.key0 = 0; c.len = 0; c.w_end = 0; c.k = nullptr; c.v = nullptr;
-    c.k_sc = 0.f; c.v_sc = 0.f;
-    for (; s < s_last; ++s) {
-      const long long seg_id = ((long long)b * a.n_seg + s) * a.n_kv_heads + g;
-      const int len_idx = a.seg_len_per_head ? (int)seg_id : b * a.n_seg + s;
-      const int len = a.seg_len ? min(max(a.seg_len[len_idx], 0), a.k_t) : a.k_t;
-      const int wg_begin = split * a.keys_per_wg;
-      const int wg_end = min(len, wg_begin + a.keys_per_wg);
-      const int w_begin = wg_begin + wave_u * per_wave;
-      const int w_end = min(wg_end, w_begin + per_wave);
-      if (w_begin < w_end) {
-        c.valid = true; c.s = s; c.key0 = w_begin; c.len = len; c.w_end = w_end;
-        c.k = a.k8 + seg_id * a.k_t * D; c.v = a.v8 + seg_id * a.k_t * D;
-        c.k_sc = a.k_scale[seg_id] * a.scale_log2;         // logits in log2 units
-        c.v_sc = a.v_scale[seg_id];
-        break;
-      }
+  // A wavefront streams its run of 32-key blocks, through segment boundaries, under one running
+  // softmax (one partial per workgroup).  A cursor names the next block: where it is, the
+  // segment's base pointers and its scales (K: folded into the logit scale; V: applied to the
+  // probabilities that multiply the codes, not to the row sum).
+  struct Cursor { PcBlockCursor at; const uint8_t* k; const uint8_t* v; float k_sc, v_sc; bool valid; };
+  const long long seg_bytes = (long long)((a.k_t + 31) / 32) * 32 * D;
+  PcSegLens lens;
+  lens.seg_len = a.seg_len; lens.per_head = a.seg_len_per_head; lens.n_seg = a.n_seg;
+  lens.n_kv_heads = a.n_kv_heads; lens.k_t = a.k_t; lens.b = b; lens.g = g;
+  auto place = [&](const PcBlockCursor& at) {
+    Cursor c; c.at = at; c.valid = at.valid; c.k = nullptr; c.v = nullptr; c.k_sc = 0.f; c.v_sc = 0.f;
+    if (at.valid) {
+      const long long seg_id = ((long long)b * a.n_seg + at.s) * a.n_kv_heads + g;
+      c.k = a.k8 + seg_id * seg_bytes; c.v = a.v8 + seg_id * seg_bytes;
+      c.k_sc = a.k_scale[seg_id] * a.scale_log2;           // logits in log2 units
+      c.v_sc = a.v_scale[seg_id];
     }
     return c;
   };
-  auto next = [&](const Cursor& c) {
-    Cursor n = c;
-    n.key0 += PC_D8_ITER_KEYS;
-    if (n.key0 >= c.w_end) n = seek(c.s + 1);
-    return n;
-  };
+  auto next = [&](const Cursor& c) { return place(pc_blocks_next(lens, c.at)); };
 
   // B operand: column c16 = (t, head-in-group); k-step j of lane group kk covers
-  // d = 64 (j / 2) + 16 kk + 8 (j % 2) .. + 7, the bytes the lane loads of its K rows (load i of
-  // a row takes bytes 64 i + 16 kk .. + 15, so the 4 lanes of a row read 64 contiguous bytes)
+  // d = 64 (j / 2) + 16 kk + 8 (j % 2) .. + 7, the d order of the K block layout
   bf16x8 bq[KSTEPS];
   {
     const bool valid = c16 < n_cols;
@@ -234,36 +244,30 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   }
 
   float m_run = -INFINITY, l_run = 0.f;     // of column c16 (this lane's share of the sum)
-  float o_acc[NQ][16];
+  // O^T: row block mb, register r = value d = 16 mb + 4 kk + r of column c16
+  floatx4 o_acc[MB];
 #pragma unroll
-  for (int n = 0; n < NQ; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) o_acc[n][e] = 0.f;
-
-  const int v_row = lane / LPR, v_piece = lane % LPR;
+  for (int mb = 0; mb < MB; ++mb) o_acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // three register buffers: the loads of two iterations (2 x 8 KiB per wavefront) stay in flight
   uint4 kbuf[3][KBLK][KQ], vbuf[3][VLOADS];
   auto issue_loads = [&](int buf, const Cursor& c) {
-    const int key0 = c.key0, len = c.len;
-    const uint8_t* kseg = c.k;
-    const uint8_t* vseg = c.v;
+    // the block's pieces: key0 is a multiple of 32, and whole blocks exist up to ceil(k_t / 32)
+    const long long blk_off = (long long)c.at.blk * 32 * D + 16 * lane;
+    const uint8_t* kblk = c.k + blk_off;
+    const uint8_t* vblk = c.v + blk_off;
 #pragma unroll
-    for (int bi = 0; bi < KBLK; ++bi) {
-      const int row = min(key0 + 16 * bi + c16, len - 1);
+    for (int bi = 0; bi < KBLK; ++bi)
 #pragma unroll
       for (int i = 0; i < KQ; ++i)
-        kbuf[buf][bi][i] = pc_load_once((const uint4*)(kseg + (long long)row * D + 64 * i + 16 * kk));
-    }
+        kbuf[buf][bi][i] = pc_load_once((const uint4*)(kblk + bi * 16 * D + 1024 * i));
 #pragma unroll
-    for (int i = 0; i < VLOADS; ++i) {
-      const int row = min(key0 + RPI * i + v_row, len - 1);
-      vbuf[buf][i] = pc_load_once((const uint4*)(vseg + (long long)row * D + 16 * v_piece));
-    }
+    for (int i = 0; i < VLOADS; ++i)
+      vbuf[buf][i] = pc_load_once((const uint4*)(vblk + 1024 * i));
   };
 
   auto consume = [&](int buf, const Cursor& cur) {
-    const int key0 = cur.key0, w_end = cur.w_end;
+    const int key0 = 32 * cur.at.blk, w_end = cur.at.len;
     const float k_sc = cur.k_sc, v_sc = cur.v_sc;
     floatx4 acc[KBLK];
 #pragma unroll
@@ -297,50 +301,43 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // arguments <= 0: the bare instruction
     m_run = m_new;
     float psum = 0.f;
+    // P^T as the B operand: this lane's 8 probabilities are k-slice kk of column c16, in the
+    // key order of the V block layout; the V scale rides on them (not on the row sum)
+    u32x4 pb;
 #pragma unroll
     for (int bi = 0; bi < KBLK; ++bi)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float p = __builtin_amdgcn_exp2f(sv[bi][j] - m_new);
-        psum += p;
-        if (c16 < NQ) p_lds[wave][16 * bi + 4 * kk + j][c16] = p * v_sc;
+      for (int j = 0; j < 4; j += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(sv[bi][j] - m_new);
+        const float p1 = __builtin_amdgcn_exp2f(sv[bi][j + 1] - m_new);
+        psum += p0 + p1;
+        pb[2 * bi + j / 2] = pack_bf16x2(p0 * v_sc, p1 * v_sc);
       }
     l_run = l_run * alpha + psum;
-    const bool moved = __any(alpha != 1.0f);         // some column's maximum grew (rare after the first keys)
-    if (moved && kk == 0 && c16 < NQ) alpha_lds[wave][c16] = alpha;
-    PC_D8_WAVE_LDS_SYNC();
-    if (moved) {
+    if (__any(alpha != 1.0f)) {                      // some column's maximum grew (rare after the first keys)
 #pragma unroll
-      for (int n = 0; n < NQ; ++n) {
-        const float al = alpha_lds[wave][n];
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[n][e] *= al;
-      }
+        for (int r = 0; r < 4; ++r) o_acc[mb][r] *= alpha;
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
-      const int key_local = RPI * i + v_row;
       const uint4 raw = vbuf[buf][i];
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-      float vf[16];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const pc_f2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[e], false);
-        const pc_f2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[e], true);
-        vf[4 * e] = lo.x; vf[4 * e + 1] = lo.y; vf[4 * e + 2] = hi.x; vf[4 * e + 3] = hi.y;
-      }
-#pragma unroll
-      for (int n = 0; n < NQ; ++n) {
-        const float p = p_lds[wave][key_local][n];    // 0 for masked keys
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o_acc[n][e] = fmaf(p, vf[e], o_acc[n][e]);
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t w0 = h ? raw.z : raw.x, w1 = h ? raw.w : raw.y;
+        u32x4 va;
+        uint32_t lo, hi;
+        pc_e4m3x4_to_bf16(w0, lo, hi); va[0] = lo; va[1] = hi;
+        pc_e4m3x4_to_bf16(w1, lo, hi); va[2] = lo; va[3] = hi;
+        o_acc[2 * i + h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8*)&va, *(bf16x8*)&pb, o_acc[2 * i + h], 0, 0, 0);
       }
     }
-    PC_D8_WAVE_LDS_SYNC();
   };
 
   // three register buffers: the loads of two blocks (2 x 8 KiB per wavefront) stay in flight
-  Cursor c0 = seek(s_first);
+  Cursor c0 = place(pc_blocks_begin(lens, part, a.parts_grid, __builtin_amdgcn_readfirstlane(wave),
+                                    PC_D8_WAVES, lane));
   if (c0.valid) {
     Cursor c1 = next(c0);
     issue_loads(0, c0);
@@ -362,26 +359,16 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
   // ---- wavefront totals: sum the per-lane shares
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-#pragma unroll
-  for (int n = 0; n < NQ; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      float x = o_acc[n][e];
-#pragma unroll
-      for (int off = LPR; off < PC_WAVE; off <<= 1) x += __shfl_xor(x, off);
-      o_acc[n][e] = x;
-    }
   if (kk == 0 && c16 < NQ) { red_m[wave][c16] = m_run; red_l[wave][c16] = l_run; }
-  if (v_row == 0) {
+  if (c16 < NQ) {
 #pragma unroll
-    for (int n = 0; n < NQ; ++n)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) red_o[wave][n][16 * v_piece + e] = o_acc[n][e];
+      for (int r = 0; r < 4; ++r) red_o[wave][c16][16 * mb + 4 * kk + r] = o_acc[mb][r];
   }
   __syncthreads();
 
   // ---- merge the 4 wavefronts, write one partial per workgroup (values scaled back)
-  const int part = sg * a.n_split + split;
   for (int idx = threadIdx.x; idx < n_cols * D; idx += blockDim.x) {
     const int n = idx / D, d = idx % D;
     float M = -INFINITY;
@@ -405,7 +392,7 @@ __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(
 
 template <int D>
 static int launch_decode8_d(const PcDecode8Args& a, int batch, int nq_pad, hipStream_t st) {
-  const long long blocks = (long long)batch * a.n_kv_heads * ((a.n_seg + a.seg_per_wg - 1) / a.seg_per_wg) * a.n_split;
+  const long long blocks = (long long)batch * a.n_kv_heads * a.parts_grid;
   if (blocks == 0) return PC_OK;
   if (blocks > 0x7fffffffLL) return PC_ERR_SHAPE;
   dim3 grid((unsigned)blocks), block(PC_D8_WAVES * PC_WAVE);
@@ -426,8 +413,7 @@ int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, cons
   a.k_scale = k_scale; a.v_scale = v_scale;
   a.seg_len = seg_len; a.seg_len_per_head = seg_len_per_head; a.part_o = part_o; a.part_lse = part_lse;
   a.n_q = n_q; a.n_seg = n_seg; a.k_t = k_t; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
-  const PcDecodeSplit sp = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads);
-  a.keys_per_wg = sp.keys_per_wg; a.n_split = sp.n_split; a.seg_per_wg = sp.seg_per_wg;
+  a.parts_grid = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_D8_LOG2E;
   const int cols = n_q * (n_q_heads / n_kv_heads);

@@ -147,9 +147,91 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
                      int pos0, float base, hipStream_t st);
-// how the split-KV decode kernels cut the keys into workgroups (n_bg = batch * H_kv)
-struct PcDecodeSplit { int keys_per_wg, n_split, seg_per_wg, n_parts; };
+// How the split-KV decode kernels cut the keys into workgroups (n_bg = batch * H_kv): the keys of
+// a (sequence, KV head) group, all its segments laid end to end in blocks of 32 keys, are cut
+// into n_parts equal runs of blocks, one workgroup (and one partial result) each.
+struct PcDecodeSplit { int n_parts; };
 PcDecodeSplit pc_decode_split(int k_t, int n_seg, long long n_bg);
+
+// A wavefront's walk over its run of 32-key blocks.  The group's blocks are numbered through all
+// segments (segment s has ceil(len_s / 32) of them); part `part` of n_parts takes blocks
+// [NB part / n_parts, NB (part + 1) / n_parts), wavefront w of n_waves the w-th of n_waves equal
+// runs of that.  Everything here is wavefront-uniform.
+struct PcSegLens {
+  const int32_t* seg_len;   // [B, S] ([B, S, H_kv] if per_head) or nullptr (= k_t)
+  int per_head, n_seg, n_kv_heads, k_t, b, g;
+  __device__ __forceinline__ int len(int s) const {
+    if (!seg_len) return k_t;
+    const int idx = per_head ? (b * n_seg + s) * n_kv_heads + g : b * n_seg + s;
+    return min(max(seg_len[idx], 0), k_t);
+  }
+};
+struct PcBlockCursor {
+  int s, blk, n_blk, len, left;   // segment, block within it, its block count and length, blocks left in the run
+  bool valid;
+};
+__device__ __forceinline__ PcBlockCursor pc_blocks_begin(const PcSegLens& L, int part, int n_parts,
+                                                         int wave, int n_waves, int lane) {
+  PcBlockCursor c; c.s = 0; c.blk = 0; c.n_blk = 0; c.len = 0; c.left = 0; c.valid = false;
+  const int nb_full = (L.k_t + 31) / 32;
+  long long total = 0;
+  if (!L.seg_len) {
+    total = (long long)L.n_seg * nb_full;
+  } else {
+    // lanes take a segment each, 64 segments per round
+    for (int s0 = 0; s0 < L.n_seg; s0 += PC_WAVE) {
+      int nb = s0 + lane < L.n_seg ? (L.len(s0 + lane) + 31) / 32 : 0;
+#pragma unroll
+      for (int off = PC_WAVE / 2; off > 0; off >>= 1) nb += __shfl_xor(nb, off);
+      total += __builtin_amdgcn_readfirstlane(nb);
+    }
+  }
+  const long long lo = total * part / n_parts, hi = total * (part + 1) / n_parts;
+  const long long w_lo = lo + (hi - lo) * wave / n_waves, w_hi = lo + (hi - lo) * (wave + 1) / n_waves;
+  if (w_lo >= w_hi) return c;
+  c.left = (int)(w_hi - w_lo);
+  if (!L.seg_len) {
+    c.s = (int)(w_lo / nb_full); c.blk = (int)(w_lo % nb_full); c.n_blk = nb_full; c.len = L.k_t;
+    c.valid = true;
+    return c;
+  }
+  long long base = 0;
+  for (int s0 = 0; s0 < L.n_seg; s0 += PC_WAVE) {
+    const int len = s0 + lane < L.n_seg ? L.len(s0 + lane) : 0;
+    const int nb = (len + 31) / 32;
+    int incl = nb;                                            // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int off = 1; off < PC_WAVE; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const long long rel = w_lo - base;                        // the run's first block, counted from this round's first segment
+    const unsigned long long hit = __ballot(nb > 0 && incl - nb <= rel && rel < incl);
+    if (hit) {
+      const int src = __ffsll((long long)hit) - 1;
+      c.s = s0 + src;
+      c.blk = __builtin_amdgcn_readfirstlane((int)rel - __shfl(incl - nb, src));
+      c.n_blk = __builtin_amdgcn_readfirstlane(__shfl(nb, src));
+      c.len = __builtin_amdgcn_readfirstlane(__shfl(len, src));
+      c.valid = true;
+      return c;
+    }
+    base += __builtin_amdgcn_readfirstlane(__shfl(incl, PC_WAVE - 1));
+  }
+  return c;                                                   // not reached: w_lo < total
+}
+__device__ __forceinline__ PcBlockCursor pc_blocks_next(const PcSegLens& L, PcBlockCursor c) {
+  if (--c.left <= 0) { c.valid = false; return c; }
+  if (++c.blk < c.n_blk) return c;
+  c.blk = 0;
+  for (++c.s; c.s < L.n_seg; ++c.s) {                         // the next segment that has keys
+    c.len = L.len(c.s);
+    c.n_blk = (c.len + 31) / 32;
+    if (c.n_blk > 0) return c;
+  }
+  c.valid = false;                                            // not reached: left counted real blocks
+  return c;
+}
 int pc_launch_kv_append(const void* k_new, const void* v_new, int batch, int n_new, int n_seg,
                         int seg, int k_t, int n_kv_heads, int head_dim, int pos0, float base,
                         void* kc, void* vc, int32_t* seg_len, int seg_len_per_head,

@@ -7,6 +7,7 @@ import torch
 
 import oracle
 import paper_2502_14317_amd as pc
+from paper_2502_14317_amd.layer import fp8_alloc, fp8_rows_view, fp8_from_rows
 from workloads import CFG4, f32_to_bf16_bits, bf16_bits_to_f64
 from helpers import (O_ATOL, O_RTOL, LSE_ATOL, bits_to_dev, dev_bf16_to_f64, assert_close)
 
@@ -23,14 +24,17 @@ def _mk(r, shape, s=1.0):
 
 def _quantize(kc_bits, vc_bits, seg_len, per_head):
     B, S, Hkv, kt, D = kc_bits.shape
-    k8 = torch.full((B, S, Hkv, kt, D), 0x55, dtype=torch.uint8, device="cuda")
-    v8 = torch.full_like(k8, 0x55)
+    k8 = fp8_alloc(B, S, Hkv, kt, D).fill_(0x55)              # codes: 32-key blocks in matrix-core order
+    v8 = fp8_alloc(B, S, Hkv, kt, D).fill_(0x55)
     ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda")
     vs = torch.empty_like(ks)
     pc.pc_kv_quantize_fp8(bits_to_dev(kc_bits), bits_to_dev(vc_bits),
                           None if seg_len is None else torch.from_numpy(seg_len).cuda(), B, S, kt, Hkv, D,
                           k8, v8, ks, vs, seg_len_per_head=per_head)
     torch.cuda.synchronize()
+    # keys behind k_t in the last block must be written too (code 0): the attention kernel reads whole blocks
+    for which, c8 in (("k", k8), ("v", v8)):
+        assert (fp8_rows_view(which, c8, kt, D, padded=True)[..., kt:, :] == 0).all(), "codes behind k_t are not zero"
     return k8, v8, ks, vs
 
 
@@ -49,8 +53,8 @@ def test_quantize_every_bf16_value_bit_exact():
     k8, v8, ks, vs = _quantize(bits, bits[:, :, :, ::-1].copy(), None, 0)
     rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(bits[0]), bf16_bits_to_f64(bits[0, :, :, ::-1]))
     assert ks.item() == 1.0 and vs.item() == 1.0 and rks[0, 0] == 1.0
-    np.testing.assert_array_equal(k8.cpu().numpy()[0], rk8)
-    np.testing.assert_array_equal(v8.cpu().numpy()[0], rv8)
+    np.testing.assert_array_equal(fp8_rows_view("k", k8, kt, D).cpu().numpy()[0], rk8)
+    np.testing.assert_array_equal(fp8_rows_view("v", v8, kt, D).cpu().numpy()[0], rv8)
 
 
 @pytest.mark.parametrize("D,per_head", [(128, 0), (64, 1)])
@@ -68,8 +72,8 @@ def test_quantize_random_segments_bit_exact(D, per_head):
         rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]), sl[b])
         np.testing.assert_array_equal(ks[b].cpu().numpy(), rks)
         np.testing.assert_array_equal(vs[b].cpu().numpy(), rvs)
-        np.testing.assert_array_equal(k8[b].cpu().numpy(), rk8)
-        np.testing.assert_array_equal(v8[b].cpu().numpy(), rv8)
+        np.testing.assert_array_equal(fp8_rows_view("k", k8[b], kt, D).cpu().numpy(), rk8)
+        np.testing.assert_array_equal(fp8_rows_view("v", v8[b], kt, D).cpu().numpy(), rv8)
 
 
 def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed):
@@ -172,11 +176,12 @@ def test_fp8_dequantisation_is_exact_for_every_code():
     lse = torch.empty((1, Hq, 1), dtype=torch.float32, device="cuda")
     for half in range(2):
         row = torch.from_numpy(codes[128 * half:128 * half + 128].copy()).cuda().view(1, 1, 1, 1, D)
+        krow, vrow = fp8_from_rows("k", row), fp8_from_rows("v", row)   # the key as a block of K and of V
         for d0 in range(0, D, Hq):
             q = np.zeros((1, 1, Hq, D), dtype=np.float32)
             for h in range(Hq):
                 q[0, 0, h, d0 + h] = 1.0
-            pc.pc_parallel_attn_fp8(bits_to_dev(f32_to_bf16_bits(q)), row, row, one, one, None, None, None, None, 0,
+            pc.pc_parallel_attn_fp8(bits_to_dev(f32_to_bf16_bits(q)), krow, vrow, one, one, None, None, None, None, 0,
                                     1, 1, 1, 1, Hq, 1, D, -1, 1.0e4, 1.0, out, lse, ws)
             torch.cuda.synchronize()
             want = vals[128 * half:128 * half + 128]
@@ -214,7 +219,7 @@ def test_fp8_decode_full_size_sampled():
     for b in range(B):
         kc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
         vc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
-    k8 = torch.empty(kc.shape, dtype=torch.uint8, device="cuda"); v8 = torch.empty_like(k8)
+    k8, v8 = fp8_alloc(B, S, Hkv, kt, D), fp8_alloc(B, S, Hkv, kt, D)
     ks = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); vs = torch.empty_like(ks)
     pc.pc_kv_quantize_fp8(kc, vc, None, B, S, kt, Hkv, D, k8, v8, ks, vs)
     q = torch.randn((B, 1, Hq, D), generator=g, device="cuda").to(bf)
@@ -230,8 +235,8 @@ def test_fp8_decode_full_size_sampled():
         kf = dev_bf16_to_f64(kc[b, :, gk])[:, None]          # [S, 1, kt, D]
         vf = dev_bf16_to_f64(vc[b, :, gk])[:, None]
         rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(kf, vf)
-        np.testing.assert_array_equal(k8[b, :, gk].cpu().numpy(), rk8[:, 0])
-        np.testing.assert_array_equal(v8[b, :, gk].cpu().numpy(), rv8[:, 0])
+        np.testing.assert_array_equal(fp8_rows_view("k", k8[b, :, gk], kt, D).cpu().numpy(), rk8[:, 0])
+        np.testing.assert_array_equal(fp8_rows_view("v", v8[b, :, gk], kt, D).cpu().numpy(), rv8[:, 0])
         np.testing.assert_array_equal(ks[b, :, gk].cpu().numpy(), rks[:, 0])
         qf = dev_bf16_to_f64(q[b, :, gk * G:(gk + 1) * G])
         ro, rl = oracle.global_attention_concat(qf, oracle.dequantize_kv_fp8(rk8, rks),
