@@ -28,9 +28,9 @@ PEAK_HBM_BYTES = 8.0e12       # MI355X HBM3E
 # counters read for a plain 1 GiB copy (2048 B per FETCH_SIZE count, 1024 B per WRITE_SIZE count);
 # commands and raw counts: profiles/pmc_hbm_traffic.md.  Keyed by (kernel, workload).
 MEASURED_TRAFFIC = {
-    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.2551e6 * 2048 + 1.0650e6 * 1024,
-    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.1032e6 * 2048 + 2.1e3 * 1024,
-    ("decode_attn_fp8_kernel", "cfg4_decode_llama3_8b"): 1.0518e6 * 2048 + 2.1e3 * 1024,
+    ("flash_fwd_kernel", "cfg1_llama3_8b_128k"): 1.2456e6 * 2048 + 1.0650e6 * 1024,
+    ("decode_attn_kernel", "cfg4_decode_llama3_8b"): 2.1146e6 * 2048 + 5.2e2 * 1024,
+    ("decode_attn_fp8_kernel", "cfg4_decode_llama3_8b"): 1.0490e6 * 2048 + 5.2e2 * 1024,
     ("kv_quantize_fp8_kernel", "cfg4_decode_llama3_8b"): 4.1805e6 * 2048 + 2.0974e6 * 1024,
     ("gather_kv_kernel", "cfg4_decode_llama3_8b"): 2.1136e6 * 2048 + 4.1944e6 * 1024,
     ("self_info_rows_kernel", "16x512x128256"): 1.0266e6 * 2048,
