@@ -197,6 +197,12 @@ def test_fp8_attention_many_ragged_groups():
     _attn_case("many-groups", 64, 1, 8, 48, 16, 8, 64, 0, -1, True, 5)
 
 
+def test_fp8_attention_more_segments_than_lanes():
+    """150 short ragged segments per group (the kernel walks the segment lengths 64 at a time to
+    find a wavefront's first block), with a 16-bit tail."""
+    _attn_case("150-segments", 2, 1, 150, 40, 8, 2, 128, 24, -1, True, 9)
+
+
 def test_fp8_attention_rejects_many_query_columns():
     one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(pc.PcError) as e:

@@ -202,6 +202,34 @@ def test_parallel_attn_decode_many_ragged_groups():
         assert_close(lse[b].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"lse[b={b}]")
 
 
+@pytest.mark.parametrize("per_head", [0, 1])
+def test_parallel_attn_decode_more_segments_than_lanes(per_head):
+    """150 short segments per group: the kernel's search for a wavefront's first block walks the
+    segment lengths 64 at a time; ragged lengths with many empty segments, blocks of fewer than 32
+    keys, and (per_head) a different length for every KV head."""
+    B, S, kt, Hq, Hkv, D = 2, 150, 40, 8, 2, 128
+    _say(f"parallel_attn 150 segments: B={B} S={S} kt={kt} H={Hq}/{Hkv} D={D} per_head={per_head}")
+    r = np.random.default_rng([15, 150, per_head])
+    mk = lambda shape, sc=1.0: f32_to_bf16_bits((r.standard_normal(shape) * sc).astype(np.float32))
+    q, kc, vc = mk((B, 1, Hq, D), 2.0), mk((B, S, Hkv, kt, D)), mk((B, S, Hkv, kt, D))
+    shape = (B, S, Hkv) if per_head else (B, S)
+    seg_len = r.integers(0, kt + 1, size=shape).astype(np.int32)
+    seg_len[r.random(shape) < 0.4] = 0
+    seg_len[0, :70] = 0                                      # the first round of 64 lengths holds no key
+    seg_len[1, 60:] = 0                                      # ... and here the later rounds hold none
+    out = torch.empty((B, 1, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(B, 1, S, kt, Hq, Hkv, D, 0))
+    pc.pc_parallel_attn(bits_to_dev(q), bits_to_dev(kc), bits_to_dev(vc), torch.from_numpy(seg_len).cuda(), None, None,
+                        B, 1, S, kt, Hq, Hkv, D, -1, 1.0e4, 0.0, out, lse, ws, seg_len_per_head=per_head)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ro, rl = oracle.global_attention_concat(bf16_bits_to_f64(q[b]), bf16_bits_to_f64(kc[b]), bf16_bits_to_f64(vc[b]),
+                                                seg_len=seg_len[b])
+        assert_close(dev_bf16_to_f64(out[b]), ro, O_ATOL, O_RTOL, f"out[b={b}]")
+        assert_close(lse[b].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"lse[b={b}]")
+
+
 def test_parallel_attn_query_block():
     _parallel_attn_case("block", 1, 104, 3, 200, 8, 2, 128, True, 600, False, 6)
     _parallel_attn_case("block-ragged64", 2, 300, 2, 130, 4, 4, 64, True, -1, True, 7)
