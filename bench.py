@@ -148,6 +148,54 @@ def bench_flash_zero_operands(pc, torch, cfg, layer, qd, kd, vd, steps):
             "frac_of_peak": flash_flops(cfg) / avg / PEAK_BF16_FLOPS}
 
 
+def bench_chunk_scaling(pc, torch, reps=3):
+    """The shape of the paper's throughput table (prefill and per-token time against the number
+    of parallel chunks, with the chunks' KV whole or compressed to half), per layer and on
+    synthetic data: Llama-2-7B shape (32 MHA heads of 128, 3584-token chunks + 512 query rows).
+    Prefill = chunk-batched local attention + scores for C chunks in one launch; generation = one
+    decode-attention step for one sequence over the C chunks' retained keys."""
+    from paper_2502_14317_amd.layer import ParallelCompLayer
+    w, wq, H, D = 3584, 512, 32, 128
+    L = w + wq
+    bf = torch.bfloat16
+    g = torch.Generator(device="cuda").manual_seed(7)
+    rows = []
+    for C in (1, 4, 8, 12, 16, 20, 23):
+        q = (torch.randn((C, L, H, D), generator=g, device="cuda") * 0.09).to(bf)
+        k = (torch.randn((C, L, H, D), generator=g, device="cuda") * 0.09).to(bf)
+        v = (torch.randn((C, L, H, D), generator=g, device="cuda") * 0.09).to(bf)
+        layer = ParallelCompLayer(C, w, wq, H, H, D, 32, 1.0e4, 0, 0)
+        layer.chunk_prefill(q, k, v, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            layer.chunk_prefill(q, k, v, True)
+        torch.cuda.synchronize()
+        row = {"chunks": C, "prefill_ms": (time.perf_counter() - t0) / reps * 1e3}
+        del layer, q
+        qd = (torch.randn((1, 1, H, D), generator=g, device="cuda") * 0.09).to(bf)
+        out = torch.empty((1, 1, H, D), dtype=bf, device="cuda")
+        for name, kt in (("whole", w), ("half", w // 2)):
+            kc = k[:, :kt].permute(0, 2, 1, 3).contiguous().view(1, C, H, kt, D)
+            vc = v[:, :kt].permute(0, 2, 1, 3).contiguous().view(1, C, H, kt, D)
+            ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(1, 1, C, kt, H, H, D, 0))
+            run = lambda: pc.pc_parallel_attn(qd, kc, vc, None, None, None, 1, 1, C, kt, H, H, D, -1, 1.0e4, 0.0,
+                                              out, None, ws)
+            run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10 * reps):
+                run()
+            torch.cuda.synchronize()
+            row[f"generation_ms_per_token_{name}"] = (time.perf_counter() - t0) / (10 * reps) * 1e3
+            row[f"kv_mb_{name}"] = 2.0 * C * H * kt * D * 2 / 1e6
+            del kc, vc, ws
+        rows.append(row)
+        del k, v
+        torch.cuda.empty_cache()
+    return {"workload": "Llama-2-7B shape, C chunks x (3584 + 512) rows, one layer, synthetic", "rows": rows}
+
+
 def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
@@ -582,6 +630,7 @@ def main():
         if args.workload == "cfg1_llama3_8b_128k":
             result["other_configs"] = {n: bench_other_config(pc, torch, n) for n in
                                        ("cfg0_tiny_mha", "cfg2_llama2_7b_128k", "cfg3_llama3_8b_512k_stress")}
+        result["chunk_scaling"] = bench_chunk_scaling(pc, torch)
         result["ceilings"] = bench_ceilings(pc, torch)
         print(f"[bench] secondary done; ceilings {result['ceilings']}", file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:
