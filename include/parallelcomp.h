@@ -224,7 +224,7 @@ int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_
  *     + m of key 4 g + j (j < 4) or 16 + 4 g + (j - 4) (j >= 4) of the block.
  *   k_scale, v_scale [B, S, H_kv] fp32 out.   Pointers 16-byte aligned.  No workspace.
  *   B = 0 or S = 0 is a no-op (pointers are not looked at).
- * pc_parallel_attn_fp8: pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 8, else
+ * pc_parallel_attn_fp8: pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 16, else
  * PC_ERR_UNSUPPORTED) over the 8-bit segments plus, optionally, one 16-bit tail segment (the
  * query block and the generated tokens, grown by pc_kv_append with n_seg = 1):
  *   k_tail, v_tail [B, 1, H_kv, tail_cap, D] bf16 rotated, tail_len [B] int32 (device); all

@@ -398,7 +398,8 @@ static int launch_decode8_d(const PcDecode8Args& a, int batch, int nq_pad, hipSt
   dim3 grid((unsigned)blocks), block(PC_D8_WAVES * PC_WAVE);
   PcProfScope prof(PC_KERNEL_DECODE_FP8, st);
   if (nq_pad == 4) hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 4>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 8>), grid, block, 0, st, a);
+  else if (nq_pad == 8) hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 8>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((decode_attn_fp8_kernel<D, 16>), grid, block, 0, st, a);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }
@@ -417,7 +418,8 @@ int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, cons
   a.n_parts = n_parts;
   a.scale_log2 = scale * PC_D8_LOG2E;
   const int cols = n_q * (n_q_heads / n_kv_heads);
-  if (cols > 8) return PC_ERR_UNSUPPORTED;
-  return head_dim == 128 ? launch_decode8_d<128>(a, batch, cols <= 4 ? 4 : 8, st)
-                         : launch_decode8_d<64>(a, batch, cols <= 4 ? 4 : 8, st);
+  if (cols > 16) return PC_ERR_UNSUPPORTED;               // the columns of one 16x16x32 MFMA
+  const int nq_pad = cols <= 4 ? 4 : (cols <= 8 ? 8 : 16);
+  return head_dim == 128 ? launch_decode8_d<128>(a, batch, nq_pad, st)
+                         : launch_decode8_d<64>(a, batch, nq_pad, st);
 }

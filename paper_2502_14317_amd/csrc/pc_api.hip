@@ -260,7 +260,7 @@ static int check_par8(int batch, int n_q, int n_seg, int k_t, int tail_cap, int 
   if (D != 64 && D != 128) return PC_ERR_SHAPE;
   if (k_t > (1 << 24) || tail_cap > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
   if (n_seg == 0 && tail_cap == 0) return PC_ERR_SHAPE;
-  if ((long long)n_q * (n_q_heads / n_kv_heads) > 8) return PC_ERR_UNSUPPORTED;
+  if ((long long)n_q * (n_q_heads / n_kv_heads) > 16) return PC_ERR_UNSUPPORTED;
   return PC_OK;
 }
 

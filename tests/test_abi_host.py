@@ -103,9 +103,9 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert call(one, None, None, pa, 1 << 30) == -1
     assert call(one, one, None, pa, 8) == -3
     assert call(one, one, None, (16,) + pa[1:], 1 << 30) == -1                  # tail_cap > 0 without a tail
-    assert call(one, one, None, (0, 1, 3, 2, 64, 8, 2, 128, -1), 1 << 30) == -5  # 12 query columns
+    assert call(one, one, None, (0, 1, 5, 2, 64, 8, 2, 128, -1), 1 << 30) == -5  # 20 query columns
     assert call(one, one, None, (0, 1, 1, 0, 64, 8, 2, 128, -1), 1 << 30) == -2  # nothing to attend to
-    assert pc.pc_parallel_attn_fp8_workspace_bytes(1, 3, 2, 64, 0, 8, 2, 128) == 0
+    assert pc.pc_parallel_attn_fp8_workspace_bytes(1, 5, 2, 64, 0, 8, 2, 128) == 0
     a8 = pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 0, 8, 2, 128)
     assert 0 < a8 < pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 512, 8, 2, 128)
 

@@ -125,6 +125,7 @@ def test_fp8_attention_gqa_with_tail():
 def test_fp8_attention_mha64_and_two_rows():
     _attn_case("mha64", 3, 1, 3, 333, 4, 4, 64, 0, -1, True, 2)
     _attn_case("nq2-g4", 1, 2, 2, 2048, 8, 2, 128, 1500, -1, False, 3)
+    _attn_case("nq4-g4", 2, 4, 3, 300, 8, 2, 128, 64, 9, True, 6)            # 16 query columns
     _attn_case("tail-only", 2, 1, 0, 64, 4, 2, 64, 40, 7, False, 4)
 
 
@@ -206,7 +207,7 @@ def test_fp8_attention_more_segments_than_lanes():
 def test_fp8_attention_rejects_many_query_columns():
     one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
     with pytest.raises(pc.PcError) as e:
-        pc.pc_parallel_attn_fp8(one, one, one, one, one, None, None, None, None, 0, 1, 4, 1, 64, 32, 8, 128,
+        pc.pc_parallel_attn_fp8(one, one, one, one, one, None, None, None, None, 0, 1, 5, 1, 64, 32, 8, 128,
                                 -1, 1.0e4, 0.0, one, None, one)
     assert e.value.status == -5                             # PC_ERR_UNSUPPORTED
 
