@@ -43,6 +43,12 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_select_chunks_topk(one, 4, 5, one, None, None) == -2
     assert L.pc_select_chunks_topk(one, 0, 0, one, None, None) == -2
     assert L.pc_select_chunks_topk(one, 5000, 1, one, None, None) == -2
+    # ceiling kernel (measurement aid): mode, sizes and scratch are checked before the launch
+    fl = ctypes.c_double(0.0)
+    assert L.pc_mfma_ceiling(0, 256, 10, None, 1 << 20, ctypes.byref(fl), None) == -1
+    assert L.pc_mfma_ceiling(3, 256, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
+    assert L.pc_mfma_ceiling(2, 0, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
+    assert L.pc_mfma_ceiling(2, 256, 10, one, 1024, ctypes.byref(fl), None) == -3
     # select tokens
     assert L.pc_select_tokens_topk(None, None, 1, 1, 8, 2, one, None) == -1
     assert L.pc_select_tokens_topk(one, None, 1, 1, 8, 9, one, None) == -2
