@@ -247,6 +247,31 @@ size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_q, int32_t 
                                             int32_t tail_cap, int32_t n_q_heads, int32_t n_kv_heads,
                                             int32_t head_dim);
 
+/* ---- Eq. 9-11 for callers that cannot allocate ----------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:
+ * pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 16: the decoding stage), with the
+ * scratch memory (rotated query + per-workgroup partial results) in a fixed array inside the
+ * library instead of a caller workspace.  Calls no hipMalloc / hipFree / allocating routine.
+ * Same arguments, arithmetic and results as pc_parallel_attn (the same kernels run), except:
+ *   - no ws / ws_bytes;
+ *   - PC_ERR_UNSUPPORTED when n_q * H_q / H_kv > 16 (the tile path's K/V images do not fit);
+ *   - PC_ERR_WORKSPACE when the request needs more than PC_STATIC_SCRATCH_BYTES, i.e. when
+ *     pc_parallel_attn_workspace_bytes(...) of the same shape exceeds it
+ *     (the decode config, 16 sequences x 32 heads x 128, 2 partials per group, needs 0.63 MiB).
+ * Each GPU holds one such array from the moment the library is loaded until the process ends;
+ * its address is looked up on the first call on a device.  All calls on one GPU share the array:
+ * calls whose kernels overlap on a GPU (different streams, several threads) race; calls on one
+ * stream are ordered and safe.  Every byte the call reads from the array it has written first,
+ * so the previous call's contents do not matter. */
+#define PC_STATIC_SCRATCH_BYTES (4u << 20)
+int pc_parallel_attn_static(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
+                            int32_t seg_len_per_head, const void* k_self, const void* v_self,
+                            int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t q_pos0,
+                            float rope_base, float softmax_scale, void* out, float* lse_out,
+                            void* stream);
+size_t pc_parallel_attn_static_max_bytes(void);   /* = PC_STATIC_SCRATCH_BYTES */
+
 /* ---- housekeeping -------------------------------------------------------------------------- */
 const char* pc_status_string(int status);   /* static string, never NULL                       */
 int         pc_last_hip_error(void);        /* hipError_t of the last PC_ERR_HIP on this thread */

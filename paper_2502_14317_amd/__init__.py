@@ -8,4 +8,5 @@ from .binding import (lib, make_shape, alloc_workspace, pc_shape, PcError, SYMBO
                       pc_gather_kv, pc_kv_append, pc_kv_quantize_fp8, pc_parallel_attn_fp8,
                       pc_parallel_attn_fp8_workspace_bytes,
                       pc_parallel_attn, pc_parallel_attn_workspace_bytes,
+                      pc_parallel_attn_static, pc_parallel_attn_static_max_bytes,
                       pc_profile_begin, pc_profile_end, pc_profile_records, pc_mfma_ceiling)

@@ -23,7 +23,7 @@ SYMBOLS = [
     "pc_last_hip_error", "pc_version", "pc_profile_begin", "pc_profile_end", "pc_profile_count",
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
     "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
-    "pc_profile_begin_kernel",
+    "pc_profile_begin_kernel", "pc_parallel_attn_static", "pc_parallel_attn_static_max_bytes",
 ]
 
 
@@ -74,6 +74,10 @@ def lib():
     L.pc_select_tokens_calibrated.argtypes = [P, P] + [c_int32] * 4 + [c_float, c_int32, c_int32, P, P, P, P]
     L.pc_select_tokens_calibrated.restype = c_int
     L.pc_parallel_attn.restype = c_int
+    L.pc_parallel_attn_static.argtypes = [P] * 4 + [c_int32, P, P] + [c_int32] * 8 + [c_float, c_float, P, P, P]
+    L.pc_parallel_attn_static.restype = c_int
+    L.pc_parallel_attn_static_max_bytes.argtypes = []
+    L.pc_parallel_attn_static_max_bytes.restype = c_size_t
     L.pc_parallel_attn_workspace_bytes.argtypes = [c_int32] * 8
     L.pc_parallel_attn_workspace_bytes.restype = c_size_t
     L.pc_status_string.argtypes = [c_int]
@@ -204,6 +208,20 @@ def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t,
                                   _ptr(v_self), batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads,
                                   head_dim, q_pos0, rope_base, softmax_scale, _ptr(out),
                                   _ptr(lse_out), p, n, _stream()), "pc_parallel_attn")
+
+
+def pc_parallel_attn_static(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t, n_q_heads,
+                            n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out, lse_out,
+                            seg_len_per_head=0):
+    _check(lib().pc_parallel_attn_static(_ptr(q), _ptr(kc), _ptr(vc), _ptr(seg_len),
+                                         int(seg_len_per_head), _ptr(k_self), _ptr(v_self), batch,
+                                         n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, q_pos0,
+                                         rope_base, softmax_scale, _ptr(out), _ptr(lse_out),
+                                         _stream()), "pc_parallel_attn_static")
+
+
+def pc_parallel_attn_static_max_bytes():
+    return int(lib().pc_parallel_attn_static_max_bytes())
 
 
 def pc_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_dim, pos0, rope_base,

@@ -2,6 +2,7 @@
 // Every host-visible argument is checked before any GPU work is enqueued.
 #include "pc_common.h"
 #include <math.h>
+#include <mutex>
 
 static thread_local int g_last_hip_error = 0;
 void pc_set_hip_error(int err) { g_last_hip_error = err; }
@@ -431,25 +432,34 @@ extern "C" size_t pc_parallel_attn_workspace_bytes(int32_t batch, int32_t n_q, i
   return par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, has_self).total;
 }
 
-extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
-                                int32_t seg_len_per_head, const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
-                                int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
-                                int32_t head_dim, int32_t q_pos0, float rope_base,
-                                float softmax_scale, void* out, float* lse_out, void* ws,
-                                size_t ws_bytes, void* stream) {
+// Host-visible argument checks shared by pc_parallel_attn and its no-allocation variant.
+static int check_par_args(const void* q, const void* kc, const void* vc, int32_t seg_len_per_head,
+                          const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                          int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t head_dim, int32_t q_pos0, float rope_base, float softmax_scale,
+                          const void* out) {
   int rc = check_par(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim);
   if (rc != PC_OK) return rc;
   if (!q || !out) return PC_ERR_NULL;
   if (n_seg > 0 && (!kc || !vc)) return PC_ERR_NULL;
   if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
   if ((k_self == nullptr) != (v_self == nullptr)) return PC_ERR_NULL;
-  const int has_self = k_self != nullptr;
-  if (n_seg == 0 && !has_self) return PC_ERR_SHAPE;
+  if (n_seg == 0 && k_self == nullptr) return PC_ERR_SHAPE;
   if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
   if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
+  return PC_OK;
+}
+
+// Enqueues the kernels of Eq. 9-11 on a validated request; ws holds at least w.total bytes.
+static int parallel_attn_run(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
+                             int32_t seg_len_per_head, const void* k_self, const void* v_self,
+                             int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
+                             int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int32_t q_pos0, float rope_base, float softmax_scale, void* out,
+                             float* lse_out, const ParWs& w, void* ws, void* stream) {
+  int rc;
+  const int has_self = k_self != nullptr;
   const int D = head_dim;
-  const ParWs w = par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, D, has_self);
-  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
   const float scale = eff_scale(softmax_scale, D);
@@ -508,4 +518,74 @@ extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, c
   }
   return pc_launch_merge(part_o, part_lse, q_rot, nullptr, nullptr, out, lse_out, batch, n_q,
                          n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
+}
+
+extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
+                                int32_t seg_len_per_head, const void* k_self, const void* v_self, int32_t batch, int32_t n_q,
+                                int32_t n_seg, int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t head_dim, int32_t q_pos0, float rope_base,
+                                float softmax_scale, void* out, float* lse_out, void* ws,
+                                size_t ws_bytes, void* stream) {
+  const int rc = check_par_args(q, kc, vc, seg_len_per_head, k_self, v_self, batch, n_q, n_seg, k_t,
+                                n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out);
+  if (rc != PC_OK) return rc;
+  const ParWs w = par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim,
+                                k_self != nullptr);
+  if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
+  return parallel_attn_run(q, kc, vc, seg_len, seg_len_per_head, k_self, v_self, batch, n_q, n_seg,
+                           k_t, n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale,
+                           out, lse_out, w, ws, stream);
+}
+
+// ---------------------------------------------------------------------------- no-allocation variant
+// The scratch memory of pc_parallel_attn_static: one array per GPU, part of the loaded code
+// object, alive until the process ends.  `scratch` names it in device code only; host code uses
+// the per-device address that hipGetSymbolAddress returns (the array sits at a different address
+// on every GPU).
+static __device__ __align__(256) unsigned char scratch[PC_STATIC_SCRATCH_BYTES];
+
+#define PC_MAX_DEVICES 64
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[PC_MAX_DEVICES];     // by device ordinal; nullptr = not resolved yet
+
+// Address of `scratch` on the current device (resolved once per device, with that device current).
+static int static_scratch(void** ptr) {
+  int dev = -1;
+  PC_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= PC_MAX_DEVICES) return PC_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    PC_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr || !pc_aligned(p, kAlign)) return PC_ERR_WORKSPACE;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return PC_OK;
+}
+
+extern "C" size_t pc_parallel_attn_static_max_bytes(void) { return PC_STATIC_SCRATCH_BYTES; }
+
+extern "C" int pc_parallel_attn_static(const void* q, const void* kc, const void* vc,
+                                       const int32_t* seg_len, int32_t seg_len_per_head,
+                                       const void* k_self, const void* v_self, int32_t batch,
+                                       int32_t n_q, int32_t n_seg, int32_t k_t, int32_t n_q_heads,
+                                       int32_t n_kv_heads, int32_t head_dim, int32_t q_pos0,
+                                       float rope_base, float softmax_scale, void* out,
+                                       float* lse_out, void* stream) {
+  int rc = check_par_args(q, kc, vc, seg_len_per_head, k_self, v_self, batch, n_q, n_seg, k_t,
+                          n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale, out);
+  if (rc != PC_OK) return rc;
+  const ParWs w = par_ws_layout(batch, n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim,
+                                k_self != nullptr);
+  if (!w.small) return PC_ERR_UNSUPPORTED;                  // the tile path needs K/V images: too large
+  if (w.total > PC_STATIC_SCRATCH_BYTES) return PC_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != PC_OK) return rc;
+  // every byte of the scratch that the merge reads is written by this call's kernels first
+  // (rotated q, one partial per workgroup), so nothing has to be cleared
+  return parallel_attn_run(q, kc, vc, seg_len, seg_len_per_head, k_self, v_self, batch, n_q, n_seg,
+                           k_t, n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale,
+                           out, lse_out, w, ws, stream);
 }

@@ -86,6 +86,14 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_parallel_attn(one, one, one, one, 2, None, None, *args, one, None, one, 1 << 30, None) == -2
     bad_args = (1, 1, 2, 64, 8, 3, 128, -1, 1e4, 0.0)
     assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
+    # the variant that allocates nothing: same checks, plus its own limits (all on the host)
+    assert L.pc_parallel_attn_static(None, one, one, None, 0, None, None, *args, one, None, None) == -1
+    assert L.pc_parallel_attn_static(one, one, one, None, 0, None, None, *bad_args, one, None, None) == -2
+    many_rows = (1, 64, 2, 64, 8, 2, 128, -1, 1e4, 0.0)     # 64 query rows: the tile path
+    assert L.pc_parallel_attn_static(one, one, one, None, 0, None, None, *many_rows, one, None, None) == -5
+    too_big = (4096, 1, 2, 64, 32, 8, 128, -1, 1e4, 0.0)    # partials beyond the fixed scratch
+    assert pc.pc_parallel_attn_workspace_bytes(4096, 1, 2, 64, 32, 8, 128, 0) > pc.pc_parallel_attn_static_max_bytes()
+    assert L.pc_parallel_attn_static(one, one, one, None, 0, None, None, *too_big, one, None, None) == -3
     # decoding stage: append to the tail segment
     ok = (2, 1, 3, 2, 64, 2, 128, 10, 1e4)          # batch, n_new, n_seg, seg, k_t, H_kv, D, pos0, base
     assert L.pc_kv_append(None, one, *ok, one, one, one, 0, None) == -1
