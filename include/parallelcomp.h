@@ -73,8 +73,10 @@ typedef struct pc_shape {
  *          follow the context directly, at positions chunk_lens[c] + t.  Rows behind a short
  *          sequence are padding: o and lse there are not written, tok_score of the missing
  *          tokens is 0, k_rope there is unspecified.  NULL => every chunk has w rows.
- * Arithmetic: bf16 MFMA products of the bf16-rounded rotated q and k, fp32 softmax and
- * accumulation.  Workspace: pc_chunk_prefill_workspace_bytes(shape). */
+ * Arithmetic: bf16 MFMA products, fp32 softmax and accumulation.  The operands are the rotated
+ * k rounded to bf16 (the cache's precision) and the rotated q multiplied by scale * log2(e) in
+ * fp32 and then rounded to bf16, once; probabilities are rounded to bf16 for the second product.
+ * Workspace: pc_chunk_prefill_workspace_bytes(shape). */
 int pc_chunk_prefill_attn(const pc_shape* shape, const void* q, const void* k, const void* v,
                           const int32_t* chunk_lens, void* o, float* lse, void* k_rope, float* tok_score,
                           float* chunk_score, void* ws, size_t ws_bytes, void* stream);
@@ -172,7 +174,10 @@ int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
  *   k_self, v_self [B, n_q, H_kv, D] bf16 rotated keys / values of the query rows, both NULL
  *     for no self segment (decode)
  *   out [B, n_q, H_q, D] bf16;  lse_out [B, H_q, n_q] fp32, nullable.
- * n_q * (H_q / H_kv) <= 16 runs the HBM-bound split-KV kernel; larger n_q the MFMA tile kernel.
+ * n_q * (H_q / H_kv) <= 16 runs the HBM-bound split-KV kernel (bf16 operands as given, scale
+ * applied to the fp32 logits); larger n_q the MFMA tile kernel, whose query operand is the rotated
+ * q times scale * log2(e), rounded to bf16 once when q_pos0 >= 0 (a q that arrives rotated,
+ * q_pos0 < 0, is scaled and rounded a second time).
  * Workspace: pc_parallel_attn_workspace_bytes(...). */
 int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,
                      int32_t seg_len_per_head, const void* k_self, const void* v_self, int32_t batch, int32_t n_q,

@@ -353,32 +353,36 @@ __global__ __launch_bounds__(D) void merge_kernel(PcMergeArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Rotate the query rows of the global attention at positions pos0 + t (fp64 angles).
+// Rotate the query rows of the global attention at positions pos0 + t (fp64 angles; pos0 < 0:
+// the rows are already rotated) and multiply them by `mul` before the one rounding to bf16 (the
+// tile kernel wants its query operand scaled by softmax scale x log2(e); 1 for the split-KV kernel).
 __global__ void rope_q_kernel(const uint16_t* __restrict__ q, uint16_t* __restrict__ q_rot,
                               long long n_pairs, int n_q, int n_heads, int D, int pos0,
-                              double log_base) {
+                              double log_base, double mul) {
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_pairs) return;
   const int half = D / 2;
   const int i = (int)(idx % half);
   const long long row = idx / half;                       // (b, t, h)
   const int t = (int)((row / n_heads) % n_q);
-  const double theta = exp(-2.0 * (double)i / (double)D * log_base);
-  double sn, cs;
-  sincos((double)(pos0 + t) * theta, &sn, &cs);
-  const float x1 = bf16_bits_to_f32(q[row * D + i]), x2 = bf16_bits_to_f32(q[row * D + i + half]);
-  q_rot[row * D + i] = (uint16_t)f32_to_bf16_bits((float)(x1 * cs - x2 * sn));
-  q_rot[row * D + i + half] = (uint16_t)f32_to_bf16_bits((float)(x2 * cs + x1 * sn));
+  double sn = 0.0, cs = 1.0;
+  if (pos0 >= 0) {
+    const double theta = exp(-2.0 * (double)i / (double)D * log_base);
+    sincos((double)(pos0 + t) * theta, &sn, &cs);
+  }
+  const double x1 = bf16_bits_to_f32(q[row * D + i]), x2 = bf16_bits_to_f32(q[row * D + i + half]);
+  q_rot[row * D + i] = (uint16_t)f32_to_bf16_bits((float)((x1 * cs - x2 * sn) * mul));
+  q_rot[row * D + i + half] = (uint16_t)f32_to_bf16_bits((float)((x2 * cs + x1 * sn) * mul));
 }
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
-                     int pos0, float base, hipStream_t st) {
+                     int pos0, float base, float mul, hipStream_t st) {
   const long long n_pairs = n_rows * (D / 2);
   if (n_pairs == 0) return PC_OK;
   PcProfScope prof(PC_KERNEL_ROPE_Q, st);
   hipLaunchKernelGGL(rope_q_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)q, (uint16_t*)q_rot, n_pairs, n_q, n_heads, D, pos0,
-                     log((double)base));
+                     log((double)(pos0 >= 0 ? base : 2.0f)), (double)mul);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }

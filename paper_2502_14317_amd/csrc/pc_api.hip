@@ -300,7 +300,7 @@ extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v
   const void* q_rot = q;
   if (q_pos0 >= 0) {
     rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
-                          q_pos0, rope_base, st);
+                          q_pos0, rope_base, 1.0f, st);
     if (rc != PC_OK) return rc;
     q_rot = base + w.q_rot;
   }
@@ -464,10 +464,14 @@ static int parallel_attn_run(const void* q, const void* kc, const void* vc, cons
   char* base = (char*)ws;
   const float scale = eff_scale(softmax_scale, D);
 
+  // Query operand.  Split-KV path: the rotated rows (the scale is applied to the fp32 logits).
+  // Tile path: rotated and multiplied by scale * log2(e) before the one rounding to bf16, so the
+  // matrix cores deliver logits in log2 units (rows that arrive already rotated, q_pos0 < 0, are
+  // only scaled: their bf16 values are rounded a second time).
   const void* q_rot = q;
-  if (q_pos0 >= 0) {
+  if (q_pos0 >= 0 || !w.small) {
     rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
-                          q_pos0, rope_base, st);
+                          q_pos0, rope_base, w.small ? 1.0f : scale * 1.4426950408889634f, st);
     if (rc != PC_OK) return rc;
     q_rot = base + w.q_rot;
   }

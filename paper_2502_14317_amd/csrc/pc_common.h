@@ -120,7 +120,8 @@ struct PcFlashArgs {
   const void* q;            // [n_seq, n_rows, H_q, D] bf16
   const void* k_img;        // K tile images (rotated keys), image index = seq * img_seq_stride +
   const void* v_img;        //   part * img_part_stride + head * img_head_stride + tile; V^T likewise
-  const float2* table;      // rope table (rotate q at q_pos0 + row) or nullptr (q already rotated)
+  const float2* table;      // rope table (rotate q at q_pos0 + row, then scale), or nullptr: q is
+                            //   already rotated AND already multiplied by scale * log2(e)
   void* o;                  // [n_seq, n_rows, H_q, D] bf16 (final output mode)
   float* lse;               // [n_seq, H_q, n_rows] or nullptr
   float* part_o;            // partial mode: [n_seq, n_parts_total, n_rows, H_q, D] fp32, else nullptr
@@ -147,7 +148,7 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
                      void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st);
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
-                     int pos0, float base, hipStream_t st);
+                     int pos0, float base, float mul, hipStream_t st);
 // How the split-KV decode kernels cut the keys into workgroups (n_bg = batch * H_kv): the keys of
 // a (sequence, KV head) group, all its segments laid end to end in blocks of 32 keys, are cut
 // into n_parts equal runs of blocks, one workgroup (and one partial result) each.

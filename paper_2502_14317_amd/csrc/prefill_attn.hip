@@ -310,11 +310,9 @@ __global__ __launch_bounds__(PC_FA_THREADS, 2) void flash_fwd_kernel(PcFlashArgs
     } else {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
+        // already rotated and scaled by the caller (rounded to bf16 once, there)
         const u32x4 x = *(const u32x4*)(qrow + 16 * ks + 8 * hf);
-        u32x4 y;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = pack_bf16x2(bf16_lo_to_f32(x[e]) * c_log2, bf16_hi_to_f32(x[e]) * c_log2);
-        bq[nb][ks] = *(bf16x8*)&y;
+        bq[nb][ks] = *(bf16x8*)&x;
       }
     }
   }
