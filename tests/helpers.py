@@ -57,3 +57,58 @@ def assert_selection_matches(gpu_idx, ref_idx, ref_score, what):
         assert gap <= SEL_GAP * abs(kth), (f"{what}: index {i} differs, oracle score "
                                            f"{ref_score[i]!r} vs k-th {kth!r} (gap {gap:.3e})")
     return len(gs ^ rs)
+
+
+# ------------------------------------------------------------------ informative full-size checks
+def sample_rows(cfg):
+    """Rows of a chunk sequence the full-size tests evaluate the oracle on: tile and chunk
+    boundaries plus seeded random rows."""
+    L, w = cfg.seq_len, cfg.chunk_len
+    fixed = [0, 1, 31, 32, 63, 64, 255, 256, 257, L // 2, w - 1, w, w + 1, L - 33, L - 2, L - 1]
+    rng = np.random.default_rng([99, cfg.cfg_id])
+    return np.unique(np.concatenate([np.array(fixed), rng.integers(0, L, size=16)]))
+
+
+def assert_informative(ref_o, what):
+    """The reference must carry signal: the median magnitude of the sampled outputs is at least
+    five times the absolute tolerance, so a check on it cannot pass on zeros or on a flat mean."""
+    med = float(np.median(np.abs(ref_o)))
+    assert med >= 5 * O_ATOL, f"{what}: median |ref| {med:.3e} is below 5 x the absolute tolerance"
+    return med
+
+
+def rejects(gpu, ref, atol, rtol):
+    """True iff assert_close(gpu, ref, ...) raises."""
+    try:
+        assert_close(gpu, ref, atol, rtol, "probe")
+    except AssertionError:
+        return True
+    return False
+
+
+def pinned_tiles(P, o, lse, v, tile=64):
+    """Which key tiles do the sampled rows pin?  P [n_rows, H_q, L] the oracle's probabilities,
+    o [n_rows, H_q, D] and lse its outputs, v [L, H_kv, D].  For every (row, head) and every
+    `tile`-key tile, the output the row would have if that tile's keys were missing is
+    (o - m_t o_t) / (1 - m_t) with m_t the tile's mass and o_t its own weighted mean, and the
+    logsumexp moves by log(1 - m_t).  Returns a boolean [n_tiles]: True where for at least one
+    sampled (row, head) the output without the tile falls outside the outputs' tolerance, or the
+    logsumexp outside its own, i.e. where the parity check fails if the kernel drops that tile."""
+    n, Hq, L = P.shape
+    Hkv = v.shape[1]
+    G = Hq // Hkv
+    nt = (L + tile - 1) // tile
+    pin = np.zeros(nt, dtype=bool)
+    pad = nt * tile - L
+    for h in range(Hq):
+        p = np.pad(P[:, h, :], ((0, 0), (0, pad)))                        # [n, nt * tile]
+        vv = np.pad(v[:, h // G, :], ((0, pad), (0, 0)))                   # [nt * tile, D]
+        m = p.reshape(n, nt, tile).sum(axis=2)                            # [n, nt]
+        part = np.einsum("ntk,tkd->ntd", p.reshape(n, nt, tile), vv.reshape(nt, tile, -1))
+        ok = m < 1.0 - 1e-9                                               # a tile holding everything: no output left
+        denom = np.where(ok, 1.0 - m, 1.0)
+        without = (o[:, h, None, :] - part) / denom[..., None]
+        bad_o = (np.abs(without - o[:, h, None, :]) > O_ATOL + O_RTOL * np.abs(o[:, h, None, :])).any(axis=2)
+        bad_l = -np.log(denom) > LSE_ATOL + 1e-3 * np.abs(lse[:, h, None])
+        pin |= ((bad_o | bad_l) & ok).any(axis=0)
+    return pin

@@ -9,9 +9,10 @@ import torch
 import oracle
 import paper_2502_14317_amd as pc
 from paper_2502_14317_amd.layer import ParallelCompLayer
-from workloads import CFG1, CFG2, CFG3, CFG4, prefill_inputs, bf16_bits_to_f64
+from workloads import CFG1, CFG2, CFG3, CFG4, CFG1P, CFG2P, CFG3P, prefill_inputs, bf16_bits_to_f64
 from helpers import (O_ATOL, O_RTOL, S_RTOL, S_ATOL, LSE_ATOL, bits_to_dev, dev_to_bits,
-                     dev_bf16_to_f64, assert_close, assert_selection_matches)
+                     dev_bf16_to_f64, assert_close, assert_selection_matches, sample_rows,
+                     assert_informative, pinned_tiles)
 
 pytestmark = pytest.mark.gpu
 
@@ -20,24 +21,30 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _sample_rows(cfg):
-    L, w = cfg.seq_len, cfg.chunk_len
-    fixed = [0, 1, 31, 32, 63, 64, 255, 256, 257, L // 2, w - 1, w, w + 1, L - 33, L - 2, L - 1]
-    rng = np.random.default_rng([99, cfg.cfg_id])
-    return np.unique(np.concatenate([np.array(fixed), rng.integers(0, L, size=16)]))
-
-
-def _check_prefill_samples(cfg, layer, q, k, v, chunks, score_chunks):
-    """Sampled rows of o / lse / k_rope and whole score tensors of the given chunks."""
+def _check_prefill_samples(cfg, layer, q, k, v, chunks, score_chunks, informative=False):
+    """Sampled rows of o / lse / k_rope and whole score tensors of the given chunks.  With
+    informative=True (the peaked inputs) the reference outputs must carry signal and the sampled
+    rows must pin every key tile: see helpers.assert_informative / pinned_tiles."""
     pos = np.arange(cfg.seq_len)
-    rows = _sample_rows(cfg)
+    rows = sample_rows(cfg)
     ref_tok = {}
+    pin = None
     for c in sorted(set(chunks) | set(score_chunks)):
         _say(f"  oracle chunk {c}")
         q_rot = oracle.rope(bf16_bits_to_f64(q[c]), pos, cfg.rope_base)
         k_rot = oracle.rope(bf16_bits_to_f64(k[c]), pos, cfg.rope_base)
-        if c in chunks:
+        if c in chunks and informative:
+            vf = bf16_bits_to_f64(v[c])
+            ro, rl, P = oracle.local_attention(q_rot, k_rot, vf, rows=rows, return_probs=True)
+            med = assert_informative(ro, f"o[c={c}]")
+            tiles = pinned_tiles(P, ro, rl, vf)
+            pin = tiles if pin is None else (pin | tiles)
+            _say(f"    median |ref o| {med:.3f}; key tiles pinned by this chunk's sampled rows: "
+                 f"{int(tiles.sum())} of {tiles.size}")
+            del P
+        elif c in chunks:
             ro, rl = oracle.local_attention(q_rot, k_rot, bf16_bits_to_f64(v[c]), rows=rows)
+        if c in chunks:
             assert_close(dev_bf16_to_f64(layer.o[c, rows]), ro, O_ATOL, O_RTOL, f"o[c={c}]")
             assert_close(layer.lse[c][:, rows].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"lse[c={c}]")
             assert_close(dev_bf16_to_f64(layer.k_rope[c, rows]), k_rot[rows], 1e-5, 2.0 ** -8, f"k_rope[c={c}]")
@@ -46,6 +53,10 @@ def _check_prefill_samples(cfg, layer, q, k, v, chunks, score_chunks):
             assert_close(layer.tok_score[c].cpu().numpy(), tok, S_ATOL, S_RTOL, f"tok_score[c={c}]")
             assert_close(layer.chunk_score[c].cpu().numpy(), chunk, S_ATOL, S_RTOL, f"chunk_score[c={c}]")
             ref_tok[c] = (tok, chunk, q_rot if c == 0 else None, k_rot)
+    if informative:
+        # every 64-key tile of the sequence decides some sampled output: a kernel that dropped
+        # any one of them (or read it from elsewhere) would fail the checks above
+        assert pin is not None and pin.all(), f"key tiles no sampled row pins: {np.nonzero(~pin)[0]}"
     return ref_tok
 
 
@@ -61,8 +72,13 @@ def _finite_and_bounded(cfg, layer):
     return cs
 
 
-@pytest.mark.parametrize("cfg", [CFG1, CFG2], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [CFG1, CFG2, CFG1P, CFG2P], ids=lambda c: c.name)
 def test_full_layer_sampled(cfg):
+    """cfg1 / cfg2: the configs' own inputs (entries of std 1/sqrt(D): flat softmax, so the
+    outputs say little; scores, selections and the gather are what these pin).  cfg1p / cfg2p:
+    the same shapes on peaked inputs, where the outputs carry signal, every key tile is pinned by
+    a sampled row and selection gaps are real."""
+    informative = cfg.v_offset > 0.0
     _say(f"full layer {cfg.name}: generating inputs")
     q, k, v = prefill_inputs(cfg, threads=16)
     layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
@@ -75,7 +91,8 @@ def test_full_layer_sampled(cfg):
     _finite_and_bounded(cfg, layer)
     C = cfg.n_chunks
     # Eq. 5-6 on every chunk (the oracle only needs the voting rows), Eq. 1-2 on three chunks
-    ref = _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, C // 2, C - 1], score_chunks=range(C))
+    ref = _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, C // 2, C - 1], score_chunks=range(C),
+                                 informative=informative)
     ref_chunk_score = np.array([ref[c][1] for c in range(C)])
     # Eq. 3-4 mechanics
     g_cidx = layer.chunk_idx.cpu().numpy()
@@ -89,7 +106,10 @@ def test_full_layer_sampled(cfg):
         for g in range(cfg.n_kv_heads):
             assert list(g_tidx[s_, g]) == sorted(set(g_tidx[s_, g]))
             n_diff += assert_selection_matches(g_tidx[s_, g], ref_t[g], tok[g], f"tokens chunk {g_cidx[s_]} head {g}")
-    _say(f"  selection differences inside the tie zone: {n_diff}")
+    n_kept = cfg.keep_chunks * (1 + cfg.n_kv_heads * cfg.keep_tokens)
+    _say(f"  selection differences inside the tie zone: {n_diff} of {n_kept} kept indices")
+    if informative:       # real score gaps: the tie-zone clause may excuse at most 0.1 % of the kept set
+        assert n_diff <= 1e-3 * n_kept, (n_diff, n_kept)
     # Eq. 7 gather: bit-exact on the GPU's own rotated keys at the GPU's indices
     kr = dev_to_bits(layer.k_rope)
     rk, rv = oracle.gather_kv(kr, v, g_cidx, g_tidx)
@@ -104,6 +124,7 @@ def test_full_layer_sampled(cfg):
     vc_ref = np.stack([np.stack([vf[int(c)][g_tidx[s_, g], g] for g in range(cfg.n_kv_heads)])
                        for s_, c in enumerate(g_cidx)])
     v0 = bf16_bits_to_f64(v[0])
+    ref_global = []
     for t in (0, 1, 63, 64, wq // 2, wq - 1):
         # the self keys 0..t enter as one more segment of t + 1 valid rows
         kt = cfg.keep_tokens
@@ -115,11 +136,15 @@ def test_full_layer_sampled(cfg):
                                                 np.concatenate([vc_ref, vs]), seg_len=seg_len)
         assert_close(dev_bf16_to_f64(layer.global_o[0, t]), ro[0], O_ATOL, O_RTOL, f"global_o[t={t}]")
         assert_close(layer.global_lse[0, :, t].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"global_lse[t={t}]")
+        ref_global.append(ro[0])
+    if informative:
+        assert_informative(np.stack(ref_global), "global_o")
 
 
-def test_full_prefill_stress_config():
-    """64 chunks x 8704 rows in one launch: prefill + scores only (the stress config's step)."""
-    cfg = CFG3
+@pytest.mark.parametrize("cfg", [CFG3, CFG3P], ids=lambda c: c.name)
+def test_full_prefill_stress_config(cfg):
+    """64 chunks x 8704 rows in one launch: prefill + scores only (the stress config's step), on
+    the config's own flat inputs and on the peaked variant whose outputs carry signal."""
     _say(f"prefill {cfg.name}: generating inputs")
     q, k, v = prefill_inputs(cfg, threads=16)
     layer = ParallelCompLayer(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
@@ -128,10 +153,15 @@ def test_full_prefill_stress_config():
     torch.cuda.synchronize()
     _say("  GPU pass done")
     _finite_and_bounded(cfg, layer)
-    _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, 63], score_chunks=[0, 31, 63])
+    _check_prefill_samples(cfg, layer, q, k, v, chunks=[0, 63], score_chunks=[0, 31, 63],
+                           informative=cfg.v_offset > 0.0)
 
 
 def test_full_decode_and_gather_sampled():
+    """The decode config at full size: gather (bit-exact on sampled segments), then one decode step
+    over the gathered cache.  Inputs are peaked so that the outputs carry signal: unit-variance
+    keys, queries of std 3 (logit std 3: a handful of the 65536 keys of a group carry the row), and
+    a constant per (sequence, segment, KV head) on V, so a segment read from elsewhere shows."""
     cfg = CFG4
     _say(f"decode {cfg.name}")
     g = torch.Generator(device="cuda").manual_seed(4)
@@ -140,9 +170,11 @@ def test_full_decode_and_gather_sampled():
     # gather source [B, S, rows, H_kv, D] and sorted random index subsets
     R = cfg.src_rows
     ks = torch.empty((B, S, R, Hkv, D), dtype=bf, device="cuda")
+    vs = torch.empty_like(ks)
+    v_off = (torch.rand((B, S, 1, Hkv, 1), generator=g, device="cuda") * 4.0 - 2.0)
     for b in range(B):
-        ks[b] = (torch.randn(ks.shape[1:], generator=g, device="cuda") * cfg.entry_scale).to(bf)
-    vs = ks.flip(0).contiguous()
+        ks[b] = torch.randn(ks.shape[1:], generator=g, device="cuda").to(bf)
+        vs[b] = (torch.randn(ks.shape[1:], generator=g, device="cuda") + v_off[b]).to(bf)
     idx = torch.rand((B, S, Hkv, R), generator=g, device="cuda").argsort(dim=-1)[..., :kt]
     idx = idx.sort(dim=-1).values.to(torch.int32).contiguous()
     kc = torch.empty((B, S, Hkv, kt, D), dtype=bf, device="cuda")
@@ -156,7 +188,7 @@ def test_full_decode_and_gather_sampled():
     del ks, vs
     torch.cuda.empty_cache()
     # decode over the gathered cache: sampled (sequence, KV group) pairs against one softmax
-    q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda")).to(bf)     # logits with std ~ 1
+    q = (torch.randn((B, 1, Hq, D), generator=g, device="cuda") * 3.0).to(bf)
     out = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
     lse = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
     ws = pc.alloc_workspace(pc.pc_parallel_attn_workspace_bytes(B, 1, S, kt, Hq, Hkv, D, 0))
@@ -164,13 +196,27 @@ def test_full_decode_and_gather_sampled():
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
     G = Hq // Hkv
-    for (b, gk) in ((0, 0), (5, 3), (15, 7)):
+    refs, run_pinned = [], np.zeros(8, dtype=bool)
+    pairs = [(b, (3 * b + j) % Hkv) for b in range(B) for j in (0, 4)]       # 32 of the 128 groups
+    for i, (b, gk) in enumerate(pairs):
         kf = dev_bf16_to_f64(kc[b, :, gk])[:, None]          # [S, 1, kt, D]
         vf = dev_bf16_to_f64(vc[b, :, gk])[:, None]
         qf = dev_bf16_to_f64(q[b, :, gk * G:(gk + 1) * G])    # [1, G, D]
         ro, rl = oracle.global_attention_concat(qf, kf, vf)
         assert_close(dev_bf16_to_f64(out[b, :, gk * G:(gk + 1) * G]), ro, O_ATOL, O_RTOL, f"decode out[b={b},g={gk}]")
         assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"decode lse[b={b},g={gk}]")
+        refs.append(ro)
+        if i % 8 == 0:
+            # the launch cuts a group's 32 segments into 8 wavefront runs of 4 segments: would the
+            # check notice a run that is not read?  (the oracle without those segments' keys)
+            for run in range(8):
+                sl = np.full(S, kt); sl[4 * run:4 * run + 4] = 0
+                wo, wl = oracle.global_attention_concat(qf, kf, vf, seg_len=sl)
+                run_pinned[run] |= bool((np.abs(wo - ro) > O_ATOL + O_RTOL * np.abs(ro)).any() or
+                                        (np.abs(wl - rl) > LSE_ATOL + 1e-3 * np.abs(rl)).any())
+    med = assert_informative(np.stack(refs), "decode out")
+    _say(f"  median |ref out| {med:.3f}; runs of 4 segments pinned: {int(run_pinned.sum())} of 8")
+    assert run_pinned.all(), run_pinned
 
 
 def test_full_decode_steps_sampled():
@@ -192,9 +238,11 @@ def test_full_decode_steps_sampled():
         vc[b] = torch.randn(kc.shape[1:], generator=g, device="cuda").to(bf)
     k0 = torch.randn((B, n0, Hkv, D), generator=g, device="cuda").to(bf)
     v0 = torch.randn((B, n0, Hkv, D), generator=g, device="cuda").to(bf)
-    qn = torch.randn((T, B, 1, Hq, D), generator=g, device="cuda").to(bf)
+    # peaked: queries of std 3 (logit std 3), a constant per (sequence, segment, KV head) on V
+    qn = (torch.randn((T, B, 1, Hq, D), generator=g, device="cuda") * 3.0).to(bf)
     kn = torch.randn((T, B, 1, Hkv, D), generator=g, device="cuda").to(bf)
     vn = torch.randn((T, B, 1, Hkv, D), generator=g, device="cuda").to(bf)
+    vc = (vc.float() + (torch.rand((B, S, Hkv, 1, 1), generator=g, device="cuda") * 4.0 - 2.0)).to(bf)
     cache.load(kc, vc, None, k0, v0)
     outs, lses = [], []
     for t in range(T):
@@ -215,6 +263,7 @@ def test_full_decode_steps_sampled():
         gl = np.stack([l[b, hs, 0].cpu().numpy() for l in lses])
         assert_close(go, ro, O_ATOL, O_RTOL, f"decode steps out[b={b},g={gk}]")
         assert_close(gl, rl, LSE_ATOL, 1e-3, f"decode steps lse[b={b},g={gk}]")
+        assert_informative(ro, f"decode steps out[b={b},g={gk}]")
 
 
 def test_self_information_full_size_sampled():

@@ -31,6 +31,9 @@ class PrefillConfig:
     key_lognormal_sigma: float = 0.0  # >0: key norms are log-normal with this sigma
     recency_rows: int = 0            # last context rows of each chunk with boosted key norm
     recency_gain: float = 1.0
+    q_gain: float = 1.0              # extra multiplier on the query-side entries (q): logit std
+    v_offset: float = 0.0            # >0: a constant drawn per (chunk, KV head) from [-v_offset, v_offset] is added to V
+    key_norm: float = 1.0            # median key norm when key_lognormal_sigma > 0
     cfg_id: int = 0                  # enters the seed
 
     @property
@@ -81,6 +84,22 @@ CFG0U = replace(CFG0, name="cfg0u_tiny_mha_unit", entry_scale=1.0, plant_gain=0.
 CFG1U = replace(CFG1, name="cfg1u_llama3_8b_128k_unit", entry_scale=1.0,
                 plant_gain=0.5 * 128.0 ** 0.5, cfg_id=11)
 
+# "p" variants: inputs on which the attention outputs carry signal at the full sizes.  With the
+# 1/sqrt(D) entries above, logits have std ~ 1/D: the softmax is flat and an output row is the
+# mean of thousands of zero-mean values, far below any tolerance.  Here entries have unit
+# variance, q carries a gain (logit std ~ 2: a row's weight sits on a few dozen keys, which fall
+# in different key tiles for different rows), and V carries a constant per (chunk, KV head), so
+# that a tile taken from another chunk or head shows in the output.  The gains are the largest
+# for which bf16 operands (rotated q and k rounded to bf16, probabilities rounded to bf16) stay
+# within about 0.6 of the outputs' tolerance when emulated on the CPU; at logit std 3 that
+# rounding alone reaches the tolerance on the heaviest rows (the sink key, the log-normal norms).
+CFG1P = replace(CFG1U, name="cfg1p_llama3_8b_128k_peaked", q_gain=2.0, v_offset=2.0, sink_gain=1.5,
+                cfg_id=41)
+CFG2P = replace(CFG2, name="cfg2p_llama2_7b_128k_peaked", entry_scale=1.0, q_gain=0.45,
+                key_norm=128.0 ** 0.5, recency_gain=1.25, v_offset=2.0, cfg_id=42)
+CFG3P = replace(CFG3, name="cfg3p_llama3_8b_512k_stress_peaked", entry_scale=1.0, q_gain=2.0,
+                v_offset=2.0, cfg_id=43)
+
 # Reduced shapes with the same structure as cfg 1 / cfg 2 / cfg 4: several tiles plus a ragged
 # tail, small enough for the oracle to finish in seconds.
 CFG1_SMALL = replace(CFG1, name="cfg1_small", n_chunks=5, chunk_len=600, query_len=104,
@@ -90,5 +109,6 @@ CFG2_SMALL = replace(CFG2, name="cfg2_small", n_chunks=6, chunk_len=459, query_l
 CFG4_SMALL = replace(CFG4, name="cfg4_small", batch=3, n_seg=5, keep_tokens=333, src_rows=700,
                      cfg_id=24)
 
-PREFILL_CONFIGS = {c.name: c for c in (CFG0, CFG1, CFG2, CFG3, CFG0U, CFG1U, CFG1_SMALL, CFG2_SMALL)}
+PREFILL_CONFIGS = {c.name: c for c in (CFG0, CFG1, CFG2, CFG3, CFG0U, CFG1U, CFG1P, CFG2P, CFG3P,
+                                       CFG1_SMALL, CFG2_SMALL)}
 DECODE_CONFIGS = {c.name: c for c in (CFG4, CFG4_SMALL)}

@@ -20,6 +20,7 @@ _STREAM_QUERY = 1_000_000
 _STREAM_RELEVANT = 1_000_001
 _STREAM_DECODE_Q = 1_000_002
 _STREAM_GATHER_IDX = 1_000_003
+_STREAM_V_OFFSET = 1_000_004
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -65,17 +66,28 @@ def _key_norm_structure(cfg: PrefillConfig, rng, k_rows: np.ndarray, first_row: 
     if cfg.key_lognormal_sigma > 0.0:
         nrm = np.linalg.norm(k_rows, axis=-1, keepdims=True)
         z = rng.standard_normal(nrm.shape, dtype=np.float32)
-        k_rows *= np.exp(np.float32(cfg.key_lognormal_sigma) * z) / np.maximum(nrm, 1e-20)
+        k_rows *= np.float32(cfg.key_norm) * np.exp(np.float32(cfg.key_lognormal_sigma) * z) / np.maximum(nrm, 1e-20)
     return k_rows
+
+
+def v_offsets(cfg: PrefillConfig) -> np.ndarray:
+    """[C + 1, H_kv] constants added to V: row c for chunk c's context rows, row C for the query
+    rows.  Zeros when the config has no offset."""
+    if cfg.v_offset <= 0.0:
+        return np.zeros((cfg.n_chunks + 1, cfg.n_kv_heads), dtype=np.float32)
+    rng = _rng(cfg.cfg_id, _STREAM_V_OFFSET)
+    return (rng.uniform(-1.0, 1.0, size=(cfg.n_chunks + 1, cfg.n_kv_heads)) * cfg.v_offset).astype(np.float32)
 
 
 def query_rows_f32(cfg: PrefillConfig):
     """The w_q query rows (q, k, v), identical in every chunk, before rounding."""
     rng = _rng(cfg.cfg_id, _STREAM_QUERY)
-    q = _normal(rng, (cfg.query_len, cfg.n_q_heads, cfg.head_dim), cfg.entry_scale)
+    q = _normal(rng, (cfg.query_len, cfg.n_q_heads, cfg.head_dim), cfg.entry_scale * cfg.q_gain)
     k = _normal(rng, (cfg.query_len, cfg.n_kv_heads, cfg.head_dim), cfg.entry_scale)
     v = _normal(rng, (cfg.query_len, cfg.n_kv_heads, cfg.head_dim), cfg.entry_scale)
     k = _key_norm_structure(cfg, rng, k, cfg.chunk_len)
+    if cfg.v_offset > 0.0:
+        v += v_offsets(cfg)[cfg.n_chunks][None, :, None]
     return q, k, v
 
 
@@ -94,10 +106,12 @@ def prefill_chunk(cfg: PrefillConfig, c: int, _cache=None):
     qq, kq, vq, u, rel = _cache
     rng = _rng(cfg.cfg_id, c)
     w = cfg.chunk_len
-    q = _normal(rng, (w, cfg.n_q_heads, cfg.head_dim), cfg.entry_scale)
+    q = _normal(rng, (w, cfg.n_q_heads, cfg.head_dim), cfg.entry_scale * cfg.q_gain)
     k = _normal(rng, (w, cfg.n_kv_heads, cfg.head_dim), cfg.entry_scale)
     v = _normal(rng, (w, cfg.n_kv_heads, cfg.head_dim), cfg.entry_scale)
     k = _key_norm_structure(cfg, rng, k, 0)
+    if cfg.v_offset > 0.0:
+        v += v_offsets(cfg)[c][None, :, None]
     if cfg.recency_rows > 0:
         k[w - cfg.recency_rows:] *= np.float32(cfg.recency_gain)
     if c in rel:
