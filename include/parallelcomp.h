@@ -53,7 +53,8 @@ typedef struct pc_shape {
   int32_t n_q_heads;     /* H_q, multiple of n_kv_heads                                      */
   int32_t n_kv_heads;    /* H_kv                                                             */
   int32_t head_dim;      /* D in {64, 128}                                                   */
-  int32_t obs_window;    /* w_obs: the last w_obs rows of each sequence vote; 1..min(L, 64)  */
+  int32_t obs_window;    /* w_obs: the last w_obs rows of each sequence vote; 1..L (1..w_q
+                            when chunk_lens is given); w_obs = w_q is Eq. 6 as printed         */
   float   rope_base;     /* e.g. 1e4, 5e5                                                    */
   float   softmax_scale; /* 0 => 1/sqrt(D)                                                   */
 } pc_shape;
@@ -64,7 +65,7 @@ typedef struct pc_shape {
  *   q  [C, L, H_q, D]  bf16, before RoPE            k, v [C, L, H_kv, D] bf16, k before RoPE
  *   o  [C, L, H_q, D]  bf16 out                     lse  [C, H_q, L]     fp32 out (natural log)
  *   k_rope [C, L, H_kv, D] bf16 out, nullable: the rotated keys (the KV cache the later
- *          steps gather from); when NULL the rotated keys live only in the workspace.
+ *          steps gather from); when NULL they are not written.
  *   tok_score [C, H_kv, w] fp32 out, nullable; chunk_score [C] fp32 out, nullable (needs
  *          tok_score): exactly what pc_chunk_query_scores writes, from the same launch queue.
  *   chunk_lens [C] int32 (device), nullable: ragged chunks ("at most w tokens" per chunk,

@@ -70,7 +70,7 @@ extern "C" const char* pc_kernel_name(int id) {
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
       "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel", "kv_quantize_fp8_kernel",
-      "decode_attn_fp8_kernel"};
+      "decode_attn_fp8_kernel", "scores_kernel<1>+kv_prepass"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -88,10 +88,12 @@ static int check_shape(const pc_shape* s) {
   return PC_OK;
 }
 
-static int check_obs(const pc_shape* s) {
+// The voting rows are the last w_obs rows of a sequence.  With ragged chunks a sequence may be
+// as short as the query block alone, so the window must then fit the query block (Eq. 6 sums
+// over query rows only); with full chunks it may reach into the context rows.
+static int check_obs(const pc_shape* s, bool ragged) {
   const int L = s->chunk_len + s->query_len;
-  if (s->obs_window < 1 || s->obs_window > 64 || s->obs_window > L) return PC_ERR_SHAPE;
-  if ((s->n_q_heads / s->n_kv_heads) * s->obs_window > 512) return PC_ERR_UNSUPPORTED;
+  if (s->obs_window < 1 || s->obs_window > (ragged ? s->query_len : L)) return PC_ERR_SHAPE;
   return PC_OK;
 }
 
@@ -100,7 +102,7 @@ static float eff_scale(float scale, int head_dim) {
 }
 
 struct PrefillWs {
-  size_t table, v_img, k_img, k_rope, ml, total;
+  size_t table, v_img, k_img, ml, total;
   int Lp;
 };
 
@@ -113,7 +115,6 @@ static PrefillWs prefill_ws_layout(const pc_shape* s) {
   const size_t img_bytes = (size_t)s->n_chunks * s->n_kv_heads * s->head_dim * w.Lp * 2;   // tile images
   w.v_img = off; off = pc_align_up(off + img_bytes, kAlign);
   w.k_img = off; off = pc_align_up(off + img_bytes, kAlign);
-  w.k_rope = off; off = pc_align_up(off + (size_t)s->n_chunks * L * s->n_kv_heads * s->head_dim * 2, kAlign);
   w.ml = off;    off = pc_align_up(off + pc_scores_ml_bytes(s), kAlign);
   w.total = off;
   return w;
@@ -122,13 +123,13 @@ static PrefillWs prefill_ws_layout(const pc_shape* s) {
 extern "C" size_t pc_chunk_prefill_workspace_bytes(const pc_shape* s) {
   if (check_shape(s) != PC_OK) return 0;
   pc_shape t = *s;
-  if (t.obs_window < 1) t.obs_window = 1;
-  if (t.obs_window > 64) t.obs_window = 64;
+  if (t.obs_window < 1) t.obs_window = 1;                  // a call without scores ignores the window
+  if (t.obs_window > t.chunk_len + t.query_len) return 0;
   return prefill_ws_layout(&t).total;
 }
 
 extern "C" size_t pc_chunk_query_scores_workspace_bytes(const pc_shape* s) {
-  if (check_shape(s) != PC_OK || check_obs(s) != PC_OK) return 0;
+  if (check_shape(s) != PC_OK || check_obs(s, false) != PC_OK) return 0;
   const size_t L = (size_t)s->chunk_len + s->query_len;
   return pc_align_up(L * (s->head_dim / 2) * sizeof(float2), kAlign) +
          pc_align_up(pc_scores_ml_bytes(s), kAlign);
@@ -142,7 +143,7 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   if (!q || !k || !v || !o || !lse) return PC_ERR_NULL;
   if (chunk_score && !tok_score) return PC_ERR_NULL;
   if (tok_score) {
-    rc = check_obs(s);
+    rc = check_obs(s, chunk_lens != nullptr);
     if (rc != PC_OK) return rc;
   }
   pc_shape t = *s;
@@ -154,12 +155,19 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   float2* table = (float2*)(base + w.table);
   void* v_img = base + w.v_img;
   void* k_img = base + w.k_img;
-  void* kr = k_rope ? k_rope : (void*)(base + w.k_rope);
+  void* kr = k_rope;                                       // nullable: then only the images are written
   const int L = s->chunk_len + s->query_len, D = s->head_dim;
 
   rc = pc_launch_rope_table(table, L, D, s->rope_base, st);
   if (rc != PC_OK) return rc;
-  rc = pc_launch_kv_prepass(k, v, table, kr, k_img, v_img, s->n_chunks, L, w.Lp, s->n_kv_heads, D, st);
+  if (tok_score) {
+    // the first score pass reads and rotates every key anyway: it also writes the rotated keys
+    // and the tile images (the keys are read from memory once for both jobs)
+    const PcPrepassOut pre = {v, kr, k_img, v_img, w.Lp};
+    rc = pc_launch_scores(s, q, k, chunk_lens, table, base + w.ml, tok_score, chunk_score, &pre, st);
+  } else {
+    rc = pc_launch_kv_prepass(k, v, table, kr, k_img, v_img, s->n_chunks, L, w.Lp, s->n_kv_heads, D, st);
+  }
   if (rc != PC_OK) return rc;
 
   PcFlashArgs a = {};
@@ -173,14 +181,7 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   a.causal_offset = 0; a.q_pos0 = 0;
   a.seq_ctx = chunk_lens; a.seq_add = s->query_len;
   a.scale = eff_scale(s->softmax_scale, D);
-  rc = pc_launch_flash(a, st);
-  if (rc != PC_OK) return rc;
-
-  if (tok_score) {
-    rc = pc_launch_scores(s, q, k, chunk_lens, table, base + w.ml, tok_score, chunk_score, st);
-    if (rc != PC_OK) return rc;
-  }
-  return PC_OK;
+  return pc_launch_flash(a, st);
 }
 
 extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const void* k,
@@ -188,7 +189,7 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
                                      size_t ws_bytes, void* stream) {
   int rc = check_shape(s);
   if (rc != PC_OK) return rc;
-  rc = check_obs(s);
+  rc = check_obs(s, chunk_lens != nullptr);
   if (rc != PC_OK) return rc;
   if (!q || !k || !tok_score) return PC_ERR_NULL;
   const size_t need = pc_chunk_query_scores_workspace_bytes(s);
@@ -199,7 +200,7 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
   void* ml = (char*)ws + pc_align_up((size_t)L * (s->head_dim / 2) * sizeof(float2), kAlign);
   rc = pc_launch_rope_table(table, L, s->head_dim, s->rope_base, st);
   if (rc != PC_OK) return rc;
-  return pc_launch_scores(s, q, k, chunk_lens, table, ml, tok_score, chunk_score, st);
+  return pc_launch_scores(s, q, k, chunk_lens, table, ml, tok_score, chunk_score, nullptr, st);
 }
 
 extern "C" int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_new,

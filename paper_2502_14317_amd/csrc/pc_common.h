@@ -144,8 +144,13 @@ int pc_launch_self_info(const void* logits, const int32_t* targets, int n_chunks
                         int vocab, int negate, float* token_nll, float* info, hipStream_t st);
 
 size_t pc_scores_ml_bytes(const pc_shape* s);
+// Pre-pass duties the first score pass can take over (it reads and rotates every key anyway):
+// the rotated keys (k_rope, nullable), the K tile images and the V^T tile images of
+// pc_launch_kv_prepass, Lp = L rounded up to 64.
+struct PcPrepassOut { const void* v; void* k_rope; void* k_img; void* v_img; int Lp; };
 int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
-                     void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st);
+                     void* ml_ws, float* tok_score, float* chunk_score, const PcPrepassOut* pre,
+                     hipStream_t st);
 
 int pc_launch_rope_q(const void* q, void* q_rot, long long n_rows, int n_q, int n_heads, int D,
                      int pos0, float base, float mul, hipStream_t st);

@@ -18,9 +18,22 @@
 //   pass 2  (S = Q K^T, a lane owns a key)           recompute the logits, p = exp2(s - lse)
 //           and sum p over the columns (voting rows x heads of the group) for each key
 //           -> tok_score
-// A third kernel sums tok_score per chunk in a fixed order (deterministic) -> chunk_score.
+// Pass 2 also leaves the sum of its tok_score block; a last kernel adds those per chunk in a
+// fixed order (deterministic) -> chunk_score.
+//
+// Fused K/V pre-pass.  Inside pc_chunk_prefill_attn pass 1 takes over the work of
+// kv_prepass_kernel (switched on by its output pointers): it already reads every key row once and rotates it in
+// fp32, and the bf16 "hi" half of the split IS the rotated key rounded to bf16, so in its first
+// round over the columns it also writes the rotated keys (row-major cache) and the K tile images,
+// and moves V through LDS into the V^T tile images.  The keys are then read from HBM once for
+// both jobs, and rotated once.
+//
+// Any number of voting rows: the (row, head) columns of a KV group are handled in rounds of 128
+// (4 blocks of 32), the key tiles being re-read (from the caches) in every round.
 #include "pc_common.h"
 #include <math.h>
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define PC_SC_THREADS 256
 #define PC_SC_WAVES 4
@@ -40,6 +53,13 @@ struct PcScoreArgs {
   int L, w, w_obs, n_q_heads, n_kv_heads, n_kb, n_cols;
   int kb_keys;             // keys per workgroup: 256, 512 or 1024 (at most 512 when WPC == 4)
   float scale_log2;        // softmax scale x log2(e), folded into the query operand
+  float* blk_sum;          // workspace [C, H_kv, n_kb]: sum of each pass-2 block's tok_score
+  // pre-pass duties of pass 1 (all nullptr: off): V rows in, rotated keys / K images / V^T images out
+  const uint16_t* v;       // [C, L, H_kv, D]
+  uint16_t* k_rope;        // [C, L, H_kv, D] or nullptr
+  uint16_t* k_img;         // tile images [C][H_kv][Lp / 64][64 * D]
+  uint16_t* v_img;
+  int Lp;                  // L rounded up to 64
 };
 
 // (x0, x1) -> packed bf16 pair of the values and packed bf16 pair of the rounding remainders
@@ -56,13 +76,15 @@ __device__ __forceinline__ void split_bf16x2(float x0, float x1, uint32_t& hi, u
 // MHA with 32 voting rows) the four 32-key quarters of a 128-key tile.
 template <int D, int PASS, int WPC>
 __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a) {
+  // The pre-pass duties ride on pass 1 and are switched at run time (a.v_img != nullptr), so the
+  // standalone score call and the fused one execute the same code and give the same bits.
+  constexpr bool PRE = PASS == 1;
   constexpr int KS = D / 16, HALF = D / 2, KSTRIDE = D + 8;
   constexpr int TILE = WPC == 4 ? 2 * PC_SC_TILE : PC_SC_TILE;   // keys staged in LDS at a time
   constexpr int NSUB = TILE / 32;                                // 32-key sub-blocks per tile
   constexpr int CB_PER_ROUND = PC_SC_WAVES / WPC;
   __shared__ __attribute__((aligned(16))) uint16_t k_hi[TILE * KSTRIDE];
   __shared__ __attribute__((aligned(16))) uint16_t k_lo[TILE * KSTRIDE];
-  __shared__ float lse2_lds[512];
   constexpr int KB_CAP = WPC == 4 ? PC_SC_KB_MAX / 2 : PC_SC_KB_MAX;   // LDS: two workgroups per CU
   __shared__ float tok_part[PC_SC_WAVES][PASS == 2 ? KB_CAP : 1];
   __shared__ float2 ml_part[PC_SC_WAVES][32];
@@ -77,10 +99,7 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
   const int first_obs = ctx_len + (a.L - a.w) - a.w_obs;
   const long long ml_base = (((long long)c * a.n_kv_heads + g) * a.n_kb) * a.n_cols;
 
-  if (PASS == 2) {
-    const float* lse2 = a.lse2 + ((long long)c * a.n_kv_heads + g) * a.n_cols;
-    for (int col = tid; col < a.n_cols; col += PC_SC_THREADS) lse2_lds[col] = lse2[col];
-  }
+  const float* lse2 = a.lse2 + ((long long)c * a.n_kv_heads + g) * a.n_cols;
 
   // pass 2: every wavefront accumulates its columns' share of the keys' sums in its own LDS row
   if (PASS == 2)
@@ -128,12 +147,11 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
     float lse_r[16];
     int qrow_r[16];
     if (PASS == 2) {
-      __syncthreads();       // lse2_lds ready (first round) / K tiles free (later rounds)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int cc = 32 * cb + 8 * (r / 4) + 4 * hf + (r % 4);
         const bool ok = active && cc < a.n_cols;
-        lse_r[r] = ok ? lse2_lds[cc] : INFINITY;            // exp2(-inf) = 0 for padding columns
+        lse_r[r] = ok ? lse2[cc] : INFINITY;                // exp2(-inf) = 0 for padding columns
         qrow_r[r] = ok ? first_obs + cc % a.w_obs : -1;
       }
     }
@@ -160,6 +178,14 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         cs_step[2 * e] = make_float2(sv4.x, sv4.y); cs_step[2 * e + 1] = make_float2(sv4.z, sv4.w);
       }
     }
+    // pre-pass duties run in the first round only (every round stages the same keys)
+    const bool pre = PRE && round == 0 && a.v_img != nullptr;
+    // V: a thread takes 8 consecutive keys x 4 values (eight 8-byte loads), transposes them in
+    // registers and stores four 16-byte granules of the V^T image, (8 keys, d) each
+    constexpr int V_ALL = (TILE / 8) * (D / 4);                        // such items per tile
+    constexpr int V_ITEMS = (V_ALL + PC_SC_THREADS - 1) / PC_SC_THREADS;
+    u32x2 pf_v[PRE ? V_ITEMS : 1][8];
+    const long long img_cg = ((long long)c * a.n_kv_heads + g) * (a.Lp / 64);   // first tile image of (c, g)
     auto fetch = [&](int key0) __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < ITEMS; ++u) {
@@ -168,8 +194,49 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         pf_x1[u] = pc_load_once((const uint4*)(krow + st_i0));
         pf_x2[u] = pc_load_once((const uint4*)(krow + HALF + st_i0));
       }
+      if (pre) {
+#pragma unroll
+        for (int u = 0; u < V_ITEMS; ++u) {
+          const int it = tid + u * PC_SC_THREADS;
+          const int row0 = key0 + 8 * (it / (D / 4)), d4 = (it % (D / 4)) * 4;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            pf_v[u][j] = u32x2{0u, 0u};                                // rows past the sequence: zeros in the image
+            if (it < V_ALL && row0 + j < a.L)
+              pf_v[u][j] = __builtin_nontemporal_load(
+                  (const u32x2*)(a.v + (((long long)c * a.L + row0 + j) * a.n_kv_heads + g) * D + d4));
+          }
+        }
+      }
     };
-    auto stage = [&]() __attribute__((always_inline)) {
+    auto stage = [&](int key0) __attribute__((always_inline)) {
+      if (pre) {
+        // V^T tile images: granule (c8, d) = V[keys 8 c8 .. 8 c8 + 7][d]; word e of a granule pairs
+        // the values of keys 2 e and 2 e + 1 (one byte permute per word)
+#pragma unroll
+        for (int u = 0; u < V_ITEMS; ++u) {
+          const int it = tid + u * PC_SC_THREADS;
+          const int row0 = key0 + 8 * (it / (D / 4)), d4 = (it % (D / 4)) * 4;
+          if (it < V_ALL && row0 < a.Lp) {
+            uint16_t* img = a.v_img + (img_cg + row0 / 64) * (64LL * D) + (((row0 % 64) / 8) * D + d4) * 8;
+            uint4 gr[4];
+            uint32_t* gw = (uint32_t*)gr;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const u32x2 r0 = pf_v[u][2 * e], r1 = pf_v[u][2 * e + 1];
+              gw[0 * 4 + e] = __builtin_amdgcn_perm(r1.x, r0.x, 0x05040100u);   // d4 + 0: low halves
+              gw[1 * 4 + e] = __builtin_amdgcn_perm(r1.x, r0.x, 0x07060302u);   // d4 + 1: high halves
+              gw[2 * 4 + e] = __builtin_amdgcn_perm(r1.y, r0.y, 0x05040100u);   // d4 + 2
+              gw[3 * 4 + e] = __builtin_amdgcn_perm(r1.y, r0.y, 0x07060302u);   // d4 + 3
+            }
+            // ordinary stores: an instruction writes 16 bytes of every 64 a lane owns, and the
+            // last-level cache merges the four pieces of a line (with the streaming hint they
+            // reached memory as partial lines: 2.4 times slower)
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) *(uint4*)(img + dd * 8) = gr[dd];
+          }
+        }
+      }
 #pragma unroll
       for (int u = 0; u < ITEMS; ++u) {
         const int r = st_r0 + u * RP, i0 = st_i0;
@@ -188,6 +255,23 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
         *(uint4*)(k_lo + r * KSTRIDE + i0) = make_uint4(l1[0], l1[1], l1[2], l1[3]);
         *(uint4*)(k_hi + r * KSTRIDE + HALF + i0) = make_uint4(h2[0], h2[1], h2[2], h2[3]);
         *(uint4*)(k_lo + r * KSTRIDE + HALF + i0) = make_uint4(l2[0], l2[1], l2[2], l2[3]);
+        if (pre) {
+          // the hi halves are the rotated key rounded to bf16: the cache row and its K image granules
+          const int row = key0 + r;
+          const bool in_seq = row < a.L;
+          const uint4 oa = in_seq ? make_uint4(h1[0], h1[1], h1[2], h1[3]) : make_uint4(0, 0, 0, 0);
+          const uint4 ob = in_seq ? make_uint4(h2[0], h2[1], h2[2], h2[3]) : make_uint4(0, 0, 0, 0);
+          if (in_seq && a.k_rope != nullptr) {
+            uint16_t* dst = a.k_rope + (((long long)c * a.L + row) * a.n_kv_heads + g) * D;
+            pc_store_once((uint4*)(dst + i0), oa);
+            pc_store_once((uint4*)(dst + HALF + i0), ob);
+          }
+          if (row < a.Lp) {
+            uint16_t* img = a.k_img + (img_cg + row / 64) * (64LL * D);
+            pc_store_once((uint4*)(img + ((i0 / 8) * 64 + row % 64) * 8), oa);
+            pc_store_once((uint4*)(img + (((HALF + i0) / 8) * 64 + row % 64) * 8), ob);
+          }
+        }
         // (cos, sin) of the thread's next row: angle + RP theta
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -206,7 +290,7 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
       const int key0 = kblock * a.kb_keys + t * TILE;
       if (key0 >= a.L) break;                               // uniform over the workgroup
       __syncthreads();                                      // previous tile fully consumed
-      stage();
+      stage(key0);
       __syncthreads();
       if (t + 1 < n_tiles && key0 + TILE < a.L) fetch(key0 + TILE);
       if (!active) continue;
@@ -308,14 +392,29 @@ __global__ __launch_bounds__(PC_SC_THREADS, 2) void scores_kernel(PcScoreArgs a)
 
   if (PASS == 2) {
     __syncthreads();
+    float blk = 0.f;                                         // this thread's share of the block's sum
     for (int i = tid; i < a.kb_keys; i += PC_SC_THREADS) {
       const int key = kblock * a.kb_keys + i;
       if (key < a.w) {
         float x = 0.f;
 #pragma unroll
         for (int wv = 0; wv < PC_SC_WAVES; ++wv) x += tok_part[wv][i];
-        a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = key < ctx_len ? x : 0.f;
+        x = key < ctx_len ? x : 0.f;
+        a.tok_score[((long long)c * a.n_kv_heads + g) * a.w + key] = x;
+        blk += x;
       }
+    }
+    // block sum in a fixed order: lanes (xor tree), then the wavefronts in order
+#pragma unroll
+    for (int off = PC_WAVE / 2; off > 0; off >>= 1) blk += __shfl_xor(blk, off);
+    __syncthreads();                                         // tok_part is read no more: reuse its first floats
+    if (lane == 0) tok_part[0][wave] = blk;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < PC_SC_WAVES; ++wv) tot += tok_part[0][wv];
+      a.blk_sum[((long long)c * a.n_kv_heads + g) * a.n_kb + kblock] = tot;
     }
   }
 }
@@ -349,18 +448,18 @@ __global__ __launch_bounds__(128) void scores_lse_kernel(const float2* __restric
   lse2[(long long)blockIdx.x * n_cols + col] = M + log2f(sum);
 }
 
-// chunk_score[c] = sum of tok_score[c, :, :], summed in a fixed order (thread-strided partial
-// sums, then a tree over the workgroup), so the result does not depend on timing.
-__global__ __launch_bounds__(1024) void chunk_score_kernel(const float* __restrict__ tok_score,
-                                                           float* __restrict__ chunk_score,
-                                                           long long per_chunk) {
-  __shared__ float red[1024];
-  const float* src = tok_score + (long long)blockIdx.x * per_chunk;
+// chunk_score[c] = sum of tok_score[c, :, :] = sum of the chunk's pass-2 block sums, added in a
+// fixed order (thread-strided partial sums, then a tree), so the result does not depend on timing.
+__global__ __launch_bounds__(256) void chunk_score_kernel(const float* __restrict__ blk_sum,
+                                                          float* __restrict__ chunk_score,
+                                                          int per_chunk) {
+  __shared__ float red[256];
+  const float* src = blk_sum + (long long)blockIdx.x * per_chunk;
   float x = 0.f;
-  for (long long i = threadIdx.x; i < per_chunk; i += 1024) x += src[i];
+  for (int i = threadIdx.x; i < per_chunk; i += 256) x += src[i];
   red[threadIdx.x] = x;
   __syncthreads();
-  for (int s = 512; s > 0; s >>= 1) {
+  for (int s = 128; s > 0; s >>= 1) {
     if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
@@ -382,17 +481,18 @@ static void launch_scores_pass(int head_dim, int wpc, dim3 grid, dim3 block, hip
 }
 
 size_t pc_scores_ml_bytes(const pc_shape* s) {
-  const int L = s->chunk_len + s->query_len;
-  const int n_kb = (L + PC_SC_KB - 1) / PC_SC_KB;
-  const int n_cols = (s->n_q_heads / s->n_kv_heads) * s->obs_window;
-  // per-block (max, sum) of pass 1, then the combined row logsumexp
-  return (size_t)s->n_chunks * s->n_kv_heads * n_kb * n_cols * sizeof(float2) +
-         (size_t)s->n_chunks * s->n_kv_heads * n_cols * sizeof(float);
+  const size_t L = (size_t)s->chunk_len + s->query_len;
+  const size_t n_kb = (L + PC_SC_KB - 1) / PC_SC_KB;
+  const size_t n_cols = (size_t)(s->n_q_heads / s->n_kv_heads) * s->obs_window;
+  const size_t cg = (size_t)s->n_chunks * s->n_kv_heads;
+  // per-block (max, sum) of pass 1, the combined row logsumexp, the block sums of pass 2
+  return cg * n_kb * n_cols * sizeof(float2) + cg * n_cols * sizeof(float) + cg * n_kb * sizeof(float);
 }
 
 int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int32_t* chunk_lens, const float2* table,
-                     void* ml_ws, float* tok_score, float* chunk_score, hipStream_t st) {
-  PcScoreArgs a;
+                     void* ml_ws, float* tok_score, float* chunk_score, const PcPrepassOut* pre,
+                     hipStream_t st) {
+  PcScoreArgs a = {};
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.table = table; a.chunk_lens = chunk_lens;
   a.ml = (float2*)ml_ws; a.tok_score = tok_score;
   a.L = s->chunk_len + s->query_len; a.w = s->chunk_len; a.w_obs = s->obs_window;
@@ -409,12 +509,21 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   a.n_kb = (a.L + a.kb_keys - 1) / a.kb_keys;
   const float scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
   a.scale_log2 = scale * PC_SC_LOG2E;
-  a.lse2 = (float*)(a.ml + (size_t)s->n_chunks * s->n_kv_heads * a.n_kb * a.n_cols);
+  const size_t cg = (size_t)s->n_chunks * s->n_kv_heads;
+  a.lse2 = (float*)(a.ml + cg * a.n_kb * a.n_cols);
+  a.blk_sum = a.lse2 + cg * a.n_cols;
+  if ((long long)a.n_kb > 65535 || (long long)s->n_kv_heads > 65535) return PC_ERR_SHAPE;   // grid limits
   dim3 grid(s->n_chunks, s->n_kv_heads, a.n_kb), block(PC_SC_THREADS);
-  {
+  if (pre) {
+    a.v = (const uint16_t*)pre->v; a.k_rope = (uint16_t*)pre->k_rope; a.k_img = (uint16_t*)pre->k_img;
+    a.v_img = (uint16_t*)pre->v_img; a.Lp = pre->Lp;
+    PcProfScope prof(PC_KERNEL_PREPASS_SCORES, st);
+    launch_scores_pass<1>(s->head_dim, wpc, grid, block, st, a);
+  } else {
     PcProfScope prof(PC_KERNEL_SCORES_P1, st);
     launch_scores_pass<1>(s->head_dim, wpc, grid, block, st, a);
   }
+  PC_LAUNCH_CHECK();
   {
     PcProfScope prof(PC_KERNEL_SCORES_LSE, st);
     hipLaunchKernelGGL(scores_lse_kernel, dim3(s->n_chunks * s->n_kv_heads, (a.n_cols + 127) / 128),
@@ -427,8 +536,8 @@ int pc_launch_scores(const pc_shape* s, const void* q, const void* k, const int3
   PC_LAUNCH_CHECK();
   if (chunk_score) {
     PcProfScope prof(PC_KERNEL_CHUNK_SCORE, st);
-    hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(1024), 0, st, tok_score,
-                       chunk_score, (long long)s->n_kv_heads * s->chunk_len);
+    hipLaunchKernelGGL(chunk_score_kernel, dim3(s->n_chunks), dim3(256), 0, st, a.blk_sum,
+                       chunk_score, s->n_kv_heads * a.n_kb);
     PC_LAUNCH_CHECK();
   }
   return PC_OK;

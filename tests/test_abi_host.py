@@ -76,6 +76,11 @@ def test_null_and_shape_errors_before_any_gpu_work():
         assert pc.pc_chunk_prefill_workspace_bytes(bad) == 0
     bad = pc.make_shape(2, 64, 16, 8, 2, 128, 100, 1e4)     # obs_window too large
     assert L.pc_chunk_query_scores(ctypes.byref(bad), one, one, None, one, None, one, 1 << 30, None) == -2
+    # ragged chunks: the voting window must fit the query block (a chunk may be empty)
+    ragged = pc.make_shape(2, 64, 16, 8, 2, 128, 17, 1e4)
+    assert L.pc_chunk_query_scores(ctypes.byref(ragged), one, one, one, one, None, one, 1 << 30, None) == -2
+    assert L.pc_chunk_prefill_attn(ctypes.byref(ragged), one, one, one, one, one, one, None, one, None, one, 1 << 30, None) == -2
+    assert pc.pc_chunk_query_scores_workspace_bytes(ragged) > 0       # fine with full chunks
     # chunk_score without tok_score
     assert L.pc_chunk_prefill_attn(ctypes.byref(good), one, one, one, None, one, one, None, None, one, one, 1 << 30, None) == -1
     # parallel attention

@@ -157,6 +157,33 @@ def test_full_prefill_stress_config(cfg):
                            informative=cfg.v_offset > 0.0)
 
 
+def test_full_scores_every_query_row_votes():
+    """Eq. 6 as printed: all w_q = 512 query rows vote (2048 (row, head) columns per KV head on the
+    128K config).  Score tensors of two chunks of the peaked input against the oracle."""
+    import dataclasses
+    cfg = dataclasses.replace(CFG1P, obs_window=CFG1P.query_len)
+    _say(f"scores {cfg.name} w_obs = {cfg.obs_window}: generating inputs")
+    q, k, v = prefill_inputs(cfg, threads=16)
+    shape = pc.make_shape(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads, cfg.n_kv_heads,
+                          cfg.head_dim, cfg.obs_window, cfg.rope_base)
+    ts = torch.empty((cfg.n_chunks, cfg.n_kv_heads, cfg.chunk_len), dtype=torch.float32, device="cuda")
+    cs = torch.empty((cfg.n_chunks,), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_chunk_query_scores_workspace_bytes(shape))
+    pc.pc_chunk_query_scores(shape, bits_to_dev(q), bits_to_dev(k), ts, cs, ws)
+    torch.cuda.synchronize()
+    _say("  GPU pass done")
+    pos = np.arange(cfg.seq_len)
+    for c in (3, cfg.n_chunks - 1):
+        _say(f"  oracle chunk {c}")
+        tok, chunk = oracle.query_scores(oracle.rope(bf16_bits_to_f64(q[c]), pos, cfg.rope_base),
+                                         oracle.rope(bf16_bits_to_f64(k[c]), pos, cfg.rope_base),
+                                         cfg.chunk_len, cfg.obs_window, cfg.n_kv_heads)
+        assert_close(ts[c].cpu().numpy(), tok, S_ATOL, S_RTOL, f"tok_score[c={c}]")
+        assert_close(cs[c].cpu().numpy(), chunk, S_ATOL, S_RTOL, f"chunk_score[c={c}]")
+    m = cs.cpu().numpy()
+    assert np.all(m > 0) and np.all(m < cfg.n_q_heads * cfg.obs_window)
+
+
 def test_full_decode_and_gather_sampled():
     """The decode config at full size: gather (bit-exact on sampled segments), then one decode step
     over the gathered cache.  Inputs are peaked so that the outputs carry signal: unit-variance

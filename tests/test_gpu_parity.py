@@ -422,13 +422,14 @@ def test_chunk_prefill_without_scores_and_without_k_rope_out():
 
 
 def test_scores_obs_window_variants():
-    """w_obs = 8 (the paper's appendix), w_obs = w_q, and a window reaching into the context."""
+    """w_obs = 8 (the paper's appendix), smaller and larger windows, w_obs = w_q = 104 (Eq. 6 as
+    printed: every query row votes) and a window reaching into the context (200 > w_q)."""
     cfg = CFG1_SMALL
     q, k, v = prefill_inputs(cfg)
     qf, kf = bf16_bits_to_f64(q), bf16_bits_to_f64(k)
     qd, kd = bits_to_dev(q), bits_to_dev(k)
     pos = np.arange(cfg.seq_len)
-    for w_obs in (8, 1, 16, 64):        # 1, 1, 2 and 8 blocks of 32 (row, head) columns
+    for w_obs in (8, 1, 16, 64, cfg.query_len, 200):   # 1, 1, 2, 8, 13 and 25 blocks of 32 (row, head) columns
         _say(f"scores w_obs={w_obs}")
         shape = pc.make_shape(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads,
                               cfg.n_kv_heads, cfg.head_dim, w_obs, cfg.rope_base)

@@ -1,5 +1,7 @@
 """GPU parity of ragged chunks (chunk_lens) and of the streaming chunk priority queue against the
 fp64 CPU oracle, and of the streaming result against the all-chunks-at-once result."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -34,8 +36,13 @@ def _ragged_inputs(cfg, lens):
 
 
 @pytest.mark.parametrize("cfg,lens", [(CFG1_SMALL, [600, 600, 431, 256, 77]),
-                                      (CFG2_SMALL, [459, 64, 459, 300, 1, 459])],
-                         ids=["cfg1_small", "cfg2_small"])
+                                      (CFG2_SMALL, [459, 64, 459, 300, 1, 459]),
+                                      # chunks of 0 and 1 tokens, every query row voting (w_obs = w_q,
+                                      # Eq. 6 as printed): the voting window is the whole sequence of
+                                      # an empty chunk
+                                      (dataclasses.replace(CFG1_SMALL, obs_window=CFG1_SMALL.query_len),
+                                       [600, 0, 1, 256, 77])],
+                         ids=["cfg1_small", "cfg2_small", "cfg1_small_empty_chunks_all_rows_vote"])
 def test_ragged_chunks_layer(cfg, lens):
     _say(f"ragged layer {cfg.name} lens={lens}")
     lens = np.array(lens, dtype=np.int32)
