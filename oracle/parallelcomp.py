@@ -13,6 +13,8 @@ and follows the paper's order of steps:
   local_attention       Eq. 1-2: A = Softmax(Q K^T / sqrt(d)), F = A V, inside one chunk
   query_scores          Eq. 5-6: cumulative query->key attention, summed over voting rows
   select_chunks         Eq. 3-4 mechanics: fixed number of best chunks (see readings below)
+  chunk_queue_stream    sec. 3.1 "Chunk eviction": the fixed-size priority queue, chunks arriving
+                        a batch at a time; an evicted chunk frees its KV slot for a later entrant
   chunk_self_information  Eq. 3: I_c = -log P(X^q | X^c) from given language-model logits
   select_tokens         Eq. 7: retained token set per head per chunk
   select_tokens_calibrated  Eq. 8 then Eq. 7: evict the tokens of one position class whose score
@@ -168,6 +170,40 @@ def _top_k_lower_index_wins(score, k):
 def select_chunks(chunk_score, k_c):
     """Kept chunk ids in rank order (best first); ties go to the lower id (Eq. 3-4 mechanics)."""
     return _top_k_lower_index_wins(chunk_score, k_c).astype(np.int32)
+
+
+def chunk_queue_stream(chunk_score, batch, capacity):
+    """The fixed-size priority queue of sec. 3.1 ("Chunk eviction"), fed a batch of chunks at a
+    time (the chunks are encoded in memory-sized batches; only the chunks in the queue keep their
+    compressed KV).  After each batch the queue holds the `capacity` best chunks seen so far under
+    the order (score descending, earlier chunk first; NaN below every number), and every chunk in
+    the queue owns one of `capacity` KV slots: a chunk keeps its slot while it stays in the queue,
+    a chunk that enters takes a free slot (entrants in rank order take the free slots in ascending
+    order), an evicted chunk frees its slot.
+
+    chunk_score [C]; returns a list with one entry per batch: (queue ids in rank order,
+    slot of each queue entry, list of (chunk id, slot) of the batch's entrants).
+    """
+    score = np.asarray(chunk_score, dtype=np.float64)
+    key = np.where(np.isnan(score), -np.inf, score)
+    nan_last = np.isnan(score)                                  # NaN ranks below -inf too
+    queue, slot_of, out = [], {}, []
+    for c0 in range(0, score.shape[0], batch):
+        cand = queue + list(range(c0, min(c0 + batch, score.shape[0])))
+        cand.sort(key=lambda c: (bool(nan_last[c]), -key[c], c))
+        new_queue = cand[:capacity]
+        for c in queue:
+            if c not in new_queue:
+                del slot_of[c]
+        free = [s for s in range(capacity) if s not in slot_of.values()]
+        entrants = []
+        for c in new_queue:                                     # rank order
+            if c not in slot_of:
+                slot_of[c] = free.pop(0)
+                entrants.append((c, slot_of[c]))
+        queue = new_queue
+        out.append((list(queue), [slot_of[c] for c in queue], entrants))
+    return out
 
 
 def select_tokens(tok_score, k_t):

@@ -736,3 +736,41 @@ def test_generators_are_seeded_and_structured():
     w2 = CFG2_SMALL.chunk_len
     assert np.median(n2[:, w2 - 64:w2]) > 1.7 * np.median(n2[:, :w2 - 64])   # recency bump
     np.testing.assert_allclose(np.std(np.log(n2[:, :w2 - 64])), 0.5, rtol=0.1)  # log-normal sigma
+
+
+def test_chunk_queue_stream_equals_offline_top_k_of_every_prefix():
+    """Sec. 3.1 "Chunk eviction": the streaming queue must hold, after every batch, exactly the
+    offline top-k of the chunks seen so far (select_chunks on the prefix, itself pinned by brute
+    force above), whatever the batch size; slots are a permutation-free bookkeeping: distinct,
+    stable while a chunk stays, and entrants reuse only freed slots."""
+    r = np.random.default_rng(77)
+    for trial in range(30):
+        C = int(r.integers(1, 40)); cap = int(r.integers(1, 12)); batch = int(r.integers(1, 9))
+        score = r.integers(0, 6, size=C).astype(np.float64)          # heavy ties
+        if trial % 3 == 0:
+            score[r.integers(0, C, size=2)] = np.nan
+        if trial % 5 == 0:
+            score[r.integers(0, C)] = -np.inf
+        steps = oracle.chunk_queue_stream(score, batch, cap)
+        prev_slot = {}
+        for i, (queue, slots, entrants) in enumerate(steps):
+            seen = min((i + 1) * batch, C)
+            # offline: a stable sort of the prefix by descending score, NaN last (plain Python)
+            order = sorted(range(seen), key=lambda c: (np.isnan(score[c]), -np.nan_to_num(score[c], nan=0.0), c))
+            assert queue == order[:cap]
+            if not np.isnan(score[:seen]).any():
+                assert queue == list(oracle.select_chunks(score[:seen], min(cap, seen)))
+            assert len(set(slots)) == len(slots) and all(0 <= s < cap for s in slots)
+            now = dict(zip(queue, slots))
+            for c, s_ in now.items():
+                if c in prev_slot:
+                    assert prev_slot[c] == s_                        # a resident chunk never moves
+            assert [c for c, _ in entrants] == [c for c in queue if c not in prev_slot]
+            freed = sorted(set(range(cap)) - set(prev_slot[c] for c in prev_slot if c in now))
+            assert [s_ for _, s_ in entrants] == freed[:len(entrants)]   # ascending free slots, in rank order
+            prev_slot = now
+    # a worked case: capacity 2, batches of 2, scores 5 1 | 7 5 | 0 9
+    steps = oracle.chunk_queue_stream([5, 1, 7, 5, 0, 9], 2, 2)
+    assert steps[0] == ([0, 1], [0, 1], [(0, 0), (1, 1)])
+    assert steps[1] == ([2, 0], [1, 0], [(2, 1)])                     # 1 leaves, 2 takes its slot; tie 5 = 5: chunk 0 stays
+    assert steps[2] == ([5, 2], [0, 1], [(5, 0)])
