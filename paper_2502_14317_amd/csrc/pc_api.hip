@@ -83,6 +83,9 @@ static int check_shape(const pc_shape* s) {
   if (s->head_dim != 64 && s->head_dim != 128) return PC_ERR_SHAPE;
   const long long L = (long long)s->chunk_len + s->query_len;
   if (L > (1 << 20) || s->n_chunks > (1 << 20) || s->n_q_heads > 1024) return PC_ERR_SHAPE;
+  // kernels index (chunk, head, row) tuples and workgroups with 32-bit integers
+  if ((long long)s->n_chunks * s->n_q_heads * ((L + 127) / 128) > 0x7fffffffLL / 8) return PC_ERR_SHAPE;
+  if ((long long)s->n_chunks * L * s->n_q_heads > 0x7fffffffLL) return PC_ERR_SHAPE;
   if (!(s->rope_base > 1.0f) || !isfinite(s->rope_base)) return PC_ERR_SHAPE;
   if (!(s->softmax_scale >= 0.0f) || !isfinite(s->softmax_scale)) return PC_ERR_SHAPE;
   return PC_OK;
@@ -142,6 +145,10 @@ extern "C" int pc_chunk_prefill_attn(const pc_shape* s, const void* q, const voi
   if (rc != PC_OK) return rc;
   if (!q || !k || !v || !o || !lse) return PC_ERR_NULL;
   if (chunk_score && !tok_score) return PC_ERR_NULL;
+  // every kernel moves these tensors with 16-byte loads and stores
+  if (!pc_aligned(q, 16) || !pc_aligned(k, 16) || !pc_aligned(v, 16) || !pc_aligned(o, 16) ||
+      !pc_aligned(k_rope, 16))
+    return PC_ERR_SHAPE;
   if (tok_score) {
     rc = check_obs(s, chunk_lens != nullptr);
     if (rc != PC_OK) return rc;
@@ -192,6 +199,7 @@ extern "C" int pc_chunk_query_scores(const pc_shape* s, const void* q, const voi
   rc = check_obs(s, chunk_lens != nullptr);
   if (rc != PC_OK) return rc;
   if (!q || !k || !tok_score) return PC_ERR_NULL;
+  if (!pc_aligned(q, 16) || !pc_aligned(k, 16)) return PC_ERR_SHAPE;
   const size_t need = pc_chunk_query_scores_workspace_bytes(s);
   if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < need) return PC_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -212,6 +220,9 @@ extern "C" int pc_kv_append(const void* k_new, const void* v_new, int32_t batch,
     return PC_ERR_SHAPE;
   if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
   if (pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
+  if (!pc_aligned(k_new, 2) || !pc_aligned(v_new, 2) || !pc_aligned(kc, 2) || !pc_aligned(vc, 2) ||
+      !pc_aligned(seg_len, 4))
+    return PC_ERR_SHAPE;
   if (batch == 0 || n_new == 0) return PC_OK;
   return pc_launch_kv_append(k_new, v_new, batch, n_new, n_seg, seg, k_t, n_kv_heads, head_dim,
                              pos0, rope_base, kc, vc, seg_len, seg_len_per_head != 0,
@@ -262,6 +273,8 @@ static int check_par8(int batch, int n_q, int n_seg, int k_t, int tail_cap, int 
   if (D != 64 && D != 128) return PC_ERR_SHAPE;
   if (k_t > (1 << 24) || tail_cap > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
   if (n_seg == 0 && tail_cap == 0) return PC_ERR_SHAPE;
+  if ((long long)batch * ((long long)n_seg + 1) * n_kv_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
+  if ((long long)batch * n_q * n_q_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
   if ((long long)n_q * (n_q_heads / n_kv_heads) > 16) return PC_ERR_UNSUPPORTED;
   return PC_OK;
 }
@@ -292,6 +305,8 @@ extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v
   if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
   if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
   if (n_seg > 0 && (!pc_aligned(k8, 16) || !pc_aligned(v8, 16))) return PC_ERR_SHAPE;
+  if (!pc_aligned(q, 16) || !pc_aligned(out, 16) || !pc_aligned(k_tail, 16) || !pc_aligned(v_tail, 16))
+    return PC_ERR_SHAPE;
   const int D = head_dim;
   const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, D);
   if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
@@ -422,6 +437,11 @@ static int check_par(int batch, int n_q, int n_seg, int k_t, int n_q_heads, int 
   if (n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % n_kv_heads != 0) return PC_ERR_SHAPE;
   if (D != 64 && D != 128) return PC_ERR_SHAPE;
   if (n_q > (1 << 20) || k_t > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
+  // kernels index (sequence, segment, head) tuples, partial rows and workgroups with 32-bit integers
+  const long long parts = (long long)n_seg + 1;
+  if ((long long)batch * parts * n_kv_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
+  if ((long long)batch * parts * n_q_heads * ((n_q + 127) / 128) > 0x7fffffffLL / 8) return PC_ERR_SHAPE;
+  if ((long long)batch * n_q * n_q_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
   return PC_OK;
 }
 
@@ -448,6 +468,10 @@ static int check_par_args(const void* q, const void* kc, const void* vc, int32_t
   if (n_seg == 0 && k_self == nullptr) return PC_ERR_SHAPE;
   if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
   if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
+  // 16-byte loads and stores on every tensor
+  if (!pc_aligned(q, 16) || !pc_aligned(kc, 16) || !pc_aligned(vc, 16) || !pc_aligned(k_self, 16) ||
+      !pc_aligned(v_self, 16) || !pc_aligned(out, 16))
+    return PC_ERR_SHAPE;
   return PC_OK;
 }
 

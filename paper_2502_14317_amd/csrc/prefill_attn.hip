@@ -153,6 +153,7 @@ __global__ __launch_bounds__(256) void kv_prepass_kernel(
 int pc_launch_kv_prepass(const void* k, const void* v, const float2* table, void* k_rope,
                          void* k_img, void* v_img, int n_seq, int L, int Lp, int n_kv_heads,
                          int head_dim, hipStream_t st) {
+  if (n_kv_heads > 65535 || Lp / 64 > 65535) return PC_ERR_SHAPE;       // grid limits
   dim3 grid(n_seq, n_kv_heads, Lp / 64), block(256);
   PcProfScope prof(PC_KERNEL_KV_PREPASS, st);
   if (head_dim == 128)

@@ -44,12 +44,15 @@ __global__ __launch_bounds__(PC_SI_THREADS) void self_info_rows_kernel(
       for (int e = 0; e < 8; e += 2) vm = fmaxf(fmaxf(vm, f[u][e]), f[u][e + 1]);
     }
     const float m_new = fmaxf(m, vm * PC_SI_LOG2E);       // log2(e) > 0: the maximum commutes with it
+    // a lane that has seen nothing but -inf logits so far (masked vocabulary entries) keeps
+    // m = -inf, l = 0: the reference 0 turns its terms into exp2(-inf) = 0 instead of NaN
+    const float ref = (m_new == -INFINITY) ? 0.f : m_new;
     float s = 0.f;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(fmaf(f[u][e], PC_SI_LOG2E, -m_new));
-    l = l * __builtin_amdgcn_exp2f(m - m_new) + s;      // m = -inf, l = 0 on the first round: 0 * 0
+      for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(fmaf(f[u][e], PC_SI_LOG2E, -ref));
+    l = ((m == -INFINITY) ? 0.f : l * __builtin_amdgcn_exp2f(m - m_new)) + s;
     m = m_new;
   }
   // fixed-order tree over the wavefront, then over the wavefronts

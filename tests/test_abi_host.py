@@ -91,6 +91,13 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_parallel_attn(one, one, one, one, 2, None, None, *args, one, None, one, 1 << 30, None) == -2
     bad_args = (1, 1, 2, 64, 8, 3, 128, -1, 1e4, 0.0)
     assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *bad_args, one, None, one, 1 << 30, None) == -2
+    # misaligned tensors and shapes beyond the kernels' 32-bit indexing are shape errors
+    odd = ctypes.c_void_p(264)
+    assert L.pc_parallel_attn(odd, one, one, None, 0, None, None, *args, one, None, one, 1 << 30, None) == -2
+    assert L.pc_parallel_attn(one, one, odd, None, 0, None, None, *args, one, None, one, 1 << 30, None) == -2
+    huge = (1 << 20, 1, 1 << 20, 64, 8, 2, 128, -1, 1e4, 0.0)
+    assert L.pc_parallel_attn(one, one, one, None, 0, None, None, *huge, one, None, one, 1 << 30, None) == -2
+    assert L.pc_chunk_prefill_attn(ctypes.byref(good), odd, one, one, None, one, one, None, None, None, one, 1 << 30, None) == -2
     # the variant that allocates nothing: same checks, plus its own limits (all on the host)
     assert L.pc_parallel_attn_static(None, one, one, None, 0, None, None, *args, one, None, None) == -1
     assert L.pc_parallel_attn_static(one, one, one, None, 0, None, None, *bad_args, one, None, None) == -2

@@ -61,3 +61,23 @@ def test_self_information_extreme_logits_and_target_clamp():
     nll_c, _ = _run(lb, oob)
     nll_w, _ = _run(lb, np.array([0, 63, 0], dtype=np.int32))
     assert np.array_equal(nll_c, nll_w)
+
+
+def test_self_information_masked_vocabulary_entries():
+    """-inf logits (masked or padded vocabulary entries) carry probability 0: whole runs of them,
+    long enough that some lanes of the reduction see nothing else, must not poison the row."""
+    from workloads import f32_to_bf16_bits
+    r = np.random.default_rng(62)
+    C, T, V = 2, 4, 40000
+    x = (r.standard_normal((C, T, V)) * 2).astype(np.float32)
+    x[0, 0, :36000] = -np.inf            # only the tail of the row is live
+    x[0, 1, 8:] = -np.inf                # only the first vector is live
+    x[1, 2, ::2] = -np.inf               # every other entry masked
+    x[1, 3, 100:39000] = -np.inf
+    lb = f32_to_bf16_bits(x)
+    targets = np.array([39999, 3, 1, 50], dtype=np.int32)       # live entries
+    ref_I, ref_nll = oracle.chunk_self_information(bf16_bits_to_f64(lb), targets)
+    assert np.all(np.isfinite(ref_nll))
+    nll, info = _run(lb, targets)
+    assert_close(nll, ref_nll, NLL_ATOL, NLL_RTOL, "token_nll")
+    assert_close(info, ref_I, 0.0, INFO_RTOL, "info")
