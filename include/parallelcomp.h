@@ -123,11 +123,33 @@ int pc_chunk_self_information(const void* logits, const int32_t* targets, int32_
 int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_t k,
                           int32_t* out_idx, float* out_score, void* stream);
 
+/* ---- sec. 3.1 "Chunk eviction": the fixed-size priority queue, a batch at a time -------------
+ * The chunks are encoded in memory-sized batches and a fixed-size priority queue keeps the best
+ * ones; only the chunks in the queue keep their compressed KV.  The queue lives on the device:
+ *   queue_id    [capacity] int32  chunk ids in rank order (score descending, earlier chunk first
+ *                                 on ties, NaN lowest); -1 = empty entry.  Fill with -1 to start.
+ *   queue_score [capacity] fp32   their scores
+ *   queue_slot  [capacity] int32  the KV slot (0 .. capacity-1) each entry owns
+ * One call merges a batch: batch_score [n_batch] fp32 are the scores of the chunks with ids
+ * chunk_id0 .. chunk_id0 + n_batch - 1 (ids grow from batch to batch).  After it the queue holds
+ * the top `capacity` of all chunks seen so far, i.e. what pc_select_chunks_topk returns on the
+ * whole prefix.  A chunk that stays keeps its slot; the entrants, in rank order, take the free
+ * slots (never used, or freed by a chunk that left) in ascending order.
+ *   slot_src [capacity] int32 out: slot_src[s] = index within this batch (0 .. n_batch-1) of the
+ *     chunk that enters slot s, or -1 if slot s keeps its content.  Passed as chunk_idx (n_sel =
+ *     capacity) to pc_select_tokens_topk / pc_select_tokens_calibrated and pc_gather_kv, it makes
+ *     them process exactly the entrants, each into its own slot, with no host round trip.
+ * 1 <= n_batch, capacity <= 1024.  One small workgroup; calls on one stream are ordered. */
+int pc_chunk_queue_update(const float* batch_score, int32_t n_batch, int32_t chunk_id0,
+                          int32_t capacity, int32_t* queue_id, float* queue_score,
+                          int32_t* queue_slot, int32_t* slot_src, void* stream);
+
 /* ---- Eq. 7 (index sets) --------------------------------------------------------------------
  * For every selected chunk s < n_sel and KV head g: the k tokens of
  * tok_score[chunk_idx[s], g, 0:chunk_len] that are largest under (score descending, index
  * ascending), written in ascending index order.
- *   tok_score [n_chunks_total, H_kv, chunk_len] fp32   chunk_idx [n_sel] int32, NULL => s
+ *   tok_score [n_chunks_total, H_kv, chunk_len] fp32   chunk_idx [n_sel] int32, NULL => s;
+ *             an entry chunk_idx[s] < 0 is skipped: out_idx[s] (and out_cnt[s]) stay as they are
  *   out_idx   [n_sel, H_kv, k] int32.        1 <= k <= chunk_len <= 32768.   No workspace. */
 int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,
                           int32_t n_kv_heads, int32_t chunk_len, int32_t k,
@@ -154,7 +176,8 @@ int pc_select_tokens_calibrated(const float* tok_score, const int32_t* chunk_idx
  * dst[b, s, g, t, :] = src[b, chunk_idx[b, s], tok_idx[b, s, g, t], g, :]  for K and V.
  *   k_src, v_src [batch, n_chunks, rows_per_chunk, H_kv, D] bf16 (a pure 16-bit copy)
  *   chunk_idx [batch, n_sel] int32, NULL => s      tok_idx [batch, n_sel, H_kv, k] int32
- *   k_dst, v_dst [batch, n_sel, H_kv, k, D].   Indices outside the source give zero rows. */
+ *   k_dst, v_dst [batch, n_sel, H_kv, k, D].   Token indices outside the source (and chunk
+ *   indices >= n_chunks) give zero rows; a segment with chunk_idx[b, s] < 0 is left untouched. */
 int pc_gather_kv(const void* k_src, const void* v_src, const int32_t* chunk_idx,
                  const int32_t* tok_idx, int32_t batch, int32_t n_chunks,
                  int32_t rows_per_chunk, int32_t n_sel, int32_t n_kv_heads, int32_t k,

@@ -24,6 +24,7 @@ SYMBOLS = [
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
     "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
     "pc_profile_begin_kernel", "pc_parallel_attn_static", "pc_parallel_attn_static_max_bytes",
+    "pc_chunk_queue_update",
 ]
 
 
@@ -66,6 +67,8 @@ def lib():
     L.pc_chunk_query_scores_workspace_bytes.restype = c_size_t
     L.pc_select_chunks_topk.argtypes = [P, c_int32, c_int32, P, P, P]
     L.pc_select_chunks_topk.restype = c_int
+    L.pc_chunk_queue_update.argtypes = [P, c_int32, c_int32, c_int32, P, P, P, P, P]
+    L.pc_chunk_queue_update.restype = c_int
     L.pc_select_tokens_topk.argtypes = [P, P, c_int32, c_int32, c_int32, c_int32, P, P]
     L.pc_select_tokens_topk.restype = c_int
     L.pc_gather_kv.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P]
@@ -175,6 +178,13 @@ def pc_chunk_self_information(logits, targets, n_chunks, n_tokens, vocab, negate
 def pc_select_chunks_topk(chunk_score, n, k, out_idx, out_score=None):
     _check(lib().pc_select_chunks_topk(_ptr(chunk_score), n, k, _ptr(out_idx), _ptr(out_score),
                                        _stream()), "pc_select_chunks_topk")
+
+
+def pc_chunk_queue_update(batch_score, n_batch, chunk_id0, capacity, queue_id, queue_score, queue_slot,
+                          slot_src):
+    _check(lib().pc_chunk_queue_update(_ptr(batch_score), n_batch, chunk_id0, capacity, _ptr(queue_id),
+                                       _ptr(queue_score), _ptr(queue_slot), _ptr(slot_src), _stream()),
+           "pc_chunk_queue_update")
 
 
 def pc_select_tokens_topk(tok_score, chunk_idx, n_sel, n_kv_heads, chunk_len, k, out_idx):

@@ -21,11 +21,13 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
   const long long base = ((long long)blockIdx.x * PC_GATHER_UNROLL) * ROWS_PER_BLOCK + row_in_block;
 
   uint4 kv[PC_GATHER_UNROLL], vv[PC_GATHER_UNROLL];
+  bool skip[PC_GATHER_UNROLL];                                  // destination segment without a source chunk
 #pragma unroll
   for (int u = 0; u < PC_GATHER_UNROLL; ++u) {
     const long long r = base + (long long)u * ROWS_PER_BLOCK;   // destination row id
     kv[u] = make_uint4(0, 0, 0, 0);
     vv[u] = make_uint4(0, 0, 0, 0);
+    skip[u] = false;
     if (r < n_dst_rows) {
       // r = ((b * n_sel + s) * H_kv + g) * k + t
       const long long bsg = r / k;
@@ -34,7 +36,8 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
       const int s = (int)(bs % n_sel);
       const long long b = bs / n_sel;
       const int c = chunk_idx ? chunk_idx[bs] : s;
-      const int t = tok_idx[r];
+      skip[u] = c < 0;
+      const int t = skip[u] ? -1 : tok_idx[r];
       if (c >= 0 && c < n_chunks && t >= 0 && t < rows) {
         const long long src_row = ((b * n_chunks + c) * rows + t) * n_kv_heads + g;
         kv[u] = pc_load_once(k_src + src_row * LANES_PER_ROW + piece);
@@ -45,7 +48,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(
 #pragma unroll
   for (int u = 0; u < PC_GATHER_UNROLL; ++u) {
     const long long r = base + (long long)u * ROWS_PER_BLOCK;
-    if (r < n_dst_rows) {
+    if (r < n_dst_rows && !skip[u]) {
       pc_store_once(k_dst + r * LANES_PER_ROW + piece, kv[u]);
       pc_store_once(v_dst + r * LANES_PER_ROW + piece, vv[u]);
     }

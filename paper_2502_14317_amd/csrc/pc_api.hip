@@ -70,7 +70,7 @@ extern "C" const char* pc_kernel_name(int id) {
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
       "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel", "kv_quantize_fp8_kernel",
-      "decode_attn_fp8_kernel", "scores_kernel<1>+kv_prepass"};
+      "decode_attn_fp8_kernel", "scores_kernel<1>+kv_prepass", "chunk_queue_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -352,6 +352,16 @@ extern "C" int pc_select_chunks_topk(const float* chunk_score, int32_t n, int32_
   if (!chunk_score || !out_idx) return PC_ERR_NULL;
   if (n < 1 || n > 4096 || k < 1 || k > n) return PC_ERR_SHAPE;
   return pc_launch_select_chunks(chunk_score, n, k, out_idx, out_score, (hipStream_t)stream);
+}
+
+extern "C" int pc_chunk_queue_update(const float* batch_score, int32_t n_batch, int32_t chunk_id0,
+                                     int32_t capacity, int32_t* queue_id, float* queue_score,
+                                     int32_t* queue_slot, int32_t* slot_src, void* stream) {
+  if (!batch_score || !queue_id || !queue_score || !queue_slot || !slot_src) return PC_ERR_NULL;
+  if (n_batch < 1 || n_batch > 1024 || capacity < 1 || capacity > 1024 || chunk_id0 < 0) return PC_ERR_SHAPE;
+  if ((long long)chunk_id0 + n_batch > 0x7fffffffLL) return PC_ERR_SHAPE;
+  return pc_launch_chunk_queue(batch_score, n_batch, chunk_id0, capacity, queue_id, queue_score,
+                               queue_slot, slot_src, (hipStream_t)stream);
 }
 
 extern "C" int pc_select_tokens_topk(const float* tok_score, const int32_t* chunk_idx, int32_t n_sel,

@@ -33,6 +33,19 @@ struct PcProfScope {
   ~PcProfScope();
 };
 
+// hipFuncAttributeMaxDynamicSharedMemorySize, set once per (kernel, device) instead of on every
+// launch: `done` holds one bit per device ordinal (ordinals beyond 63 set it every time).
+#include <atomic>
+static inline int pc_raise_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  PC_HIP_TRY(hipGetDevice(&dev));
+  const uint64_t bit = dev < 64 ? (1ull << dev) : 0ull;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return PC_OK;
+  PC_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return PC_OK;
+}
+
 static inline size_t pc_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline bool pc_aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -105,6 +118,10 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
                             int n_kv_heads, int chunk_len, int k, float lambda, int cls_lo,
                             int cls_hi, const int32_t* chunk_lens, int32_t* out_idx,
                             int32_t* out_cnt, hipStream_t st);
+
+int pc_launch_chunk_queue(const float* batch_score, int n_batch, int chunk_id0, int cap,
+                          int32_t* queue_id, float* queue_score, int32_t* queue_slot,
+                          int32_t* slot_src, hipStream_t st);
 
 int pc_launch_rope_table(float2* table, int n_pos, int head_dim, float base, hipStream_t st);
 

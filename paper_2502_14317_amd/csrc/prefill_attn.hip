@@ -680,8 +680,9 @@ template <int D, bool ROPE_Q, bool PARTIAL>
 static int launch_flash_t(const PcFlashArgs& a, hipStream_t st) {
   using SM = FlashSmem<D>;
   auto kern = flash_fwd_kernel<D, ROPE_Q, PARTIAL>;
-  PC_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 SM::BYTES));
+  static std::atomic<uint64_t> raised{0};          // one per instantiation of this launcher
+  const int lds_rc = pc_raise_dynamic_lds((const void*)kern, SM::BYTES, raised);
+  if (lds_rc != PC_OK) return lds_rc;
   const int G = a.n_q_heads / a.n_kv_heads;
   const int n_qt = (a.n_rows + PC_FA_BM - 1) / PC_FA_BM;
   const long long per_group = (long long)G * n_qt * a.n_parts_grid;

@@ -3,6 +3,7 @@
 // the lower index wins.  Scores are mapped to unsigned keys whose integer order is the float
 // order, so every comparison is exact integer work.
 #include "pc_common.h"
+#include <atomic>
 
 // ------------------------------------------------------------------------------------------
 // Chunks: n <= 4096.  One workgroup; rank by counting.  rank(i) = #{j : key_j > key_i or
@@ -37,6 +38,78 @@ int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, 
 }
 
 // ------------------------------------------------------------------------------------------
+// The fixed-size priority queue of chunks (sec. 3.1 "Chunk eviction"), updated with one batch
+// of newly encoded chunks.  The queue lives on the device: ids in rank order (-1 = empty
+// entry), their scores, and the KV slot each entry owns.  One workgroup ranks the resident
+// entries and the batch together by counting, under (score descending, earlier chunk first;
+// NaN lowest, empty entries last); the best `cap` stay.  A chunk that stays keeps its slot; the
+// entrants, in rank order, take the free slots in ascending order.  slot_src[s] names, for the
+// later selection / gather launches, the batch-local index of the chunk that enters slot s, or
+// -1 where the slot keeps its content.
+#define PC_QUEUE_MAX 1024              // capacity and batch size limit (each)
+__global__ __launch_bounds__(256) void chunk_queue_kernel(
+    const float* __restrict__ batch_score, int n_batch, int chunk_id0, int cap,
+    int32_t* __restrict__ queue_id, float* __restrict__ queue_score,
+    int32_t* __restrict__ queue_slot, int32_t* __restrict__ slot_src) {
+  __shared__ uint32_t key[2 * PC_QUEUE_MAX];
+  __shared__ int32_t id[2 * PC_QUEUE_MAX], slot[2 * PC_QUEUE_MAX];
+  __shared__ float val[2 * PC_QUEUE_MAX];
+  __shared__ int32_t new_id[PC_QUEUE_MAX], new_slot[PC_QUEUE_MAX];
+  __shared__ float new_val[PC_QUEUE_MAX];
+  __shared__ uint8_t used[PC_QUEUE_MAX];
+  const int n = cap + n_batch;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    if (i < cap) {
+      id[i] = queue_id[i]; val[i] = queue_score[i]; slot[i] = queue_slot[i];
+    } else {
+      id[i] = chunk_id0 + (i - cap); val[i] = batch_score[i - cap]; slot[i] = -1;
+    }
+    key[i] = pc_order_key(val[i]);
+  }
+  for (int i = threadIdx.x; i < cap; i += blockDim.x) { new_id[i] = -1; new_slot[i] = -1; new_val[i] = 0.f; used[i] = 0; slot_src[i] = -1; }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    if (id[i] < 0) continue;                                   // an empty entry ranks behind every chunk
+    const uint32_t ki = key[i];
+    const int ii = id[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+      const uint32_t kj = key[j];
+      rank += (id[j] >= 0) && ((kj > ki) || (kj == ki && id[j] < ii));
+    }
+    if (rank < cap) {
+      new_id[rank] = ii; new_val[rank] = val[i]; new_slot[rank] = slot[i];
+      if (slot[i] >= 0 && slot[i] < cap) used[slot[i]] = 1;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int f = 0;                                                  // next candidate free slot
+    for (int r = 0; r < cap; ++r) {
+      if (new_id[r] < 0 || new_slot[r] >= 0) continue;          // empty, or a resident chunk
+      while (f < cap && used[f]) ++f;
+      if (f >= cap) break;                                      // cannot happen: at most cap entries hold slots
+      new_slot[r] = f; used[f] = 1;
+      slot_src[f] = new_id[r] - chunk_id0;
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < cap; i += blockDim.x) {
+    queue_id[i] = new_id[i]; queue_score[i] = new_val[i]; queue_slot[i] = new_slot[i];
+  }
+}
+
+int pc_launch_chunk_queue(const float* batch_score, int n_batch, int chunk_id0, int cap,
+                          int32_t* queue_id, float* queue_score, int32_t* queue_slot,
+                          int32_t* slot_src, hipStream_t st) {
+  PcProfScope prof(PC_KERNEL_CHUNK_QUEUE, st);
+  hipLaunchKernelGGL(chunk_queue_kernel, dim3(1), dim3(256), 0, st, batch_score, n_batch, chunk_id0,
+                     cap, queue_id, queue_score, queue_slot, slot_src);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // Tokens: one workgroup per (selected chunk, KV head).  The n keys sit in LDS.
 //  1. Radix select, 4 passes of 8 bits from the top: after the passes T is the k-th largest
 //     key and `need_eq` the number of keys equal to T that still fit (1 <= need_eq).
@@ -64,6 +137,7 @@ __global__ __launch_bounds__(PC_SEL_THREADS) void select_tokens_kernel(
   const int s = blockIdx.x / n_kv_heads;
   const int g = blockIdx.x % n_kv_heads;
   const int c = chunk_idx ? chunk_idx[s] : s;
+  if (c < 0) return;                               // no chunk for this entry: its outputs stay as they are
   const float* src = tok_score + ((long long)c * n_kv_heads + g) * n;
   int32_t* dst = out_idx + (long long)blockIdx.x * k;
 
@@ -176,9 +250,10 @@ int pc_launch_select_tokens(const float* tok_score, const int32_t* chunk_idx, in
                             int cls_hi, const int32_t* chunk_lens, int32_t* out_idx,
                             int32_t* out_cnt, hipStream_t st) {
   const size_t lds = (size_t)chunk_len * sizeof(uint32_t);
-  if (lds > 48 * 1024) {
-    PC_HIP_TRY(hipFuncSetAttribute((const void*)select_tokens_kernel,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (lds > 48 * 1024) {      // raised once per device, to the largest chunk the entry point accepts
+    static std::atomic<uint64_t> raised{0};
+    const int rc = pc_raise_dynamic_lds((const void*)select_tokens_kernel, 32768 * (int)sizeof(uint32_t), raised);
+    if (rc != PC_OK) return rc;
   }
   PcProfScope prof(PC_KERNEL_SELECT_TOKENS, st);
   hipLaunchKernelGGL(select_tokens_kernel, dim3(n_sel * n_kv_heads), dim3(PC_SEL_THREADS), lds, st,

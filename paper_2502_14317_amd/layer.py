@@ -90,8 +90,10 @@ class StreamingParallelComp:
     batch the queue holds the top keep_chunks of all chunks seen so far (score descending, earlier
     chunk first on ties, i.e. the offline top-k of the prefix); only the compacted KV of the chunks
     in the queue stays resident, an evicted chunk's slot is reused.  The final queue equals the
-    offline selection, whatever the batch size.  Host code here only owns buffers and the
-    chunk-id -> slot table; every computation is a library call."""
+    offline selection, whatever the batch size.  The queue and its slot table live on the device
+    (pc_chunk_queue_update), and the token selection and the gather of a batch's entrants are one
+    launch each, driven by the device-side slot table: no host round trip between batches.  Host
+    code here only owns buffers; every computation is a library call."""
 
     def __init__(self, n_chunks, batch_chunks, chunk_len, query_len, n_q_heads, n_kv_heads,
                  head_dim, obs_window, rope_base, keep_chunks, keep_tokens, softmax_scale=0.0,
@@ -108,7 +110,11 @@ class StreamingParallelComp:
         self.k_rope = torch.empty((bc, L, Hkv, D), dtype=bf, device=device)
         self.tok_score = torch.empty((bc, Hkv, chunk_len), dtype=f32, device=device)
         self.chunk_score = torch.empty((n_chunks,), dtype=f32, device=device)     # all chunks seen
-        self.chunk_idx = torch.empty((self.kc_n,), dtype=i32, device=device)
+        # the device-side queue: ids in rank order, their scores and KV slots; entrants per slot
+        self.queue_id = torch.full((self.kc_n,), -1, dtype=i32, device=device)
+        self.queue_score = torch.zeros((self.kc_n,), dtype=f32, device=device)
+        self.queue_slot = torch.zeros((self.kc_n,), dtype=i32, device=device)
+        self.slot_src = torch.full((self.kc_n,), -1, dtype=i32, device=device)
         self.tok_idx = torch.empty((self.kc_n, Hkv, keep_tokens), dtype=i32, device=device)   # by slot
         self.kc = torch.empty((1, self.kc_n, Hkv, keep_tokens, D), dtype=bf, device=device)   # by slot
         self.vc = torch.empty_like(self.kc)
@@ -121,14 +127,13 @@ class StreamingParallelComp:
         ws = max(B.pc_chunk_prefill_workspace_bytes(shape),
                  B.pc_parallel_attn_workspace_bytes(1, query_len, self.kc_n, keep_tokens, Hq, Hkv, D, True))
         self.ws = B.alloc_workspace(ws, device)
-        self.slot_of = {}            # global chunk id -> slot of its compacted KV
-        self.one = torch.zeros((1,), dtype=i32, device=device)
 
-    def forward(self, q, k, v):
+    def forward(self, q, k, v, after_batch=None):
         """q [C, L, H_q, D], k, v [C, L, H_kv, D] (any device-resident source; only one batch is
-        touched at a time).  Returns the global attention output of the query rows."""
-        free = list(range(self.kc_n))
-        self.slot_of = {}
+        touched at a time).  Returns the global attention output of the query rows.
+        after_batch(first chunk id, chunks in the batch): optional callback after each batch's
+        launches (tests read the queue there; it is not part of the path)."""
+        self.queue_id.fill_(-1)                                  # an empty queue (plain fill)
         for c0 in range(0, self.C, self.bc):
             c1 = min(c0 + self.bc, self.C)
             nb = c1 - c0
@@ -140,23 +145,18 @@ class StreamingParallelComp:
             if c0 == 0:              # the query rows of chunk 0 are the self segment (plain copies)
                 self.q_query.copy_(q[0, self.w:]); self.k_self.copy_(self.k_rope[0, self.w:])
                 self.v_self.copy_(v[0, self.w:])
-            keep = min(self.kc_n, c1)
-            B.pc_select_chunks_topk(self.chunk_score, c1, keep, self.chunk_idx, None)
-            queue = self.chunk_idx[:keep].tolist()                     # host: queue membership
-            for c in [c for c in self.slot_of if c not in queue]:
-                free.append(self.slot_of.pop(c))
-            for c in [c for c in queue if c not in self.slot_of]:      # entrants are in this batch
-                slot = free.pop()
-                self.slot_of[c] = slot
-                self.one.fill_(c - c0)
-                B.pc_select_tokens_topk(self.tok_score, self.one, 1, self.Hkv, self.w, self.kt_n,
-                                        self.tok_idx[slot:slot + 1])
-                B.pc_gather_kv(self.k_rope, v[c0:c1], self.one, self.tok_idx[slot:slot + 1], 1, nb,
-                               self.L, 1, self.Hkv, self.kt_n, self.D, self.kc[:, slot:slot + 1],
-                               self.vc[:, slot:slot + 1])
-        n_seg = len(self.slot_of)
+            # merge the batch into the queue; then select and gather its entrants, slot by slot
+            B.pc_chunk_queue_update(self.chunk_score[c0:c1], nb, c0, self.kc_n, self.queue_id,
+                                    self.queue_score, self.queue_slot, self.slot_src)
+            B.pc_select_tokens_topk(self.tok_score, self.slot_src, self.kc_n, self.Hkv, self.w,
+                                    self.kt_n, self.tok_idx)
+            B.pc_gather_kv(self.k_rope, v[c0:c1], self.slot_src, self.tok_idx, 1, nb, self.L, self.kc_n,
+                           self.Hkv, self.kt_n, self.D, self.kc, self.vc)
+            if after_batch is not None:
+                after_batch(c0, nb)
+        # every slot is filled once keep_chunks chunks have been seen (keep_chunks <= C)
         B.pc_parallel_attn(self.q_query, self.kc, self.vc, None, self.k_self, self.v_self, 1, self.wq,
-                           n_seg, self.kt_n, self.Hq, self.Hkv, self.D, self.w, self.rope_base,
+                           self.kc_n, self.kt_n, self.Hq, self.Hkv, self.D, self.w, self.rope_base,
                            self.scale, self.global_o, self.global_lse, self.ws)
         return self.global_o
 

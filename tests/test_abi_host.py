@@ -50,6 +50,12 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_mfma_ceiling(3, 256, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
     assert L.pc_mfma_ceiling(2, 0, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
     assert L.pc_mfma_ceiling(2, 256, 10, one, 1024, ctypes.byref(fl), None) == -3
+    # streaming chunk queue
+    assert L.pc_chunk_queue_update(None, 4, 0, 2, one, one, one, one, None) == -1
+    assert L.pc_chunk_queue_update(one, 4, 0, 2, one, one, one, None, None) == -1
+    assert L.pc_chunk_queue_update(one, 0, 0, 2, one, one, one, one, None) == -2
+    assert L.pc_chunk_queue_update(one, 4, 0, 2000, one, one, one, one, None) == -2
+    assert L.pc_chunk_queue_update(one, 4, -1, 2, one, one, one, one, None) == -2
     # select tokens
     assert L.pc_select_tokens_topk(None, None, 1, 1, 8, 2, one, None) == -1
     assert L.pc_select_tokens_topk(one, None, 1, 1, 8, 9, one, None) == -2
