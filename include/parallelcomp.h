@@ -261,6 +261,23 @@ int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_
  *   out = softmax over { dequantised segments } U { tail rows } exactly as pc_parallel_attn
  *   computes it on the dequantised values code * scale (each is exact in bf16).
  * Other arguments, errors and the workspace rule as pc_parallel_attn. */
+/* One-read quantisation.  pc_kv_quantize_fp8 reads every segment twice (maximum, then codes).
+ * pc_gather_kv_amax is pc_gather_kv that also leaves, per destination segment, the largest
+ * |value| of its K rows and of its V rows (k_amax, v_amax [batch, n_sel, H_kv] fp32 out; a
+ * segment with chunk_idx < 0 keeps its old maxima), taken while the rows are in flight; an
+ * integer maximum, so the result does not depend on timing.  pc_kv_quantize_fp8_amax takes
+ * those maxima ([B, S, H_kv], the maximum over the segment's valid rows: rows behind seg_len must
+ * not exceed it, which holds for a cache the gather filled, whose missing rows are zero) and
+ * writes the same codes and scales as pc_kv_quantize_fp8 from a single read of the segment. */
+int pc_gather_kv_amax(const void* k_src, const void* v_src, const int32_t* chunk_idx,
+                      const int32_t* tok_idx, int32_t batch, int32_t n_chunks,
+                      int32_t rows_per_chunk, int32_t n_sel, int32_t n_kv_heads, int32_t k,
+                      int32_t head_dim, void* k_dst, void* v_dst, float* k_amax, float* v_amax,
+                      void* stream);
+int pc_kv_quantize_fp8_amax(const void* kc, const void* vc, const float* k_amax, const float* v_amax,
+                            const int32_t* seg_len, int32_t seg_len_per_head, int32_t batch,
+                            int32_t n_seg, int32_t k_t, int32_t n_kv_heads, int32_t head_dim,
+                            void* k8, void* v8, float* k_scale, float* v_scale, void* stream);
 int pc_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
                        int32_t seg_len_per_head, int32_t batch, int32_t n_seg, int32_t k_t,
                        int32_t n_kv_heads, int32_t head_dim, void* k8, void* v8, float* k_scale,

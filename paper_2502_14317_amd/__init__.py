@@ -5,7 +5,7 @@ from .binding import (lib, make_shape, alloc_workspace, pc_shape, PcError, SYMBO
                       pc_chunk_prefill_attn, pc_chunk_prefill_workspace_bytes,
                       pc_chunk_query_scores, pc_chunk_query_scores_workspace_bytes,
                       pc_chunk_self_information, pc_select_chunks_topk, pc_chunk_queue_update, pc_select_tokens_topk, pc_select_tokens_calibrated,
-                      pc_gather_kv, pc_kv_append, pc_kv_quantize_fp8, pc_parallel_attn_fp8,
+                      pc_gather_kv, pc_gather_kv_amax, pc_kv_append, pc_kv_quantize_fp8, pc_kv_quantize_fp8_amax, pc_parallel_attn_fp8,
                       pc_parallel_attn_fp8_workspace_bytes,
                       pc_parallel_attn, pc_parallel_attn_workspace_bytes,
                       pc_parallel_attn_static, pc_parallel_attn_static_max_bytes,

@@ -24,7 +24,7 @@ SYMBOLS = [
     "pc_profile_get", "pc_kernel_name", "pc_mfma_ceiling", "pc_chunk_self_information", "pc_kv_append",
     "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
     "pc_profile_begin_kernel", "pc_parallel_attn_static", "pc_parallel_attn_static_max_bytes",
-    "pc_chunk_queue_update",
+    "pc_chunk_queue_update", "pc_gather_kv_amax", "pc_kv_quantize_fp8_amax",
 ]
 
 
@@ -73,6 +73,10 @@ def lib():
     L.pc_select_tokens_topk.restype = c_int
     L.pc_gather_kv.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P]
     L.pc_gather_kv.restype = c_int
+    L.pc_gather_kv_amax.argtypes = [P, P, P, P] + [c_int32] * 7 + [P, P, P, P, P]
+    L.pc_gather_kv_amax.restype = c_int
+    L.pc_kv_quantize_fp8_amax.argtypes = [P, P, P, P, P] + [c_int32] * 6 + [P, P, P, P, P]
+    L.pc_kv_quantize_fp8_amax.restype = c_int
     L.pc_parallel_attn.argtypes = [P] * 4 + [c_int32, P, P] + [c_int32] * 8 + [c_float, c_float, P, P, P, c_size_t, P]
     L.pc_select_tokens_calibrated.argtypes = [P, P] + [c_int32] * 4 + [c_float, c_int32, c_int32, P, P, P, P]
     L.pc_select_tokens_calibrated.restype = c_int
@@ -207,6 +211,22 @@ def pc_gather_kv(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chu
     _check(lib().pc_gather_kv(_ptr(k_src), _ptr(v_src), _ptr(chunk_idx), _ptr(tok_idx), batch,
                               n_chunks, rows_per_chunk, n_sel, n_kv_heads, k, head_dim,
                               _ptr(k_dst), _ptr(v_dst), _stream()), "pc_gather_kv")
+
+
+def pc_gather_kv_amax(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
+                      n_kv_heads, k, head_dim, k_dst, v_dst, k_amax, v_amax):
+    _check(lib().pc_gather_kv_amax(_ptr(k_src), _ptr(v_src), _ptr(chunk_idx), _ptr(tok_idx), batch,
+                                   n_chunks, rows_per_chunk, n_sel, n_kv_heads, k, head_dim,
+                                   _ptr(k_dst), _ptr(v_dst), _ptr(k_amax), _ptr(v_amax), _stream()),
+           "pc_gather_kv_amax")
+
+
+def pc_kv_quantize_fp8_amax(kc, vc, k_amax, v_amax, seg_len, batch, n_seg, k_t, n_kv_heads, head_dim,
+                            k8, v8, k_scale, v_scale, seg_len_per_head=0):
+    _check(lib().pc_kv_quantize_fp8_amax(_ptr(kc), _ptr(vc), _ptr(k_amax), _ptr(v_amax), _ptr(seg_len),
+                                         seg_len_per_head, batch, n_seg, k_t, n_kv_heads, head_dim,
+                                         _ptr(k8), _ptr(v8), _ptr(k_scale), _ptr(v_scale), _stream()),
+           "pc_kv_quantize_fp8_amax")
 
 
 def pc_parallel_attn(q, kc, vc, seg_len, k_self, v_self, batch, n_q, n_seg, k_t, n_q_heads,

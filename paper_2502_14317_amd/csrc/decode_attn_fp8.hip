@@ -10,8 +10,10 @@
 //
 // kv_quantize_fp8_kernel   one workgroup per (sequence, segment, KV head, K or V): maximum,
 //                          then codes; the second sweep reads the segment again (5 bytes per
-//                          element in all).  Codes are written in 32-key blocks laid out for
-//                          the matrix cores (below), V transposed.
+//                          element in all), unless the caller hands in the maxima (the gather
+//                          that fills the cache can leave them: 3 bytes per element).  Codes are
+//                          written in 32-key blocks laid out for the matrix cores (below), V
+//                          transposed.
 // decode_attn_fp8_kernel   the split-KV kernel of decode_attn.hip on 8-bit operands: codes are
 //                          widened in registers (every E4M3 value is exact in bf16), both
 //                          products run on the 16x16x32 bf16 MFMA, the scales are folded into the
@@ -51,6 +53,7 @@
 __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
     const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
     const int32_t* __restrict__ seg_len, int per_head, int n_kv_heads, int k_t, int D,
+    const float* __restrict__ k_amax, const float* __restrict__ v_amax,
     uint8_t* __restrict__ k8, uint8_t* __restrict__ v8, float* __restrict__ k_scale,
     float* __restrict__ v_scale) {
   __shared__ uint32_t red[PC_Q8_THREADS / PC_WAVE];
@@ -66,9 +69,11 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
   const long long n_all = (long long)n_blk * 32 * D / 8;
   const int gpr = D / 8;                                   // groups per row
 
-  // largest magnitude: bf16 magnitudes order like their 15-bit patterns
+  // largest magnitude: bf16 magnitudes order like their 15-bit patterns.  When the caller knows
+  // it already (the gather leaves it), the first sweep is skipped and the segment is read once.
+  const float* amax_in = blockIdx.y ? v_amax : k_amax;
   uint32_t amax = 0;
-  for (long long i0 = 0; i0 < n_valid; i0 += PC_Q8_THREADS * PC_Q8_UNROLL) {
+  for (long long i0 = 0; amax_in == nullptr && i0 < n_valid; i0 += PC_Q8_THREADS * PC_Q8_UNROLL) {
     uint4 x[PC_Q8_UNROLL];
 #pragma unroll
     for (int u = 0; u < PC_Q8_UNROLL; ++u) {
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
   amax = 0;
 #pragma unroll
   for (int w = 0; w < PC_Q8_THREADS / PC_WAVE; ++w) amax = max(amax, red[w]);
-  const float fmax_ = __uint_as_float(amax << 16);
+  const float fmax_ = amax_in ? fabsf(amax_in[seg]) : __uint_as_float(amax << 16);
   const float scale = fmax_ > 0.f ? fmax_ / PC_E4M3_MAX : 1.0f;
   if (threadIdx.x == 0) scale_out[seg] = scale;
 
@@ -148,14 +153,14 @@ __global__ __launch_bounds__(PC_Q8_THREADS) void kv_quantize_fp8_kernel(
 
 int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
                               int seg_len_per_head, long long n_segs, int n_kv_heads, int k_t,
-                              int head_dim, void* k8, void* v8, float* k_scale, float* v_scale,
-                              hipStream_t st) {
+                              int head_dim, const float* k_amax, const float* v_amax, void* k8,
+                              void* v8, float* k_scale, float* v_scale, hipStream_t st) {
   if (n_segs == 0) return PC_OK;
   if (n_segs > 0x7fffffffLL) return PC_ERR_SHAPE;
   PcProfScope prof(PC_KERNEL_KV_QUANTIZE, st);
   hipLaunchKernelGGL(kv_quantize_fp8_kernel, dim3((unsigned)n_segs, 2), dim3(PC_Q8_THREADS), 0, st,
                      (const uint16_t*)kc, (const uint16_t*)vc, seg_len, seg_len_per_head, n_kv_heads,
-                     k_t, head_dim, (uint8_t*)k8, (uint8_t*)v8, k_scale, v_scale);
+                     k_t, head_dim, k_amax, v_amax, (uint8_t*)k8, (uint8_t*)v8, k_scale, v_scale);
   PC_LAUNCH_CHECK();
   return PC_OK;
 }

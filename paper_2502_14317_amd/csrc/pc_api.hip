@@ -243,7 +243,24 @@ extern "C" int pc_kv_quantize_fp8(const void* kc, const void* vc, const int32_t*
     return PC_ERR_SHAPE;
   return pc_launch_kv_quantize_fp8(kc, vc, seg_len, seg_len_per_head,
                                    (long long)batch * n_seg * n_kv_heads, n_kv_heads, k_t, head_dim,
-                                   k8, v8, k_scale, v_scale, (hipStream_t)stream);
+                                   nullptr, nullptr, k8, v8, k_scale, v_scale, (hipStream_t)stream);
+}
+
+extern "C" int pc_kv_quantize_fp8_amax(const void* kc, const void* vc, const float* k_amax,
+                                       const float* v_amax, const int32_t* seg_len,
+                                       int32_t seg_len_per_head, int32_t batch, int32_t n_seg,
+                                       int32_t k_t, int32_t n_kv_heads, int32_t head_dim, void* k8,
+                                       void* v8, float* k_scale, float* v_scale, void* stream) {
+  if (batch < 0 || n_seg < 0 || k_t < 1 || n_kv_heads < 1) return PC_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
+  if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
+  if (batch == 0 || n_seg == 0) return PC_OK;
+  if (!kc || !vc || !k_amax || !v_amax || !k8 || !v8 || !k_scale || !v_scale) return PC_ERR_NULL;
+  if (!pc_aligned(kc, 16) || !pc_aligned(vc, 16) || !pc_aligned(k8, 16) || !pc_aligned(v8, 16))
+    return PC_ERR_SHAPE;
+  return pc_launch_kv_quantize_fp8(kc, vc, seg_len, seg_len_per_head,
+                                   (long long)batch * n_seg * n_kv_heads, n_kv_heads, k_t, head_dim,
+                                   k_amax, v_amax, k8, v8, k_scale, v_scale, (hipStream_t)stream);
 }
 
 struct Par8Ws {
@@ -402,7 +419,22 @@ extern "C" int pc_gather_kv(const void* k_src, const void* v_src, const int32_t*
   if (!pc_aligned(k_src, 16) || !pc_aligned(v_src, 16) || !pc_aligned(k_dst, 16) || !pc_aligned(v_dst, 16))
     return PC_ERR_SHAPE;
   return pc_launch_gather(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
-                          n_kv_heads, k, head_dim, k_dst, v_dst, (hipStream_t)stream);
+                          n_kv_heads, k, head_dim, k_dst, v_dst, nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int pc_gather_kv_amax(const void* k_src, const void* v_src, const int32_t* chunk_idx,
+                                 const int32_t* tok_idx, int32_t batch, int32_t n_chunks,
+                                 int32_t rows_per_chunk, int32_t n_sel, int32_t n_kv_heads, int32_t k,
+                                 int32_t head_dim, void* k_dst, void* v_dst, float* k_amax,
+                                 float* v_amax, void* stream) {
+  if (!k_src || !v_src || !tok_idx || !k_dst || !v_dst || !k_amax || !v_amax) return PC_ERR_NULL;
+  if (batch < 0 || n_chunks < 1 || rows_per_chunk < 1 || n_sel < 0 || n_kv_heads < 1 || k < 1)
+    return PC_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return PC_ERR_SHAPE;
+  if (!pc_aligned(k_src, 16) || !pc_aligned(v_src, 16) || !pc_aligned(k_dst, 16) || !pc_aligned(v_dst, 16))
+    return PC_ERR_SHAPE;
+  return pc_launch_gather(k_src, v_src, chunk_idx, tok_idx, batch, n_chunks, rows_per_chunk, n_sel,
+                          n_kv_heads, k, head_dim, k_dst, v_dst, k_amax, v_amax, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------- parallel attention

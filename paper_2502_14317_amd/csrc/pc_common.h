@@ -110,7 +110,7 @@ __device__ __forceinline__ uint32_t pc_order_key(float f) {
 int pc_launch_gather(const void* k_src, const void* v_src, const int32_t* chunk_idx,
                      const int32_t* tok_idx, int batch, int n_chunks, int rows, int n_sel,
                      int n_kv_heads, int k, int head_dim, void* k_dst, void* v_dst,
-                     hipStream_t st);
+                     float* k_amax, float* v_amax, hipStream_t st);   // amax: both or neither
 int pc_launch_select_chunks(const float* score, int n, int k, int32_t* out_idx, float* out_score,
                             hipStream_t st);
 // cls_lo >= cls_hi: plain top-k (Eq. 7); else Eq. 8 first.  out_cnt may be nullptr.
@@ -264,10 +264,12 @@ int pc_launch_decode(const void* q_rot, const void* kc, const void* vc, const in
                      int seg_len_per_head, int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,
                      int head_dim, float scale, float* part_o, float* part_lse, int n_parts, int part0,
                      hipStream_t st);
+// k_amax, v_amax [n_segs] (both or neither): the largest |value| of every segment's valid rows,
+// known beforehand (the gather leaves it): the kernel then reads the segment once
 int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
                               int seg_len_per_head, long long n_segs, int n_kv_heads, int k_t,
-                              int head_dim, void* k8, void* v8, float* k_scale, float* v_scale,
-                              hipStream_t st);
+                              int head_dim, const float* k_amax, const float* v_amax, void* k8,
+                              void* v8, float* k_scale, float* v_scale, hipStream_t st);
 int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, const float* k_scale,
                          const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
                          int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,

@@ -112,3 +112,60 @@ def pinned_tiles(P, o, lse, v, tile=64):
         bad_l = -np.log(denom) > LSE_ATOL + 1e-3 * np.abs(lse[:, h, None])
         pin |= ((bad_o | bad_l) & ok).any(axis=0)
     return pin
+
+
+# ------------------------------------------------------------------ 8-bit cache: layout views
+# Host-side views of the 32-key block layout that pc_kv_quantize_fp8 writes and
+# pc_parallel_attn_fp8 reads (include/parallelcomp.h states it), in both directions, so the tests
+# can compare codes with the oracle's row-ordered ones.
+def fp8_rows(k_t):
+    """Key rows the codes of a segment occupy: whole 32-key blocks."""
+    return (k_t + 31) // 32 * 32
+
+
+def _fp8_perm(which, n, to_rows):
+    # K block: [blk, tile, i, kk, c, b]  (key = 16 tile + c, d = 64 i + 16 kk + b)
+    # V block: [blk, q, g, m, h, j / 4, j % 4]  (key = 16 (j / 4) + 4 g + j % 4, d = 32 q + 16 h + m)
+    if which == "k":
+        fwd = (n, n + 1, n + 4, n + 2, n + 3, n + 5)               # -> blk, tile, c, i, kk, b
+    else:
+        fwd = (n, n + 5, n + 2, n + 6, n + 1, n + 4, n + 3)        # -> blk, j / 4, g, j % 4, q, h, m
+    if to_rows:
+        return fwd
+    inv = [0] * len(fwd)
+    for pos, src in enumerate(fwd):
+        inv[src - n] = n + pos
+    return tuple(inv)
+
+
+def _fp8_block_shape(which, n_blk, head_dim):
+    return (n_blk, 2, head_dim // 64, 4, 16, 16) if which == "k" else (n_blk, head_dim // 32, 4, 16, 2, 2, 4)
+
+
+def _fp8_row_shape(which, n_blk, head_dim):
+    return (n_blk, 2, 16, head_dim // 64, 4, 16) if which == "k" else (n_blk, 2, 4, 4, head_dim // 32, 2, 16)
+
+
+def fp8_rows_view(which, codes, k_t, head_dim, padded=False):
+    """The K ("k") or V ("v") codes in row order [..., k_t, D] (a copy; with padded=True all
+    ceil(k_t / 32) * 32 rows) from the block layout the kernels use.  K block of 32 keys: two
+    16-key tiles of D / 64 pieces of 64 lanes x 16 bytes, lane 16 kk + c holding d = 64 i + 16 kk
+    .. + 15 of key c of the tile.  V block: D / 32 pieces of 64 lanes x 16 bytes, lane 16 g + m
+    holding [h][j] with d = 32 q + 16 h + m and key 4 g + j (j < 4) or 16 + 4 g + j - 4 (j >= 4)."""
+    lead = codes.shape[:-1]
+    n_blk, n = fp8_rows(k_t) // 32, len(codes.shape) - 1
+    x = codes.reshape(*lead, *_fp8_block_shape(which, n_blk, head_dim))
+    x = x.permute(*range(n), *_fp8_perm(which, n, True))
+    return x.reshape(*lead, n_blk * 32, head_dim)[..., :(n_blk * 32 if padded else k_t), :].contiguous()
+
+
+def fp8_from_rows(which, codes):
+    """Inverse of fp8_rows_view: codes [..., k_t, D] uint8 in row order -> the block layout
+    [..., ceil(k_t / 32) * 32 * D] (keys behind k_t get code 0)."""
+    lead, k_t, head_dim = codes.shape[:-2], codes.shape[-2], codes.shape[-1]
+    n_blk, n = fp8_rows(k_t) // 32, len(codes.shape) - 2
+    x = torch.zeros((*lead, n_blk * 32, head_dim), dtype=torch.uint8, device=codes.device)
+    x[..., :k_t, :] = codes
+    x = x.reshape(*lead, *_fp8_row_shape(which, n_blk, head_dim))
+    x = x.permute(*range(n), *_fp8_perm(which, n, False))
+    return x.reshape(*lead, n_blk * 32 * head_dim).contiguous()

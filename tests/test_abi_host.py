@@ -50,6 +50,11 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_mfma_ceiling(3, 256, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
     assert L.pc_mfma_ceiling(2, 0, 10, one, 1 << 20, ctypes.byref(fl), None) == -2
     assert L.pc_mfma_ceiling(2, 256, 10, one, 1024, ctypes.byref(fl), None) == -3
+    # gather with maxima, one-read quantisation
+    assert L.pc_gather_kv_amax(one, one, None, one, 1, 2, 8, 1, 1, 4, 128, one, one, None, one, None) == -1
+    assert L.pc_gather_kv_amax(one, one, None, one, 1, 2, 8, 1, 1, 4, 96, one, one, one, one, None) == -2
+    assert L.pc_kv_quantize_fp8_amax(one, one, None, one, None, 0, 1, 1, 4, 1, 128, one, one, one, one, None) == -1
+    assert L.pc_kv_quantize_fp8_amax(one, one, one, one, None, 2, 1, 1, 4, 1, 128, one, one, one, one, None) == -2
     # streaming chunk queue
     assert L.pc_chunk_queue_update(None, 4, 0, 2, one, one, one, one, None) == -1
     assert L.pc_chunk_queue_update(one, 4, 0, 2, one, one, one, None, None) == -1

@@ -7,9 +7,10 @@ import torch
 
 import oracle
 import paper_2502_14317_amd as pc
-from paper_2502_14317_amd.layer import fp8_alloc, fp8_rows_view, fp8_from_rows
+from paper_2502_14317_amd.layer import fp8_alloc
 from workloads import CFG4, f32_to_bf16_bits, bf16_bits_to_f64
-from helpers import (O_ATOL, O_RTOL, LSE_ATOL, bits_to_dev, dev_bf16_to_f64, assert_close)
+from helpers import (O_ATOL, O_RTOL, LSE_ATOL, bits_to_dev, dev_to_bits, dev_bf16_to_f64, assert_close,
+                     fp8_rows_view, fp8_from_rows)
 
 pytestmark = pytest.mark.gpu
 
@@ -250,3 +251,59 @@ def test_fp8_decode_full_size_sampled():
                                                 oracle.dequantize_kv_fp8(rv8, rvs))
         assert_close(dev_bf16_to_f64(out[b, :, gk * G:(gk + 1) * G]), ro, O_ATOL, O_RTOL, f"fp8 decode out[b={b},g={gk}]")
         assert_close(lse[b, gk * G:(gk + 1) * G, 0].cpu().numpy(), rl[0], LSE_ATOL, 1e-3, f"fp8 decode lse[b={b},g={gk}]")
+
+
+def test_gather_amax_and_one_read_quantisation_bit_exact():
+    """pc_gather_kv_amax = pc_gather_kv + the per-segment maxima of |K| and |V| (bit-exact against
+    the maxima of the oracle's gathered rows); pc_kv_quantize_fp8_amax with those maxima writes the
+    oracle's codes and scales (= what the two-read entry point writes).  Missing tokens (-1), a
+    segment without a source chunk (skipped, keeps its contents) and a block straddling two
+    segments (k not a multiple of the gather's rows per block) are all in."""
+    _say("gather + amax, one-read quantisation")
+    r = np.random.default_rng(57)
+    B, C, rows, Hkv, S, k, D = 2, 4, 300, 2, 3, 100, 128
+    ks = _mk(r, (B, C, rows, Hkv, D), 3.0); vs = _mk(r, (B, C, rows, Hkv, D), 0.2)
+    ks[1, 2, 17, 1] = f32_to_bf16_bits(np.full(D, -91.0, dtype=np.float32))     # an outlier row
+    cidx = np.array([[3, -1, 0], [2, 2, 1]], dtype=np.int32)
+    tidx = np.sort(np.stack([np.stack([np.stack([r.choice(rows, size=k, replace=False) for _ in range(Hkv)])
+                                       for _ in range(S)]) for _ in range(B)]), axis=-1).astype(np.int32)
+    cnt = r.integers(1, k + 1, size=(B, S, Hkv)).astype(np.int32)
+    for b in range(B):
+        for s_ in range(S):
+            for g in range(Hkv):
+                tidx[b, s_, g, cnt[b, s_, g]:] = -1                              # a head that kept fewer tokens
+    tidx[1, 1, 0, :cnt[1, 1, 0]] = np.sort(np.append(r.choice(rows, size=cnt[1, 1, 0] - 1, replace=False), 17))[:cnt[1, 1, 0]]
+    bf = torch.bfloat16
+    kd = torch.full((B, S, Hkv, k, D), 5.0, dtype=bf, device="cuda"); vd = torch.full_like(kd, 5.0)
+    kd2 = kd.clone(); vd2 = vd.clone()
+    ka = torch.full((B, S, Hkv), 123.0, dtype=torch.float32, device="cuda"); va = torch.full_like(ka, 123.0)
+    dks, dvs, dc, dt = bits_to_dev(ks), bits_to_dev(vs), torch.from_numpy(cidx).cuda(), torch.from_numpy(tidx).cuda()
+    pc.pc_gather_kv(dks, dvs, dc, dt, B, C, rows, S, Hkv, k, D, kd2, vd2)
+    pc.pc_gather_kv_amax(dks, dvs, dc, dt, B, C, rows, S, Hkv, k, D, kd, vd, ka, va)
+    torch.cuda.synchronize()
+    assert torch.equal(kd.view(torch.int16), kd2.view(torch.int16)) and torch.equal(vd.view(torch.int16), vd2.view(torch.int16))
+    ka_h, va_h = ka.cpu().numpy(), va.cpu().numpy()
+    for b in range(B):
+        live = [s_ for s_ in range(S) if cidx[b, s_] >= 0]
+        rk, rv = oracle.gather_kv(ks[b], vs[b], cidx[b, live], tidx[b, live])
+        assert np.array_equal(dev_to_bits(kd[b, live]), rk) and np.array_equal(dev_to_bits(vd[b, live]), rv)
+        np.testing.assert_array_equal(ka_h[b, live], np.abs(bf16_bits_to_f64(rk)).max(axis=(2, 3)))
+        np.testing.assert_array_equal(va_h[b, live], np.abs(bf16_bits_to_f64(rv)).max(axis=(2, 3)))
+    assert (ka_h[0, 1] == 123.0).all() and (va_h[0, 1] == 123.0).all() and (kd[0, 1] == 5.0).all()
+    # quantise the gathered cache from one read; the skipped segment gets a maximum of its own
+    ka[0, 1] = 5.0; va[0, 1] = 5.0
+    k8 = fp8_alloc(B, S, Hkv, k, D).fill_(0x55); v8 = fp8_alloc(B, S, Hkv, k, D).fill_(0x55)
+    sk = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); sv = torch.empty_like(sk)
+    dcnt = torch.from_numpy(cnt).cuda()
+    pc.pc_kv_quantize_fp8_amax(kd, vd, ka, va, dcnt, B, S, k, Hkv, D, k8, v8, sk, sv, seg_len_per_head=1)
+    k8b = fp8_alloc(B, S, Hkv, k, D).fill_(0x55); v8b = fp8_alloc(B, S, Hkv, k, D).fill_(0x55)
+    skb = torch.empty_like(sk); svb = torch.empty_like(sk)
+    pc.pc_kv_quantize_fp8(kd, vd, dcnt, B, S, k, Hkv, D, k8b, v8b, skb, svb, seg_len_per_head=1)
+    torch.cuda.synchronize()
+    assert torch.equal(k8, k8b) and torch.equal(v8, v8b) and torch.equal(sk, skb) and torch.equal(sv, svb)
+    for b in range(B):
+        rk8, rks, rv8, rvs = oracle.quantize_kv_fp8(dev_bf16_to_f64(kd[b]), dev_bf16_to_f64(vd[b]), cnt[b])
+        np.testing.assert_array_equal(fp8_rows_view("k", k8[b], k, D).cpu().numpy(), rk8)
+        np.testing.assert_array_equal(fp8_rows_view("v", v8[b], k, D).cpu().numpy(), rv8)
+        np.testing.assert_array_equal(sk[b].cpu().numpy(), rks)
+        np.testing.assert_array_equal(sv[b].cpu().numpy(), rvs)
