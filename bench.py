@@ -72,6 +72,31 @@ def bench_calibration(pc, torch, cfg, layer, qd, vd, steps):
                                     "eq8_then_eq7": round(sum(cal.values()), 4)}}
 
 
+def bench_scores_all_rows(pc, torch, cfg, qd, kd, steps):
+    """Eq. 6 as printed: every query row votes (w_obs = w_q) instead of the config's window.  The
+    standalone score call on the timed workload: its cost grows with the voting rows (the
+    probability block is recomputed in rounds of 128 (row, head) columns)."""
+    shape = pc.make_shape(cfg.n_chunks, cfg.chunk_len, cfg.query_len, cfg.n_q_heads, cfg.n_kv_heads,
+                          cfg.head_dim, cfg.query_len, cfg.rope_base)
+    ts = torch.empty((cfg.n_chunks, cfg.n_kv_heads, cfg.chunk_len), dtype=torch.float32, device="cuda")
+    cs = torch.empty((cfg.n_chunks,), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_chunk_query_scores_workspace_bytes(shape))
+    run = lambda: pc.pc_chunk_query_scores(shape, qd, kd, ts, cs, ws)
+    run(); torch.cuda.synchronize()
+    pc.pc_profile_begin()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    acc = {}
+    for name, ms in pc.pc_profile_records():
+        acc[name] = acc.get(name, 0.0) + ms / steps
+    flops = 2.0 * 3 * 2 * cfg.head_dim * cfg.query_len * cfg.n_q_heads * cfg.seq_len * cfg.n_chunks   # two passes, split bf16
+    total = sum(acc.values())
+    return {"obs_window": cfg.query_len, "kernel_ms": {k: round(v, 4) for k, v in acc.items()},
+            "total_ms": round(total, 4), "mfma_flops": flops, "tflops": flops / (total * 1e-3) / 1e12}
+
+
 def bench_streaming(torch, cfg, qd, kd, vd, steps):
     """The layer with chunks arriving in batches and a resident priority queue of the kept
     chunks' compacted KV (the memory-bounded mode of sec. 3.1): time per layer and resident bytes."""
@@ -200,7 +225,8 @@ def bench_ceilings(pc, torch):
     """What this machine sustains on the two rooflines' resources: a loop of nothing but MFMAs on
     constant and on random operands (the shader clock depends on the data: the part is
     power-limited), the same loop with attention's per-MFMA LDS operand read and softmax element
-    added (the power-limited ceiling of a flash-attention instruction mix), and a plain device copy."""
+    added (the power-limited ceiling of a flash-attention instruction mix), a plain device copy
+    (torch) and the library's bare copy loop with and without the non-temporal hint."""
     n_cus = torch.cuda.get_device_properties(0).multi_processor_count
     scratch = torch.empty((n_cus * 512,), dtype=torch.float32, device="cuda")
     out = {}
@@ -228,6 +254,19 @@ def bench_ceilings(pc, torch):
         if rep:
             best = max(best, 2.0 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3))
     out["device_copy"] = {"achieved": best / 1e9, "unit": "GB/s", "frac_of_peak": best / PEAK_HBM_BYTES}
+    # the library's own bare copy loop, ordinary and with the non-temporal hint on both sides (the
+    # gather's instructions): the read+write ceiling the gather's fraction is to be read against
+    for name, mode in (("copy_loop", 0), ("copy_loop_nontemporal", 1)):
+        best = 0.0
+        for rep in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pc.pc_copy_ceiling(mode, a, b)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep:
+                best = max(best, 2.0 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3))
+        out[name] = {"achieved": best / 1e9, "unit": "GB/s", "frac_of_peak": best / PEAK_HBM_BYTES}
     del a, b, scratch
     torch.cuda.empty_cache()
     return out
@@ -354,6 +393,17 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
     o = torch.empty((B, 1, Hq, D), dtype=bf, device="cuda")
     ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, 1, S, kt, 0, Hq, Hkv, D))
     quant = lambda: pc.pc_kv_quantize_fp8(kc, vc, None, B, S, kt, Hkv, D, k8, v8, ks, vs)
+    # the per-segment maxima as pc_gather_kv_amax leaves them when it fills the cache (here: an
+    # identity gather of the cache onto a copy), for the quantisation that reads once
+    ka = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); va = torch.empty_like(ka)
+    ident = torch.arange(kt, dtype=torch.int32, device="cuda").expand(B, S, Hkv, kt).contiguous()
+    kc2, vc2 = torch.empty_like(kc), torch.empty_like(vc)
+    pc.pc_gather_kv_amax(kc.view(B, S * Hkv, kt, 1, D), vc.view(B, S * Hkv, kt, 1, D), None,
+                         ident.view(B, S * Hkv, 1, kt), B, S * Hkv, kt, S * Hkv, 1, kt, D,
+                         kc2.view(B, S * Hkv, 1, kt, D), vc2.view(B, S * Hkv, 1, kt, D), ka.view(B, S * Hkv, 1), va.view(B, S * Hkv, 1))
+    torch.cuda.synchronize()
+    del kc2, vc2, ident
+    quant1 = lambda: pc.pc_kv_quantize_fp8_amax(kc, vc, ka, va, None, B, S, kt, Hkv, D, k8, v8, ks, vs)
     run = lambda: pc.pc_parallel_attn_fp8(q, k8, v8, ks, vs, None, None, None, None, 0, B, 1, S, kt, Hq, Hkv,
                                           D, -1, 1.0e4, 0.0, o, None, ws)
     for _ in range(warmup):
@@ -365,6 +415,13 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
     torch.cuda.synchronize()
     pc.pc_profile_end()
     per = {"kv_quantize_fp8_kernel": [ms for name, ms in pc.pc_profile_records()]}
+    quant1(); torch.cuda.synchronize()
+    pc.pc_profile_begin("kv_quantize_fp8_kernel")
+    for _ in range(3):
+        quant1()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    q1_avg = sum(ms for name, ms in pc.pc_profile_records()) / 3 * 1e-3
     pc.pc_profile_begin("decode_attn_fp8_kernel")
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -386,7 +443,11 @@ def bench_decode_fp8(pc, torch, cfg, g, steps, warmup):
            "quantize": {"bound": "hbm", "kernel": "kv_quantize_fp8_kernel", "achieved": q_bytes / q_avg / 1e9,
                         "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": q_bytes / q_avg / PEAK_HBM_BYTES,
                         "kernel_ms": q_avg * 1e3,
-                        "traffic": MEASURED_TRAFFIC.get(("kv_quantize_fp8_kernel", cfg.name))}}
+                        "traffic": MEASURED_TRAFFIC.get(("kv_quantize_fp8_kernel", cfg.name))},
+           "quantize_one_read": {"bound": "hbm", "kernel": "kv_quantize_fp8_kernel (maxima from pc_gather_kv_amax)",
+                                 "achieved": q_bytes / q1_avg / 1e9, "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
+                                 "frac": q_bytes / q1_avg / PEAK_HBM_BYTES, "kernel_ms": q1_avg * 1e3,
+                                 "traffic": MEASURED_TRAFFIC.get(("kv_quantize_fp8_kernel one read", cfg.name))}}
     del kc, vc, k8, v8
     torch.cuda.empty_cache()
     return res
@@ -421,9 +482,27 @@ def bench_other_config(pc, torch, name, steps=3, warmup=1):
     fl = [ms for n, ms in pc.pc_profile_records() if n == "flash_fwd_kernel"]
     fl = fl[0::len(fl) // steps]
     flash_avg = sum(fl) / len(fl) * 1e-3
-    del layer, qd, kd, vd
+    # without the per-kernel event records, eager and as a HIP graph replay (no per-launch host work)
+    step(); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        step()
+    gr.replay(); torch.cuda.synchronize()
+    n_rep = steps * (20 if dt < 1e-3 else 1)
+    t0 = time.perf_counter()
+    for _ in range(n_rep):
+        gr.replay()
+    torch.cuda.synchronize()
+    dt_graph = (time.perf_counter() - t0) / n_rep
+    del gr, layer, qd, kd, vd
     torch.cuda.empty_cache()
     return {"step": "chunk prefill + scores" if prefill_only else "whole path", "ms_per_step": dt * 1e3,
+            "graph_replay_ms_per_step": dt_graph * 1e3,
             "tokens_per_s_per_layer": cfg.context_tokens / dt, "flash_kernel_ms": flash_avg * 1e3,
             "flash_frac_of_bf16_mfma_peak": flash_flops(cfg) / flash_avg / PEAK_BF16_FLOPS}
 
@@ -499,6 +578,19 @@ def bench_secondary(pc, torch, steps, warmup):
                                            "unit": "GB/s", "frac": g_bytes / k_avg / PEAK_HBM_BYTES,
                                            "kernel_ms": k_avg * 1e3,
                                            "traffic": MEASURED_TRAFFIC.get(("gather_kv_kernel", cfg.name))}}
+    # the same gather leaving the per-segment maxima of |K|, |V| for the one-read quantisation
+    ka = torch.empty((B, S, Hkv), dtype=torch.float32, device="cuda"); va = torch.empty_like(ka)
+    run = lambda: pc.pc_gather_kv_amax(ks, vs, None, idx, B, S, R, S, Hkv, kt, D, kd, vd, ka, va)
+    run(); torch.cuda.synchronize()
+    pc.pc_profile_begin("gather_kv_kernel")
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    pc.pc_profile_end()
+    k_ms = [ms for name, ms in pc.pc_profile_records()]
+    a_avg = sum(k_ms) / len(k_ms) * 1e-3
+    out["gather_kv_amax"] = {"kernel_ms": a_avg * 1e3, "achieved": g_bytes / a_avg / 1e9, "unit": "GB/s",
+                             "frac": g_bytes / a_avg / PEAK_HBM_BYTES}
     return out
 
 
@@ -615,6 +707,8 @@ def main():
                               "tokens_per_s_per_layer": cfg.context_tokens / ((time.perf_counter() - t0) / args.steps)}
     del gr
     result["flash_zero_operands"] = bench_flash_zero_operands(pc, torch, cfg, layer, qd, kd, vd, max(args.steps // 2, 3))
+    if cfg.query_len > cfg.obs_window:
+        result["scores_every_query_row_votes"] = bench_scores_all_rows(pc, torch, cfg, qd, kd, 3)
     if not prefill_only:
         result["calibration"] = bench_calibration(pc, torch, cfg, layer, qd, vd, max(args.steps, 5))
         result["streaming"] = bench_streaming(torch, cfg, qd, kd, vd, max(args.steps // 2, 3))
@@ -629,7 +723,11 @@ def main():
         result["self_information"] = bench_self_info(pc, torch, max(args.steps, 5))
         if args.workload == "cfg1_llama3_8b_128k":
             result["other_configs"] = {n: bench_other_config(pc, torch, n) for n in
-                                       ("cfg0_tiny_mha", "cfg2_llama2_7b_128k", "cfg3_llama3_8b_512k_stress")}
+                                       ("cfg0_tiny_mha", "cfg2_llama2_7b_128k", "cfg3_llama3_8b_512k_stress",
+                                        # the timed shape on peaked inputs (logit std 2, unit-variance
+                                        # V): the lazy-rescale branch and the power-limited clock
+                                        # both depend on the data
+                                        "cfg1p_llama3_8b_128k_peaked")}
         result["chunk_scaling"] = bench_chunk_scaling(pc, torch)
         result["ceilings"] = bench_ceilings(pc, torch)
         print(f"[bench] secondary done; ceilings {result['ceilings']}", file=sys.stderr, flush=True)

@@ -52,6 +52,13 @@ const char* pc_kernel_name(int kernel_id);
 int pc_mfma_ceiling(int mode, int n_cus, int iters, float* scratch, size_t scratch_bytes,
                     double* flops, void* stream);
 
+/* ---- copy ceiling (measurement aid) -----------------------------------------------------------
+ * Enqueues a bare copy of `bytes` bytes (device pointers, 16-byte aligned, bytes a multiple of
+ * 16) with 16-byte loads and stores, four in flight per thread: mode 0 ordinary, mode 1 with the
+ * non-temporal hint on both sides.  The caller times it: what a read-and-write stream sustains on
+ * this machine.  PC_ERR_NULL / PC_ERR_SHAPE / PC_ERR_HIP. */
+int pc_copy_ceiling(int mode, const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,4 +9,4 @@ from .binding import (lib, make_shape, alloc_workspace, pc_shape, PcError, SYMBO
                       pc_parallel_attn_fp8_workspace_bytes,
                       pc_parallel_attn, pc_parallel_attn_workspace_bytes,
                       pc_parallel_attn_static, pc_parallel_attn_static_max_bytes,
-                      pc_profile_begin, pc_profile_end, pc_profile_records, pc_mfma_ceiling)
+                      pc_profile_begin, pc_profile_end, pc_profile_records, pc_mfma_ceiling, pc_copy_ceiling)

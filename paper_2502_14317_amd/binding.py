@@ -25,6 +25,7 @@ SYMBOLS = [
     "pc_kv_quantize_fp8", "pc_parallel_attn_fp8", "pc_parallel_attn_fp8_workspace_bytes",
     "pc_profile_begin_kernel", "pc_parallel_attn_static", "pc_parallel_attn_static_max_bytes",
     "pc_chunk_queue_update", "pc_gather_kv_amax", "pc_kv_quantize_fp8_amax",
+    "pc_copy_ceiling",
 ]
 
 
@@ -98,6 +99,8 @@ def lib():
     L.pc_kernel_name.restype = c_char_p
     L.pc_mfma_ceiling.argtypes = [c_int, c_int, c_int, P, c_size_t, POINTER(ctypes.c_double), P]
     L.pc_mfma_ceiling.restype = c_int
+    L.pc_copy_ceiling.argtypes = [c_int, P, P, c_size_t, P]
+    L.pc_copy_ceiling.restype = c_int
     L.pc_chunk_self_information.argtypes = [P, P, c_int32, c_int32, c_int32, c_int32, P, P, P]
     L.pc_chunk_self_information.restype = c_int
     L.pc_kv_append.argtypes = [P, P] + [c_int32] * 8 + [c_float, P, P, P, c_int32, P]
@@ -309,6 +312,12 @@ def pc_mfma_ceiling(mode, n_cus, iters, scratch):
                                  scratch.numel() * scratch.element_size(), ctypes.byref(flops),
                                  _stream()), "pc_mfma_ceiling")
     return flops.value
+
+
+def pc_copy_ceiling(mode, src, dst):
+    """Enqueue the bare copy loop (mode 0 ordinary, 1 non-temporal) from src to dst (time it outside)."""
+    _check(lib().pc_copy_ceiling(int(mode), _ptr(src), _ptr(dst), src.numel() * src.element_size(),
+                                 _stream()), "pc_copy_ceiling")
 
 
 def pc_profile_records():

@@ -92,3 +92,41 @@ extern "C" int pc_mfma_ceiling(int mode, int n_cus, int iters, float* scratch,
   *flops = (double)n_cus * 8.0 /* wavefronts */ * 8.0 * iters * 32768.0;
   return PC_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// Copy ceiling: what a bare read-and-write loop sustains, to put the gather's fraction of the
+// HBM peak in context.  Every thread moves 16-byte pieces, four loads in flight, a wavefront
+// covering 1 KiB of consecutive bytes per instruction; mode 0 ordinary loads and stores, mode 1
+// with the non-temporal hint on both sides (the gather's own instructions).
+template <int NT>
+__global__ __launch_bounds__(256) void copy_ceiling_kernel(const u32x4* __restrict__ src,
+                                                           u32x4* __restrict__ dst, long long n) {
+  const long long stride = (long long)gridDim.x * 256;
+  for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < n; i0 += 4 * stride) {
+    u32x4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long i = i0 + u * stride;
+      if (i < n) x[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long i = i0 + u * stride;
+      if (i < n) { if (NT) __builtin_nontemporal_store(x[u], dst + i); else dst[i] = x[u]; }
+    }
+  }
+}
+
+extern "C" int pc_copy_ceiling(int mode, const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst) return PC_ERR_NULL;
+  if (mode < 0 || mode > 1 || bytes < 16 || bytes % 16 != 0 || !pc_aligned(src, 16) || !pc_aligned(dst, 16))
+    return PC_ERR_SHAPE;
+  const long long n = (long long)(bytes / 16);
+  long long blocks = (n + 4 * 256 - 1) / (4 * 256);
+  if (blocks > 8192) blocks = 8192;                       // 32 workgroups per CU, grid-stride beyond
+  hipStream_t st = (hipStream_t)stream;
+  if (mode == 1) hipLaunchKernelGGL(copy_ceiling_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, n);
+  else hipLaunchKernelGGL(copy_ceiling_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, n);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
