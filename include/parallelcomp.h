@@ -253,13 +253,20 @@ int pc_kv_append(const void* k_new, const void* v_new, int32_t batch, int32_t n_
  *     + m of key 4 g + j (j < 4) or 16 + 4 g + (j - 4) (j >= 4) of the block.
  *   k_scale, v_scale [B, S, H_kv] fp32 out.   Pointers 16-byte aligned.  No workspace.
  *   B = 0 or S = 0 is a no-op (pointers are not looked at).
- * pc_parallel_attn_fp8: pc_parallel_attn for few query rows (n_q * H_q / H_kv <= 16, else
- * PC_ERR_UNSUPPORTED) over the 8-bit segments plus, optionally, one 16-bit tail segment (the
- * query block and the generated tokens, grown by pc_kv_append with n_seg = 1):
+ * pc_parallel_attn_fp8: pc_parallel_attn over the 8-bit segments plus, optionally, one 16-bit tail
+ * segment (the query block and the generated tokens, grown by pc_kv_append with n_seg = 1) and,
+ * optionally, the causal self segment of the query rows:
  *   k_tail, v_tail [B, 1, H_kv, tail_cap, D] bf16 rotated, tail_len [B] int32 (device); all
- *     three NULL and tail_cap = 0 for no tail.
- *   out = softmax over { dequantised segments } U { tail rows } exactly as pc_parallel_attn
- *   computes it on the dequantised values code * scale (each is exact in bf16).
+ *     three NULL and tail_cap = 0 for no tail.  Every tail row is visible to every query row.
+ *   k_self, v_self [B, n_q, H_kv, D] bf16 rotated keys / values of the query rows themselves
+ *     (row t sees rows 0..t), both NULL for none: the prefill stage of Eq. 9-11, where the query
+ *     block attends over the compressed cache and, causally, over itself.
+ *   out = softmax over { dequantised segments } U { tail rows } U { self rows <= t } exactly as
+ *   pc_parallel_attn computes it on the dequantised values code * scale.
+ * n_q * H_q / H_kv <= 16 (the decoding stage) runs the split-KV kernel on the 8-bit codes (each
+ * code is exact in bf16; the scales ride on the fp32 logits and probabilities).  More query rows
+ * run the MFMA tile kernel: the segments are first widened to bf16 rows of code * scale (rounded
+ * to bf16) in the workspace, then handled like a 16-bit cache.
  * Other arguments, errors and the workspace rule as pc_parallel_attn. */
 /* One-read quantisation.  pc_kv_quantize_fp8 reads every segment twice (maximum, then codes).
  * pc_gather_kv_amax is pc_gather_kv that also leaves, per destination segment, the largest
@@ -285,13 +292,14 @@ int pc_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg_len,
 int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v8, const float* k_scale,
                          const float* v_scale, const int32_t* seg_len, int32_t seg_len_per_head,
                          const void* k_tail, const void* v_tail, const int32_t* tail_len,
-                         int32_t tail_cap, int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
-                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t q_pos0,
-                         float rope_base, float softmax_scale, void* out, float* lse_out, void* ws,
-                         size_t ws_bytes, void* stream);
+                         int32_t tail_cap, const void* k_self, const void* v_self, int32_t batch,
+                         int32_t n_q, int32_t n_seg, int32_t k_t, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t q_pos0, float rope_base,
+                         float softmax_scale, void* out, float* lse_out, void* ws, size_t ws_bytes,
+                         void* stream);
 size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg, int32_t k_t,
                                             int32_t tail_cap, int32_t n_q_heads, int32_t n_kv_heads,
-                                            int32_t head_dim);
+                                            int32_t head_dim, int32_t has_self);
 
 /* ---- Eq. 9-11 for callers that cannot allocate ----------------------------------------------
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:

@@ -26,8 +26,8 @@ typedef enum pc_kernel_id {
   PC_KERNEL_MERGE = 11, PC_KERNEL_SELF_INFO = 12, PC_KERNEL_KV_APPEND = 13,
   PC_KERNEL_SCORES_LSE = 14, PC_KERNEL_KV_QUANTIZE = 15, PC_KERNEL_DECODE_FP8 = 16,
   PC_KERNEL_PREPASS_SCORES = 17,   /* scores pass 1 fused with the K/V pre-pass */
-  PC_KERNEL_CHUNK_QUEUE = 18,
-  PC_KERNEL_COUNT = 19
+  PC_KERNEL_CHUNK_QUEUE = 18, PC_KERNEL_FP8_TO_ROWS = 19,
+  PC_KERNEL_COUNT = 20
 } pc_kernel_id;
 int         pc_profile_begin(void);
 int         pc_profile_begin_kernel(int kernel_id);   /* as pc_profile_begin, but only the launches of one

@@ -107,10 +107,10 @@ def lib():
     L.pc_kv_append.restype = c_int
     L.pc_kv_quantize_fp8.argtypes = [P, P, P] + [c_int32] * 6 + [P, P, P, P, P]
     L.pc_kv_quantize_fp8.restype = c_int
-    L.pc_parallel_attn_fp8.argtypes = ([P] * 6 + [c_int32] + [P] * 3 + [c_int32] * 9 +
+    L.pc_parallel_attn_fp8.argtypes = ([P] * 6 + [c_int32] + [P] * 3 + [c_int32] + [P] * 2 + [c_int32] * 8 +
                                        [c_float, c_float, P, P, P, c_size_t, P])
     L.pc_parallel_attn_fp8.restype = c_int
-    L.pc_parallel_attn_fp8_workspace_bytes.argtypes = [c_int32] * 8
+    L.pc_parallel_attn_fp8_workspace_bytes.argtypes = [c_int32] * 9
     L.pc_parallel_attn_fp8_workspace_bytes.restype = c_size_t
     _lib = L
     return L
@@ -271,18 +271,20 @@ def pc_kv_quantize_fp8(kc, vc, seg_len, batch, n_seg, k_t, n_kv_heads, head_dim,
                                     _ptr(v_scale), _stream()), "pc_kv_quantize_fp8")
 
 
-def pc_parallel_attn_fp8_workspace_bytes(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim):
+def pc_parallel_attn_fp8_workspace_bytes(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim,
+                                         has_self=False):
     return int(lib().pc_parallel_attn_fp8_workspace_bytes(batch, n_q, n_seg, k_t, tail_cap, n_q_heads,
-                                                          n_kv_heads, head_dim))
+                                                          n_kv_heads, head_dim, int(has_self)))
 
 
 def pc_parallel_attn_fp8(q, k8, v8, k_scale, v_scale, seg_len, k_tail, v_tail, tail_len, tail_cap, batch,
                          n_q, n_seg, k_t, n_q_heads, n_kv_heads, head_dim, q_pos0, rope_base,
-                         softmax_scale, out, lse_out, ws, seg_len_per_head=0):
+                         softmax_scale, out, lse_out, ws, seg_len_per_head=0, k_self=None, v_self=None):
     p, n = _ws(ws)
     _check(lib().pc_parallel_attn_fp8(_ptr(q), _ptr(k8), _ptr(v8), _ptr(k_scale), _ptr(v_scale),
                                       _ptr(seg_len), seg_len_per_head, _ptr(k_tail), _ptr(v_tail),
-                                      _ptr(tail_len), tail_cap, batch, n_q, n_seg, k_t, n_q_heads,
+                                      _ptr(tail_len), tail_cap, _ptr(k_self), _ptr(v_self), batch, n_q,
+                                      n_seg, k_t, n_q_heads,
                                       n_kv_heads, head_dim, q_pos0, rope_base, softmax_scale,
                                       _ptr(out), _ptr(lse_out), p, n, _stream()), "pc_parallel_attn_fp8")
 

@@ -191,6 +191,74 @@ __device__ __forceinline__ void pc_e4m3x4_to_bf16(uint32_t w, uint32_t& lo, uint
   hi = *(const uint32_t*)&b;
 }
 
+// ------------------------------------------------------------------------------------------
+// Widening of 8-bit segments to bf16 rows (for the tile kernel, which takes the query block over
+// the 8-bit cache through the same path as a 16-bit cache): value = code * scale, rounded to bf16.
+// One workgroup per (segment, 32-key block, K or V); a thread takes one 16-byte piece of the block
+// (the layouts are those of kv_quantize_fp8_kernel above).
+__global__ __launch_bounds__(256) void fp8_to_rows_kernel(
+    const uint8_t* __restrict__ k8, const uint8_t* __restrict__ v8, const float* __restrict__ k_scale,
+    const float* __restrict__ v_scale, int k_t, int D, uint16_t* __restrict__ k_rows,
+    uint16_t* __restrict__ v_rows) {
+  const long long seg = blockIdx.x;
+  const int blk = blockIdx.y, is_v = blockIdx.z;
+  const int n_blk = (k_t + 31) / 32;
+  const int p = threadIdx.x;                              // 16-byte piece of the block
+  if (p >= 32 * D / 16) return;
+  const uint8_t* src = (is_v ? v8 : k8) + (seg * n_blk + blk) * 32LL * D + 16 * p;
+  uint16_t* dst = (is_v ? v_rows : k_rows) + seg * (long long)k_t * D;
+  const float scale = (is_v ? v_scale : k_scale)[seg];
+  const uint4 raw = *(const uint4*)src;
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  float f[16];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    uint32_t lo, hi;
+    pc_e4m3x4_to_bf16(w[e], lo, hi);
+    f[4 * e] = bf16_lo_to_f32(lo) * scale; f[4 * e + 1] = bf16_hi_to_f32(lo) * scale;
+    f[4 * e + 2] = bf16_lo_to_f32(hi) * scale; f[4 * e + 3] = bf16_hi_to_f32(hi) * scale;
+  }
+  const int lane = p % 64, piece = p / 64;
+  if (!is_v) {
+    // piece = tile * (D / 64) + i; lane 16 kk + c: values d = 64 i + 16 kk .. + 15 of key c of the tile
+    const int tile = piece / (D / 64), i = piece % (D / 64), kk = lane / 16, c = lane % 16;
+    const int key = 32 * blk + 16 * tile + c;
+    if (key < k_t) {
+      uint32_t o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = pack_bf16x2(f[2 * e], f[2 * e + 1]);
+      uint4* d4 = (uint4*)(dst + (long long)key * D + 64 * i + 16 * kk);
+      d4[0] = make_uint4(o[0], o[1], o[2], o[3]);
+      d4[1] = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+  } else {
+    // piece q; lane 16 g + m holds [h][j]: value d = 32 q + 16 h + m of key 4 g + j (j < 4) or
+    // 16 + 4 g + (j - 4)
+    const int g = lane / 16, m = lane % 16;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = 32 * blk + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4));
+        if (key < k_t) dst[(long long)key * D + 32 * piece + 16 * h + m] = (uint16_t)f32_to_bf16_bits(f[8 * h + j]);
+      }
+  }
+}
+
+int pc_launch_fp8_to_rows(const void* k8, const void* v8, const float* k_scale, const float* v_scale,
+                          long long n_segs, int k_t, int head_dim, void* k_rows, void* v_rows,
+                          hipStream_t st) {
+  if (n_segs == 0) return PC_OK;
+  const int n_blk = (k_t + 31) / 32;
+  if (n_segs > 0x7fffffffLL || n_blk > 65535) return PC_ERR_SHAPE;
+  PcProfScope prof(PC_KERNEL_FP8_TO_ROWS, st);
+  hipLaunchKernelGGL(fp8_to_rows_kernel, dim3((unsigned)n_segs, n_blk, 2), dim3(256), 0, st,
+                     (const uint8_t*)k8, (const uint8_t*)v8, k_scale, v_scale, k_t, head_dim,
+                     (uint16_t*)k_rows, (uint16_t*)v_rows);
+  PC_LAUNCH_CHECK();
+  return PC_OK;
+}
+
 template <int D, int NQ>
 __global__ __launch_bounds__(PC_D8_WAVES * PC_WAVE) void decode_attn_fp8_kernel(PcDecode8Args a) {
   constexpr int KSTEPS = D / 32;            // MFMA k-steps; a lane owns 8 KSTEPS = D / 4 bytes of each of its K rows

@@ -70,7 +70,8 @@ extern "C" const char* pc_kernel_name(int id) {
       "scores_kernel<2>", "chunk_score_kernel", "select_chunks_kernel", "select_tokens_kernel",
       "gather_kv_kernel", "rope_q_kernel", "decode_attn_kernel", "merge_kernel",
       "self_info_rows_kernel", "kv_append_kernel", "scores_lse_kernel", "kv_quantize_fp8_kernel",
-      "decode_attn_fp8_kernel", "scores_kernel<1>+kv_prepass", "chunk_queue_kernel"};
+      "decode_attn_fp8_kernel", "scores_kernel<1>+kv_prepass", "chunk_queue_kernel",
+      "fp8_to_rows_kernel"};
   return (id >= 0 && id < PC_KERNEL_COUNT) ? names[id] : "unknown";
 }
 
@@ -264,21 +265,45 @@ extern "C" int pc_kv_quantize_fp8_amax(const void* kc, const void* vc, const flo
 }
 
 struct Par8Ws {
-  size_t q_rot, part_o, part_lse, total;
-  int n_parts, parts8;
+  size_t q_rot, part_o, part_lse, rows_k, rows_v, k_seg, v_seg, k_tail, v_tail, k_self, v_self, total;
+  int n_parts, parts8, ktp, tcp, nqp;
+  bool small;
 };
 
 static Par8Ws par8_ws_layout(int batch, int n_q, int n_seg, int k_t, int tail_cap, int n_q_heads,
-                             int n_kv_heads, int D) {
+                             int n_kv_heads, int D, int has_self) {
   Par8Ws w;
-  w.parts8 = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
-  w.n_parts = w.parts8;
-  if (tail_cap > 0) w.n_parts += pc_decode_split(tail_cap, 1, (long long)batch * n_kv_heads).n_parts;
+  w.small = (long long)n_q * (n_q_heads / n_kv_heads) <= 16;
+  w.ktp = (k_t + 63) / 64 * 64; w.tcp = (tail_cap + 63) / 64 * 64; w.nqp = (n_q + 63) / 64 * 64;
+  if (w.small) {
+    w.parts8 = pc_decode_split(k_t, n_seg, (long long)batch * n_kv_heads).n_parts;
+    w.n_parts = w.parts8;
+    if (tail_cap > 0) w.n_parts += pc_decode_split(tail_cap, 1, (long long)batch * n_kv_heads).n_parts;
+  } else {           // tile path: one partial per segment, one for the tail, one for the self segment
+    w.parts8 = n_seg;
+    w.n_parts = n_seg + (tail_cap > 0 ? 1 : 0) + (has_self ? 1 : 0);
+  }
   size_t off = 0;
   const size_t rows = (size_t)batch * n_q * n_q_heads;
   w.q_rot = off;    off = pc_align_up(off + rows * D * 2, kAlign);
   w.part_o = off;   off = pc_align_up(off + rows * (size_t)w.n_parts * D * sizeof(float), kAlign);
   w.part_lse = off; off = pc_align_up(off + rows * (size_t)w.n_parts * sizeof(float), kAlign);
+  w.rows_k = w.rows_v = w.k_seg = w.v_seg = w.k_tail = w.v_tail = w.k_self = w.v_self = off;
+  if (!w.small) {
+    // dequantised segments as bf16 rows, then the tile images of segments, tail and self segment
+    const size_t seg_rows = (size_t)batch * n_seg * n_kv_heads * k_t * D * 2;
+    const size_t seg_img = (size_t)batch * n_seg * n_kv_heads * D * w.ktp * 2;
+    const size_t tail_img = (size_t)batch * n_kv_heads * D * w.tcp * 2;
+    const size_t self_img = has_self ? (size_t)batch * n_kv_heads * D * w.nqp * 2 : 0;
+    w.rows_k = off; off = pc_align_up(off + seg_rows, kAlign);
+    w.rows_v = off; off = pc_align_up(off + seg_rows, kAlign);
+    w.k_seg = off;  off = pc_align_up(off + seg_img, kAlign);
+    w.v_seg = off;  off = pc_align_up(off + seg_img, kAlign);
+    w.k_tail = off; off = pc_align_up(off + tail_img, kAlign);
+    w.v_tail = off; off = pc_align_up(off + tail_img, kAlign);
+    w.k_self = off; off = pc_align_up(off + self_img, kAlign);
+    w.v_self = off; off = pc_align_up(off + self_img, kAlign);
+  }
   w.total = off;
   return w;
 }
@@ -288,27 +313,37 @@ static int check_par8(int batch, int n_q, int n_seg, int k_t, int tail_cap, int 
   if (batch < 1 || n_q < 1 || n_seg < 0 || k_t < 1 || tail_cap < 0) return PC_ERR_SHAPE;
   if (n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % n_kv_heads != 0) return PC_ERR_SHAPE;
   if (D != 64 && D != 128) return PC_ERR_SHAPE;
-  if (k_t > (1 << 24) || tail_cap > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20)) return PC_ERR_SHAPE;
-  if (n_seg == 0 && tail_cap == 0) return PC_ERR_SHAPE;
-  if ((long long)batch * ((long long)n_seg + 1) * n_kv_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
+  if (k_t > (1 << 24) || tail_cap > (1 << 24) || n_seg > (1 << 20) || batch > (1 << 20) || n_q > (1 << 20))
+    return PC_ERR_SHAPE;
+  const long long parts = (long long)n_seg + 2;
+  if ((long long)batch * parts * n_kv_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
+  if ((long long)batch * parts * n_q_heads * ((n_q + 127) / 128) > 0x7fffffffLL / 8) return PC_ERR_SHAPE;
   if ((long long)batch * n_q * n_q_heads > 0x7fffffffLL / 64) return PC_ERR_SHAPE;
-  if ((long long)n_q * (n_q_heads / n_kv_heads) > 16) return PC_ERR_UNSUPPORTED;
   return PC_OK;
 }
+
+static int parallel_attn_fp8_tiles(const void* q, const void* k8, const void* v8, const float* k_scale,
+                                   const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
+                                   const void* k_tail, const void* v_tail, const int32_t* tail_len,
+                                   int tail_cap, const void* k_self, const void* v_self, int batch,
+                                   int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads, int D,
+                                   int q_pos0, float rope_base, float scale, void* out, float* lse_out,
+                                   const Par8Ws& w, char* base, hipStream_t st);
 
 extern "C" size_t pc_parallel_attn_fp8_workspace_bytes(int32_t batch, int32_t n_q, int32_t n_seg,
                                                        int32_t k_t, int32_t tail_cap,
                                                        int32_t n_q_heads, int32_t n_kv_heads,
-                                                       int32_t head_dim) {
+                                                       int32_t head_dim, int32_t has_self) {
   if (check_par8(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim) != PC_OK) return 0;
-  return par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim).total;
+  return par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, head_dim, has_self).total;
 }
 
 extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v8,
                                     const float* k_scale, const float* v_scale,
                                     const int32_t* seg_len, int32_t seg_len_per_head,
                                     const void* k_tail, const void* v_tail, const int32_t* tail_len,
-                                    int32_t tail_cap, int32_t batch, int32_t n_q, int32_t n_seg,
+                                    int32_t tail_cap, const void* k_self, const void* v_self,
+                                    int32_t batch, int32_t n_q, int32_t n_seg,
                                     int32_t k_t, int32_t n_q_heads, int32_t n_kv_heads,
                                     int32_t head_dim, int32_t q_pos0, float rope_base,
                                     float softmax_scale, void* out, float* lse_out, void* ws,
@@ -318,18 +353,26 @@ extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v
   if (!q || !out) return PC_ERR_NULL;
   if (n_seg > 0 && (!k8 || !v8 || !k_scale || !v_scale)) return PC_ERR_NULL;
   if (tail_cap > 0 && (!k_tail || !v_tail || !tail_len)) return PC_ERR_NULL;
+  if ((k_self == nullptr) != (v_self == nullptr)) return PC_ERR_NULL;
+  const int has_self = k_self != nullptr;
+  if (n_seg == 0 && tail_cap == 0 && !has_self) return PC_ERR_SHAPE;
   if (seg_len_per_head != 0 && seg_len_per_head != 1) return PC_ERR_SHAPE;
   if (q_pos0 >= 0 && (!(rope_base > 1.0f) || !isfinite(rope_base))) return PC_ERR_SHAPE;
   if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return PC_ERR_SHAPE;
   if (n_seg > 0 && (!pc_aligned(k8, 16) || !pc_aligned(v8, 16))) return PC_ERR_SHAPE;
-  if (!pc_aligned(q, 16) || !pc_aligned(out, 16) || !pc_aligned(k_tail, 16) || !pc_aligned(v_tail, 16))
+  if (!pc_aligned(q, 16) || !pc_aligned(out, 16) || !pc_aligned(k_tail, 16) || !pc_aligned(v_tail, 16) ||
+      !pc_aligned(k_self, 16) || !pc_aligned(v_self, 16))
     return PC_ERR_SHAPE;
   const int D = head_dim;
-  const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, D);
+  const Par8Ws w = par8_ws_layout(batch, n_q, n_seg, k_t, tail_cap, n_q_heads, n_kv_heads, D, has_self);
   if (!ws || !pc_aligned(ws, kAlign) || ws_bytes < w.total) return PC_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   char* base = (char*)ws;
   const float scale = eff_scale(softmax_scale, D);
+  if (!w.small)
+    return parallel_attn_fp8_tiles(q, k8, v8, k_scale, v_scale, seg_len, seg_len_per_head, k_tail, v_tail,
+                                   tail_len, tail_cap, k_self, v_self, batch, n_q, n_seg, k_t, n_q_heads,
+                                   n_kv_heads, D, q_pos0, rope_base, scale, out, lse_out, w, base, st);
   const void* q_rot = q;
   if (q_pos0 >= 0) {
     rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
@@ -350,7 +393,8 @@ extern "C" int pc_parallel_attn_fp8(const void* q, const void* k8, const void* v
                           n_kv_heads, D, scale, part_o, part_lse, w.n_parts, w.parts8, st);
     if (rc != PC_OK) return rc;
   }
-  return pc_launch_merge(part_o, part_lse, q_rot, nullptr, nullptr, out, lse_out, batch, n_q,
+  // the few-row causal self segment (if any) is evaluated inside the merge
+  return pc_launch_merge(part_o, part_lse, q_rot, k_self, v_self, out, lse_out, batch, n_q,
                          n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
 }
 
@@ -589,6 +633,67 @@ static int parallel_attn_run(const void* q, const void* kc, const void* vc, cons
   }
   return pc_launch_merge(part_o, part_lse, q_rot, nullptr, nullptr, out, lse_out, batch, n_q,
                          n_q_heads, n_kv_heads, D, w.n_parts, scale, st);
+}
+
+// Eq. 9-11 for a block of query rows over the 8-bit cache: the segments are widened to bf16 rows
+// (code * scale, rounded to bf16) in the workspace, then everything runs through the tile kernel
+// as for a 16-bit cache: one partial per segment, one for the 16-bit tail (all its rows
+// visible), one for the causal self segment, merged by logsumexp.
+static int parallel_attn_fp8_tiles(const void* q, const void* k8, const void* v8, const float* k_scale,
+                                   const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
+                                   const void* k_tail, const void* v_tail, const int32_t* tail_len,
+                                   int tail_cap, const void* k_self, const void* v_self, int batch,
+                                   int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads, int D,
+                                   int q_pos0, float rope_base, float scale, void* out, float* lse_out,
+                                   const Par8Ws& w, char* base, hipStream_t st) {
+  int rc = pc_launch_rope_q(q, base + w.q_rot, (long long)batch * n_q * n_q_heads, n_q, n_q_heads, D,
+                            q_pos0, rope_base, scale * 1.4426950408889634f, st);
+  if (rc != PC_OK) return rc;
+  PcFlashArgs a = {};
+  a.q = base + w.q_rot; a.table = nullptr; a.o = nullptr; a.lse = nullptr;
+  a.part_o = (float*)(base + w.part_o); a.part_lse = (float*)(base + w.part_lse);
+  a.n_seq = batch; a.n_rows = n_q; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
+  a.head_dim = D; a.n_parts_total = w.n_parts; a.q_pos0 = 0; a.scale = scale;
+  int part0 = 0;
+  // groups of segments [batch, n, H_kv, cap, D] (bf16 rows): images, then one partial each
+  auto segment_group = [&](const void* kc, const void* vc, const int32_t* len, int per_head, int n,
+                           int cap, int capp, void* k_img, void* v_img) -> int {
+    int r = pc_launch_kv_prepass(kc, vc, nullptr, nullptr, k_img, v_img, batch * n * n_kv_heads, cap, capp,
+                                 1, D, st);
+    if (r != PC_OK) return r;
+    a.k_img = k_img; a.v_img = v_img; a.part_len = len; a.part_len_per_head = per_head;
+    a.img_seq_stride = (long long)n * n_kv_heads * (capp / 64);
+    a.img_part_stride = (long long)n_kv_heads * (capp / 64);
+    a.img_head_stride = capp / 64;
+    a.n_keys = cap; a.n_parts_grid = n; a.part0 = part0; a.causal_offset = PC_NO_CAUSAL;
+    part0 += n;
+    return pc_launch_flash(a, st);
+  };
+  if (n_seg > 0) {
+    rc = pc_launch_fp8_to_rows(k8, v8, k_scale, v_scale, (long long)batch * n_seg * n_kv_heads, k_t, D,
+                               base + w.rows_k, base + w.rows_v, st);
+    if (rc != PC_OK) return rc;
+    rc = segment_group(base + w.rows_k, base + w.rows_v, seg_len, seg_len_per_head, n_seg, k_t, w.ktp,
+                       base + w.k_seg, base + w.v_seg);
+    if (rc != PC_OK) return rc;
+  }
+  if (tail_cap > 0) {
+    rc = segment_group(k_tail, v_tail, tail_len, 0, 1, tail_cap, w.tcp, base + w.k_tail, base + w.v_tail);
+    if (rc != PC_OK) return rc;
+  }
+  if (k_self != nullptr) {
+    rc = pc_launch_kv_prepass(k_self, v_self, nullptr, nullptr, base + w.k_self, base + w.v_self, batch, n_q,
+                              w.nqp, n_kv_heads, D, st);
+    if (rc != PC_OK) return rc;
+    a.k_img = base + w.k_self; a.v_img = base + w.v_self; a.part_len = nullptr; a.part_len_per_head = 0;
+    a.img_seq_stride = (long long)n_kv_heads * (w.nqp / 64); a.img_part_stride = 0;
+    a.img_head_stride = w.nqp / 64;
+    a.n_keys = n_q; a.n_parts_grid = 1; a.part0 = part0; a.causal_offset = 0;
+    rc = pc_launch_flash(a, st);
+    if (rc != PC_OK) return rc;
+  }
+  return pc_launch_merge(a.part_o, a.part_lse, a.q, nullptr, nullptr, out, lse_out, batch, n_q, n_q_heads,
+                         n_kv_heads, D, w.n_parts, scale, st);
 }
 
 extern "C" int pc_parallel_attn(const void* q, const void* kc, const void* vc, const int32_t* seg_len,

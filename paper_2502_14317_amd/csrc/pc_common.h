@@ -270,6 +270,11 @@ int pc_launch_kv_quantize_fp8(const void* kc, const void* vc, const int32_t* seg
                               int seg_len_per_head, long long n_segs, int n_kv_heads, int k_t,
                               int head_dim, const float* k_amax, const float* v_amax, void* k8,
                               void* v8, float* k_scale, float* v_scale, hipStream_t st);
+// 8-bit segments (32-key block layout of pc_kv_quantize_fp8) -> bf16 rows [n_segs, k_t, D] of
+// code * scale (rounded to bf16), K and V
+int pc_launch_fp8_to_rows(const void* k8, const void* v8, const float* k_scale, const float* v_scale,
+                          long long n_segs, int k_t, int head_dim, void* k_rows, void* v_rows,
+                          hipStream_t st);
 int pc_launch_decode_fp8(const void* q_rot, const void* k8, const void* v8, const float* k_scale,
                          const float* v_scale, const int32_t* seg_len, int seg_len_per_head,
                          int batch, int n_q, int n_seg, int k_t, int n_q_heads, int n_kv_heads,

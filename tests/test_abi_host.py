@@ -135,17 +135,21 @@ def test_null_and_shape_errors_before_any_gpu_work():
     assert L.pc_kv_quantize_fp8(one, one, None, 2, 2, 3, 64, 2, 128, one, one, one, one, None) == -2
     assert L.pc_kv_quantize_fp8(one, one, None, 0, 0, 3, 64, 2, 128, one, one, one, one, None) == 0   # empty batch
     pa = (0, 1, 1, 2, 64, 8, 2, 128, -1)            # tail_cap, batch, n_q, n_seg, k_t, H_q, H_kv, D, q_pos0
-    call = lambda q, k8, tail, args, wsb: L.pc_parallel_attn_fp8(q, k8, one, one, one, None, 0, tail, tail, tail,
-                                                                 *args, 1e4, 0.0, one, None, one, wsb, None)
+    call = lambda q, k8, tail, args, wsb, kself=None, vself=None: L.pc_parallel_attn_fp8(
+        q, k8, one, one, one, None, 0, tail, tail, tail, args[0], kself, vself, *args[1:], 1e4, 0.0, one, None,
+        one, wsb, None)
     assert call(None, one, None, pa, 1 << 30) == -1
     assert call(one, None, None, pa, 1 << 30) == -1
     assert call(one, one, None, pa, 8) == -3
     assert call(one, one, None, (16,) + pa[1:], 1 << 30) == -1                  # tail_cap > 0 without a tail
-    assert call(one, one, None, (0, 1, 5, 2, 64, 8, 2, 128, -1), 1 << 30) == -5  # 20 query columns
+    assert call(one, one, None, (0, 1, 5, 2, 64, 8, 2, 128, -1), 8) == -3        # 20 query columns: the tile path
     assert call(one, one, None, (0, 1, 1, 0, 64, 8, 2, 128, -1), 1 << 30) == -2  # nothing to attend to
-    assert pc.pc_parallel_attn_fp8_workspace_bytes(1, 5, 2, 64, 0, 8, 2, 128) == 0
+    assert call(one, one, None, pa, 1 << 30, kself=one) == -1                   # k_self without v_self
     a8 = pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 0, 8, 2, 128)
     assert 0 < a8 < pc.pc_parallel_attn_fp8_workspace_bytes(1, 1, 2, 4096, 512, 8, 2, 128)
+    # a query block widens the segments into the workspace: much larger, larger still with a self segment
+    t8 = pc.pc_parallel_attn_fp8_workspace_bytes(1, 64, 2, 4096, 0, 8, 2, 128)
+    assert a8 < t8 < pc.pc_parallel_attn_fp8_workspace_bytes(1, 64, 2, 4096, 0, 8, 2, 128, True)
 
 
 def test_workspace_sizes_are_positive_and_monotone():

@@ -77,8 +77,8 @@ def test_quantize_random_segments_bit_exact(D, per_head):
         np.testing.assert_array_equal(fp8_rows_view("v", v8[b], kt, D).cpu().numpy(), rv8)
 
 
-def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed):
-    _say(f"fp8 attention {name}: B={B} n_q={n_q} S={S} kt={kt} H={Hq}/{Hkv} D={D} tail={tail_cap} ragged={ragged}")
+def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed, with_self=False):
+    _say(f"fp8 attention {name}: B={B} n_q={n_q} S={S} kt={kt} H={Hq}/{Hkv} D={D} tail={tail_cap} ragged={ragged} self={with_self}")
     r = np.random.default_rng([52, seed])
     q = _mk(r, (B, n_q, Hq, D), 3.0)
     kc, vc = _mk(r, (B, S, Hkv, kt, D)), _mk(r, (B, S, Hkv, kt, D))
@@ -90,13 +90,18 @@ def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed):
     if tail_cap:
         kt_bits, vt_bits = _mk(r, (B, 1, Hkv, tail_cap, D)), _mk(r, (B, 1, Hkv, tail_cap, D))
         tl = r.integers(1, tail_cap + 1, size=(B,)).astype(np.int32)
-    out = torch.empty((B, n_q, Hq, D), dtype=torch.bfloat16, device="cuda")
-    lse = torch.empty((B, Hq, n_q), dtype=torch.float32, device="cuda")
-    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, n_q, S, kt, tail_cap, Hq, Hkv, D))
+    ks_bits = vs_bits = None
+    if with_self:
+        ks_bits, vs_bits = _mk(r, (B, n_q, Hkv, D)), _mk(r, (B, n_q, Hkv, D))
+    out = torch.full((B, n_q, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, Hq, n_q), float("nan"), dtype=torch.float32, device="cuda")
+    ws = pc.alloc_workspace(pc.pc_parallel_attn_fp8_workspace_bytes(B, n_q, S, kt, tail_cap, Hq, Hkv, D, with_self))
     pc.pc_parallel_attn_fp8(bits_to_dev(q), k8, v8, ks, vs, None if sl is None else torch.from_numpy(sl).cuda(),
                             bits_to_dev(kt_bits) if tail_cap else None, bits_to_dev(vt_bits) if tail_cap else None,
                             torch.from_numpy(tl).cuda() if tail_cap else None, tail_cap, B, n_q, S, kt, Hq, Hkv, D,
-                            q_pos0, 1.0e4, 0.0, out, lse, ws)
+                            q_pos0, 1.0e4, 0.0, out, lse, ws,
+                            k_self=bits_to_dev(ks_bits) if with_self else None,
+                            v_self=bits_to_dev(vs_bits) if with_self else None)
     torch.cuda.synchronize()
     for b in range(B):
         # the oracle quantises on its own (bit-equal to the GPU's codes, tested above) and attends
@@ -114,7 +119,9 @@ def _attn_case(name, B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed):
         qf = bf16_bits_to_f64(q[b])
         if q_pos0 >= 0:
             qf = oracle.rope(qf, q_pos0 + np.arange(n_q), 1.0e4)
-        ro, rl = oracle.global_attention_concat(qf, kd, vd, seg_len=seg_len)
+        ro, rl = oracle.global_attention_concat(qf, kd, vd, seg_len=seg_len,
+                                                k_self=bf16_bits_to_f64(ks_bits[b]) if with_self else None,
+                                                v_self=bf16_bits_to_f64(vs_bits[b]) if with_self else None)
         assert_close(dev_bf16_to_f64(out[b]), ro, O_ATOL, O_RTOL, f"{name} out[b={b}]")
         assert_close(lse[b].cpu().numpy().T, rl, LSE_ATOL, 1e-3, f"{name} lse[b={b}]")
 
@@ -205,12 +212,17 @@ def test_fp8_attention_more_segments_than_lanes():
     _attn_case("150-segments", 2, 1, 150, 40, 8, 2, 128, 24, -1, True, 9)
 
 
-def test_fp8_attention_rejects_many_query_columns():
-    one = torch.zeros(4096, dtype=torch.uint8, device="cuda")
-    with pytest.raises(pc.PcError) as e:
-        pc.pc_parallel_attn_fp8(one, one, one, one, one, None, None, None, None, 0, 1, 5, 1, 64, 32, 8, 128,
-                                -1, 1.0e4, 0.0, one, None, one)
-    assert e.value.status == -5                             # PC_ERR_UNSUPPORTED
+def test_fp8_attention_query_block_over_the_8bit_cache():
+    """The prefill stage of Eq. 9-11 over the 8-bit cache: a block of query rows (more than the 16
+    columns of the split-KV kernel: the MFMA tile path on widened segments) attends over the
+    dequantised segments, a 16-bit tail whose rows are all visible, and causally over itself."""
+    _attn_case("block-self", 1, 104, 3, 200, 8, 2, 128, 0, 600, False, 11, with_self=True)
+    _attn_case("block-tail-self-ragged64", 2, 70, 2, 130, 4, 4, 64, 45, -1, True, 12, with_self=True)
+    _attn_case("block-noself", 1, 40, 2, 64, 8, 8, 128, 0, -1, True, 13)
+    _attn_case("block-self-only", 1, 33, 0, 64, 8, 2, 128, 0, 5, False, 14, with_self=True)
+    # few rows with a causal self segment: the split-KV kernel, self segment inside the merge
+    _attn_case("nq3-self", 2, 3, 3, 300, 8, 2, 128, 0, 9, True, 15, with_self=True)
+    _attn_case("nq2-tail-self", 1, 2, 2, 97, 4, 1, 64, 20, -1, False, 16, with_self=True)
 
 
 def test_fp8_decode_full_size_sampled():
