@@ -604,6 +604,9 @@ def main():
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time only the chunk prefill + score reduction (the stress config's step)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="run only the warm-up and the timed steps of the workload (for a profiler: every "
+                         "launch of a kernel in the trace is then a launch of the timed step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times: the reference the "
                          "FETCH_SIZE / WRITE_SIZE counters are scaled against")
@@ -693,6 +696,9 @@ def main():
                      "algorithmic_flops": flops, "traffic": MEASURED_TRAFFIC.get(("flash_fwd_kernel", cfg.name))},
         "kernel_ms_per_step": breakdown,
     }
+    if args.step_only:
+        print(json.dumps(result), flush=True)
+        return
     # the same step recorded once into a HIP graph and replayed (no per-launch host work)
     gr = torch.cuda.CUDAGraph()
     with torch.cuda.graph(gr):
