@@ -127,8 +127,9 @@ static PrefillWs prefill_ws_layout(const pc_shape* s) {
 extern "C" size_t pc_chunk_prefill_workspace_bytes(const pc_shape* s) {
   if (check_shape(s) != PC_OK) return 0;
   pc_shape t = *s;
-  if (t.obs_window < 1) t.obs_window = 1;                  // a call without scores ignores the window
-  if (t.obs_window > t.chunk_len + t.query_len) return 0;
+  // a call without scores ignores the window: size for any window the call could accept
+  if (t.obs_window < 1) t.obs_window = 1;
+  if (t.obs_window > t.chunk_len + t.query_len) t.obs_window = t.chunk_len + t.query_len;
   return prefill_ws_layout(&t).total;
 }
 
