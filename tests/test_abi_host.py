@@ -161,3 +161,22 @@ def test_workspace_sizes_are_positive_and_monotone():
     b = pc.pc_parallel_attn_workspace_bytes(2, 1, 4, 256, 8, 2, 128, 0)
     assert 0 < a < b
     assert pc.pc_parallel_attn_workspace_bytes(1, 64, 4, 256, 8, 2, 128, 1) > a
+
+
+def test_header_compiles_as_c_and_links_from_a_c_program(tmp_path):
+    """The boundary is a C ABI: a plain C program (gcc, -std=c99 -pedantic) includes both headers,
+    links against the library and gets status codes for bad arguments, all without a GPU."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = os.path.join(ROOT, "tests", "c_abi", "host_check.c")
+    exe = str(tmp_path / "host_check")
+    lib_dir = os.path.join(ROOT, "paper_2502_14317_amd")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), src,
+                    "-o", exe, "-L", lib_dir, "-l:libparallelcomp.so", "-Wl,-rpath," + lib_dir,
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "c abi ok" in out.stdout
