@@ -337,14 +337,37 @@ def test_layer_keeping_everything_is_one_softmax_over_all_chunks():
     assert_close(layer.global_lse[0].cpu().numpy().T, lg, LSE_ATOL, 1e-3, "global_lse")
 
 
-@pytest.mark.parametrize("C,w,wq,Hq,Hkv,D,w_obs,kc_n,kt_n,gain", [(1, 1, 1, 1, 1, 64, 1, 1, 1, 1.0),
-                                                                  (3, 65, 3, 2, 1, 128, 2, 2, 64, 1.0),
-                                                                  (2, 127, 130, 4, 4, 64, 64, 1, 127, 1.0),
-                                                                  (2, 700, 40, 8, 2, 128, 32, 1, 256, 1.25)],
-                         ids=["one-token", "just-over-a-tile", "long-query", "wider-logits"])
+def _drawn_shapes(n):
+    """n layer shapes drawn from a fixed seed: chunk and query lengths that are no multiple of any
+    tile, every group size 1 to 8, both head dimensions, voting windows from one row to more than
+    the query block, and keep counts from 1 to everything."""
+    r = np.random.default_rng([2502, 99])
+    out = []
+    for _ in range(n):
+        D = int(r.choice([64, 128]))
+        Hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 4, 8]))
+        C = int(r.integers(1, 5))
+        w = int(r.integers(1, 420))
+        wq = int(r.integers(1, 150))
+        w_obs = int(r.integers(1, w + wq + 1))
+        out.append((C, w, wq, Hkv * G, Hkv, D, w_obs, int(r.integers(1, C + 1)), int(r.integers(1, w + 1)),
+                    float(r.choice([1.0, 1.25]))))
+    return out
+
+
+_FIXED_SHAPES = [(1, 1, 1, 1, 1, 64, 1, 1, 1, 1.0), (3, 65, 3, 2, 1, 128, 2, 2, 64, 1.0),
+                 (2, 127, 130, 4, 4, 64, 64, 1, 127, 1.0), (2, 700, 40, 8, 2, 128, 32, 1, 256, 1.25)]
+_DRAWN_SHAPES = _drawn_shapes(10)
+
+
+@pytest.mark.parametrize("C,w,wq,Hq,Hkv,D,w_obs,kc_n,kt_n,gain", _FIXED_SHAPES + _DRAWN_SHAPES,
+                         ids=["one-token", "just-over-a-tile", "long-query", "wider-logits"]
+                         + ["drawn-" + "x".join(str(x) for x in sh[:9]) for sh in _DRAWN_SHAPES])
 def test_layer_tiny_and_ragged_tail_shapes(C, w, wq, Hq, Hkv, D, w_obs, kc_n, kt_n, gain):
-    """Smallest possible shapes and sizes just past a tile boundary, unit-variance entries; the
-    last case has logits with a standard deviation of 1.6 (q and k entries x 1.25)."""
+    """Smallest possible shapes, sizes just past a tile boundary and ten shapes drawn from a fixed
+    seed, unit-variance entries; where the gain is 1.25 the logits have a standard deviation of
+    1.6 (q and k entries x 1.25)."""
     _say(f"tiny layer C={C} w={w} wq={wq} H={Hq}/{Hkv} D={D} gain={gain}")
     r = np.random.default_rng([16, C, w, wq])
     L = w + wq
