@@ -176,6 +176,29 @@ def test_parallel_attn_decode_ragged_self_rope():
     _parallel_attn_case("decode-self-only", 1, 3, 0, 64, 4, 2, 64, True, -1, False, 5)
 
 
+def _drawn_attn_cases(n):
+    r = np.random.default_rng([2502, 98])
+    out = []
+    for i in range(n):
+        D = int(r.choice([64, 128]))
+        Hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 4, 8]))
+        n_q = int(r.choice([1, 2, 3, 5, 17, 70, 131]))
+        with_self = bool(r.integers(0, 2))
+        S = int(r.integers(0 if with_self else 1, 6))
+        out.append((int(r.integers(1, 4)), n_q, S, int(r.integers(1, 300)), Hkv * G, Hkv, D, with_self,
+                    int(r.choice([-1, 0, 777])), bool(r.integers(0, 2)) and S > 0, 100 + i))
+    return out
+
+
+@pytest.mark.parametrize("case", _drawn_attn_cases(12), ids=lambda c: "x".join(str(int(x)) for x in c[:10]))
+def test_parallel_attn_drawn_shapes(case):
+    """Twelve calls drawn from a fixed seed: the single-row path (n_q * G <= 16) and the tile path,
+    with and without the causal self segment, rotated or not, ragged or full segments."""
+    B, n_q, S, kt, Hq, Hkv, D, with_self, q_pos0, ragged, seed = case
+    _parallel_attn_case("drawn", B, n_q, S, kt, Hq, Hkv, D, with_self, q_pos0, ragged, seed)
+
+
 def test_parallel_attn_decode_many_ragged_groups():
     """Enough (sequence, KV head, segment) groups that a workgroup takes several consecutive
     segments, with ragged lengths (empty segments in the middle and at the end of a group)."""
