@@ -225,6 +225,30 @@ def test_fp8_attention_query_block_over_the_8bit_cache():
     _attn_case("nq2-tail-self", 1, 2, 2, 97, 4, 1, 64, 20, -1, False, 16, with_self=True)
 
 
+def _drawn_fp8_cases(n):
+    r = np.random.default_rng([2502, 97])
+    out = []
+    for i in range(n):
+        D = int(r.choice([64, 128]))
+        Hkv = int(r.choice([1, 2, 3]))
+        G = int(r.choice([1, 2, 4, 8]))
+        n_q = int(r.choice([1, 2, 3, 5, 17, 70]))
+        with_self = bool(r.integers(0, 2))
+        tail_cap = int(r.choice([0, 1, 33, 90]))
+        S = int(r.integers(0 if (with_self or tail_cap) else 1, 5))
+        out.append((int(r.integers(1, 4)), n_q, S, int(r.integers(1, 300)), Hkv * G, Hkv, D, tail_cap,
+                    int(r.choice([-1, 0, 777])), bool(r.integers(0, 2)) and S > 0, 200 + i, with_self))
+    return out
+
+
+@pytest.mark.parametrize("case", _drawn_fp8_cases(12), ids=lambda c: "x".join(str(int(x)) for x in c[:10]) + f"x{int(c[11])}")
+def test_fp8_attention_drawn_shapes(case):
+    """Twelve calls over the 8-bit cache drawn from a fixed seed: the split-KV path and the tile
+    path, with and without a 16-bit tail and a causal self segment, ragged or full segments."""
+    B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed, with_self = case
+    _attn_case("drawn", B, n_q, S, kt, Hq, Hkv, D, tail_cap, q_pos0, ragged, seed, with_self=with_self)
+
+
 def test_fp8_decode_full_size_sampled():
     """The decode config (16 sequences x 32 segments x 2048 rows x 8 KV heads) in 8 bits: sampled
     (sequence, KV group) pairs against the oracle on its own codes, and the codes themselves on
