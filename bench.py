@@ -278,7 +278,7 @@ def bench_ceilings(pc, torch):
     return out
 
 
-def cpu_baseline(cfg, q, k, v, n_rows_sample=768, n_grows_sample=128):
+def cpu_baseline(cfg, q, k, v, n_rows_sample=8192, n_grows_sample=512):
     """Time the oracle (as it stands) on a bounded sample and scale to the whole step.
 
     Sample: chunk 0 only; local attention on n_rows_sample evenly spaced rows (each row costs
@@ -295,6 +295,7 @@ def cpu_baseline(cfg, q, k, v, n_rows_sample=768, n_grows_sample=128):
     except Exception:
         cores = os.cpu_count() or 1
     L, w = cfg.seq_len, cfg.chunk_len
+    n_rows_sample, n_grows_sample = min(n_rows_sample, L), min(n_grows_sample, cfg.query_len)
     qf, kf, vf = bf16_bits_to_f64(q[0]), bf16_bits_to_f64(k[0]), bf16_bits_to_f64(v[0])
     pos = np.arange(L)
     t0 = time.perf_counter()
